@@ -1,0 +1,144 @@
+"""CPU oracle for the AB-training hot path (arxiv 2405.01067).  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, fp64 NumPy statement of what the factored-layer training step and the merge
+compute, written from the paper.  It shares no code with the HIP library and must never be
+imported by the product path: only tests, the smoke check and the bench's `cpu_baseline`
+leg may use it.
+
+Notation follows the paper's Eq. 3: a layer weight W (m x n, out x in) is carried as
+W = A B with A = U_k Sigma_k^(1/2) (m x k) and B = Sigma_k^(1/2) V_k^T (k x n).
+The layer acts as y = x W^T, so for a batch X (M x n):  T = X B^T (M x k),  Y = T A^T (M x m).
+
+Pins (tests/test_oracle_pins.py): every function below is checked against closed forms,
+finite differences, planted spectra, brute-force Jacobi on tiny matrices and invariants.
+Nothing here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+_F64 = np.float64
+
+
+def _f64(x):
+    return np.asarray(x, dtype=_F64)
+
+
+# --------------------------------------------------------------------------------------
+# factored layer: forward and backward (Eq. 3 and the chain rule through it)
+# --------------------------------------------------------------------------------------
+
+def lr_linear_fwd(X, A, B):
+    """Forward of a layer whose weight is W = A B (Eq. 3): T = X B^T, Y = T A^T.
+
+    No intermediate rounding.  Returns (Y, T) in fp64."""
+    X, A, B = _f64(X), _f64(A), _f64(B)
+    T = X @ B.T
+    Y = T @ A.T
+    return Y, T
+
+
+def lr_linear_bwd(dY, X, A, B):
+    """Backward of the same layer for a loss L with dL/dY = dY (chain rule on Eq. 3; the
+    group phase of Algorithm 1 trains A or B, so both factor gradients are defined):
+
+        dT = dY A,   dA = dY^T T,   dB = dT^T X,   dX = dT B.
+
+    Returns (dX, dA, dB, dT) in fp64."""
+    dY, X, A, B = _f64(dY), _f64(X), _f64(A), _f64(B)
+    T = X @ B.T
+    dT = dY @ A
+    dA = dY.T @ T
+    dB = dT.T @ X
+    dX = dT @ B
+    return dX, dA, dB, dT
+
+
+# --------------------------------------------------------------------------------------
+# SVD, rank rule, AB decomposition (Sec. "Methodology", Eq. 3)
+# --------------------------------------------------------------------------------------
+
+def svd(W):
+    """Full thin SVD W = U diag(s) V^T in fp64, s descending.  LAPACK (numpy.linalg.svd) is
+    the library step; a wide matrix (n > m) is transposed first, as the paper prescribes
+    for unfavourable shapes, and the bases are swapped back."""
+    W = _f64(W)
+    m, n = W.shape
+    if n > m:
+        U, s, Vt = np.linalg.svd(W.T, full_matrices=False)
+        return Vt.T, s, U.T
+    U, s, Vt = np.linalg.svd(W, full_matrices=False)
+    return U, s, Vt
+
+
+def select_rank(s, tau):
+    """Rank rule of the AB decomposition: singular values smaller than sigmaCutoff times the
+    largest one are removed, i.e. keep sigma_i iff sigma_i >= tau * sigma_1.  The comparison
+    is taken in fp32 (the precision the library stores sigma in).  At least one is kept."""
+    s32 = np.asarray(s, dtype=np.float32)
+    if s32.size == 0:
+        return 0
+    cut = np.float32(tau) * s32[0]
+    return max(1, int(np.count_nonzero(s32 >= cut)))
+
+
+def ab_decomposition(W, tau=None, k=None):
+    """Eq. 3: A = U_k Sigma_k^(1/2), B = Sigma_k^(1/2) V_k^T from the SVD of W; k given, or
+    chosen by the rank rule with threshold tau.  Returns (A, B, s, k) with s the full
+    descending spectrum."""
+    U, s, Vt = svd(W)
+    if k is None:
+        k = select_rank(s, tau)
+    k = int(k)
+    root = np.sqrt(s[:k])
+    A = U[:, :k] * root[None, :]
+    B = root[:, None] * Vt[:k, :]
+    return A, B, s, k
+
+
+# --------------------------------------------------------------------------------------
+# merge (Algorithm 1: all-reduce of A and of B over all workers, then W <- A B; followed by
+# the re-decomposition with the rank rule)
+# --------------------------------------------------------------------------------------
+
+def merged_matrix(A_copies, B_copies, mode=0):
+    """The merged dense weight.
+    mode 0 (the paper): average A and B separately over the copies, then W = A_mean B_mean.
+    mode 1 (mean of reconstructions): W = (1/G) sum_g A_g B_g."""
+    G = len(A_copies)
+    assert G == len(B_copies) and G >= 1
+    if mode == 0:
+        A_mean = sum(_f64(a) for a in A_copies) / G
+        B_mean = sum(_f64(b) for b in B_copies) / G
+        return A_mean @ B_mean
+    if mode == 1:
+        return sum(_f64(a) @ _f64(b) for a, b in zip(A_copies, B_copies)) / G
+    raise ValueError("mode must be 0 or 1")
+
+
+def ab_merge(A_copies, B_copies, tau, k_fixed=0, mode=0):
+    """Merge G group copies of the factors and re-factorise the result.
+
+    Returns a dict: W (merged dense matrix, m x n), s (its full descending spectrum),
+    k (selected rank: k_fixed if > 0 else the rank rule with tau), A (m x k), B (k x n)
+    with A B the best rank-k approximation of W split as in Eq. 3, and U, V (the leading k
+    singular vectors, columns)."""
+    W = merged_matrix(A_copies, B_copies, mode)
+    U, s, Vt = svd(W)
+    k = int(k_fixed) if k_fixed and k_fixed > 0 else select_rank(s, tau)
+    k = min(k, len(s))
+    root = np.sqrt(s[:k])
+    return {
+        "W": W, "s": s, "k": k,
+        "A": U[:, :k] * root[None, :],
+        "B": root[:, None] * Vt[:k, :],
+        "U": U[:, :k], "V": Vt[:k, :].T,
+    }
+
+
+def merged_spectrum(A_copies, B_copies, mode=0):
+    """Singular values only of the merged matrix (descending, fp64)."""
+    W = merged_matrix(A_copies, B_copies, mode)
+    if W.shape[1] > W.shape[0]:
+        W = W.T
+    return np.linalg.svd(W, compute_uv=False)
