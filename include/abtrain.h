@@ -1,0 +1,165 @@
+/*
+ * abtrain.h -- C ABI of the MI355X (gfx950) hot path of AB-training (arxiv 2405.01067).
+ *
+ * The paper carries every dense layer weight W (m x n, out x in) as two thin factors
+ *     W = A B,   A = U_k Sigma_k^(1/2)  (m x k),   B = Sigma_k^(1/2) V_k^T  (k x n)     (Eq. 3)
+ * trains the factors in independent groups and periodically merges the group copies
+ * (Algorithm 1: all-reduce of A and of B, W <- A B, re-decomposition with the rank rule
+ * "drop singular values below sigmaCutoff * sigma_max").  This library is that hot path on
+ * one GPU: the factored layer's forward and backward, and the merge of G factor copies.
+ *
+ * Conventions shared by every entry point
+ *   - All matrices are row-major and contiguous (leading dimension = number of columns).
+ *   - Unless a parameter is documented as a HOST pointer it is a DEVICE pointer owned by the
+ *     caller; the library never allocates, frees or retains caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
+ *     work on it and return without synchronising the host.
+ *   - `workspace` is caller-owned device scratch of at least the size the matching
+ *     *_workspace_bytes() query returns, 256-byte aligned; its contents are undefined
+ *     afterwards.  Calls that share a workspace must be stream-ordered.
+ *   - Return value: ABT_OK (0) or a negative abt_status.  Nothing is launched when an error
+ *     is returned.  The library never throws, aborts or prints.
+ *   - `r` below is the paper's k (the retained rank).
+ */
+#ifndef ABTRAIN_H_
+#define ABTRAIN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ABT_OK = 0,
+    ABT_EINVAL = -1,     /* NULL where a pointer is required, bad enum, G < 1, tau outside [0,1] ... */
+    ABT_ESHAPE = -2,     /* a dimension is non-positive or violates a documented divisibility/limit */
+    ABT_EALIGN = -3,     /* a device pointer is not 16-byte aligned (workspace: 256) */
+    ABT_EWORKSPACE = -4, /* workspace NULL or smaller than *_workspace_bytes() */
+    ABT_EDTYPE = -5,     /* unknown abt_dtype */
+    ABT_ENOCONV = -6,    /* reported by ab_merge_info: the Jacobi sweep cap was hit */
+    ABT_EHIP = -7        /* a HIP runtime call failed (launch error, copy error) */
+} abt_status;
+
+typedef enum {
+    ABT_F32 = 0,  /* fp32 storage, fp32 accumulate (fp32 MFMA) */
+    ABT_BF16 = 1  /* bf16 storage, fp32 accumulate (bf16 MFMA); factor gradients stay fp32 */
+} abt_dtype;
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char* abt_status_string(int status);
+
+/* ---------------------------------------------------------------------------------------
+ * Factored layer, forward (Eq. 3 applied to a batch: y = x W^T with W = A B).
+ *
+ *     T[M,r] = X[M,n] . B[r,n]^T          Y[M,m] = T[M,r] . A[m,r]^T
+ *
+ * X, A, B, Y are of type `dt`.  T_save is optional (NULL = T never leaves the chip in the
+ * bf16 path); when given it receives T in type `dt` (bf16: T rounded to nearest-even, the
+ * same values the second product consumes).
+ * Shapes: M >= 1 arbitrary.  ABT_BF16: m, n multiples of 64, r a multiple of 32, r <= 384.
+ *         ABT_F32: any positive m, n, r.
+ * Workspace: lr_linear_fwd_workspace_bytes (0 for ABT_BF16).
+ * ------------------------------------------------------------------------------------- */
+int lr_linear_fwd(const void* X, const void* A, const void* B, void* Y, void* T_save,
+                  int64_t M, int64_t m, int64_t n, int64_t r, int dt,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+size_t lr_linear_fwd_workspace_bytes(int64_t M, int64_t m, int64_t n, int64_t r, int dt);
+
+/* ---------------------------------------------------------------------------------------
+ * Factored layer, backward (chain rule through Eq. 3; during the group phase of
+ * Algorithm 1 a group trains A or B and the other factor is frozen, hence the NULL skips).
+ *
+ *     dT[M,r] = dY[M,m] . A[m,r]           dX[M,n] = dT . B[r,n]
+ *     dA[m,r] = dY^T . T                   dB[r,n] = dT^T . X
+ *
+ * dY, X, T, A, B, dX are of type `dt`; dA and dB are always fp32.
+ * T: the tensor saved by the forward, or NULL to recompute it from X and B.
+ * dX, dA, dB: any may be NULL, that product is then skipped.
+ * accumulate != 0 adds into dA / dB instead of overwriting them (gradient accumulation).
+ * The reduction over the M rows uses a fixed split and a fixed summation order: two calls on
+ * the same inputs give bit-identical results.
+ * Shapes as for the forward.  Workspace: lr_linear_bwd_workspace_bytes.
+ * ------------------------------------------------------------------------------------- */
+int lr_linear_bwd(const void* dY, const void* X, const void* T, const void* A, const void* B,
+                  void* dX, float* dA, float* dB,
+                  int64_t M, int64_t m, int64_t n, int64_t r, int dt, int accumulate,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+size_t lr_linear_bwd_workspace_bytes(int64_t M, int64_t m, int64_t n, int64_t r, int dt);
+
+/* ---------------------------------------------------------------------------------------
+ * Merge of G group copies of one layer's factors (Algorithm 1: A <- allReduce(A/worldSize),
+ * B <- allReduce(B/worldSize), W <- A B; then the AB decomposition of Eq. 3 with the rank
+ * rule of Sec. "Methodology": singular values below tau * sigma_max are removed).
+ * The G copies live in one GPU's memory; there is no communication.
+ *
+ *   mode 0 (the paper): Abar = mean_g A_g, Bbar = mean_g B_g, Wbar = Abar Bbar (rank <= k)
+ *   mode 1            : Wbar = mean_g (A_g B_g)                              (rank <= G k)
+ *   sigma_1 >= sigma_2 >= ... : singular values of Wbar, U, V its singular vectors
+ *   k' = k_fixed if k_fixed > 0, else #{ i : sigma_i >= tau * sigma_1 } (compared in fp32,
+ *        at least 1), clipped to k_cap and to the number of computed singular values
+ *   A_out = U_k' Sigma_k'^(1/2),  B_out = Sigma_k'^(1/2) V_k'^T                   (Eq. 3)
+ *
+ * A_copies, B_copies: HOST arrays of G device pointers; A_g is m x k, B_g is k x n, fp32.
+ *                     The arrays are read before the call returns.
+ * tau in [0,1]; k_fixed >= 0.
+ * A_out [m, k_cap], B_out [k_cap, n]: fp32; columns (rows) >= k' are zero-filled.
+ * S_out [k_cap]: fp32, descending; entries >= the number of computed values are zero.
+ * k_out: one int32 in device memory receiving k'.
+ * W_out: optional fp32 [m, n] receiving the merged (untruncated) Wbar, the dense weight the
+ *        full-rank rebound phase of Algorithm 1 continues from; NULL to skip.
+ * Limits: k a multiple of 32; K = k (mode 0) or G k (mode 1) must be <= 2048; 1 <= k_cap.
+ * Singular vectors of (near-)zero singular values (sigma_i <= 1e-7 sigma_1) are returned as
+ * zero columns/rows: Sigma^(1/2) annihilates them in Eq. 3 anyway.
+ * The SVD runs a one-sided Jacobi iteration with a sweep cap (abt_set_jacobi_max_sweeps);
+ * ab_merge_info reports sweeps used and whether it converged.
+ * ------------------------------------------------------------------------------------- */
+int ab_merge(const float* const* A_copies, const float* const* B_copies, int G,
+             int64_t m, int64_t n, int64_t k, float tau, int64_t k_fixed, int mode,
+             float* A_out, float* B_out, float* S_out, int32_t* k_out, int64_t k_cap,
+             float* W_out, void* workspace, size_t workspace_bytes, void* stream);
+
+size_t ab_merge_workspace_bytes(int G, int64_t m, int64_t n, int64_t k, int64_t k_cap, int mode);
+
+/* One layer of a batched merge; fields as the arguments of ab_merge. */
+typedef struct {
+    const float* const* A_copies; /* HOST array of G device pointers */
+    const float* const* B_copies; /* HOST array of G device pointers */
+    int32_t G;
+    int32_t mode;
+    int64_t m, n, k;
+    float tau;
+    int64_t k_fixed;
+    float* A_out;
+    float* B_out;
+    float* S_out;
+    int32_t* k_out;
+    int64_t k_cap;
+    float* W_out;
+} abt_merge_desc;
+
+/* The same merge for L layers at once (one model's layer set per call): every stage is one
+ * grouped launch over all layers instead of L launches.  `layers` is a HOST array read
+ * before the call returns.  Layers may differ in every field. */
+int ab_merge_batched(const abt_merge_desc* layers, int L,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+size_t ab_merge_batched_workspace_bytes(const abt_merge_desc* layers, int L);
+
+/* After the stream work of ab_merge / ab_merge_batched on `workspace` has been enqueued:
+ * waits for `stream`, then reports for layer `layer` (0 for ab_merge) the Jacobi sweeps used
+ * and the number of singular values computed.  Returns ABT_OK, or ABT_ENOCONV when that
+ * layer hit the sweep cap (results were still written). sweeps / n_sigma: HOST, may be NULL. */
+int ab_merge_info(const void* workspace, int layer, int32_t* sweeps, int32_t* n_sigma,
+                  void* stream);
+
+/* Sweep cap of the Jacobi SVD (default 16, clamped to [1, 64]); returns the previous value. */
+int abt_set_jacobi_max_sweeps(int max_sweeps);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ABTRAIN_H_ */

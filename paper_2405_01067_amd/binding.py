@@ -1,0 +1,284 @@
+"""Thin ctypes binding of libabtrain.so: same names as the C ABI in include/abtrain.h,
+argument marshalling only.  torch supplies device memory and the current stream; every step
+of the computation runs in the library's HIP kernels.  There is no fallback: if the library
+is missing or a call returns an error, this raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+ABT_F32, ABT_BF16 = 0, 1
+ABT_ENOCONV = -6
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libabtrain.so")
+_lib = None
+
+EXPORTS = (
+    "abt_status_string", "abt_set_jacobi_max_sweeps",
+    "lr_linear_fwd", "lr_linear_fwd_workspace_bytes",
+    "lr_linear_bwd", "lr_linear_bwd_workspace_bytes",
+    "ab_merge", "ab_merge_workspace_bytes",
+    "ab_merge_batched", "ab_merge_batched_workspace_bytes", "ab_merge_info",
+)
+
+
+class AbtError(RuntimeError):
+    pass
+
+
+class MergeDesc(ctypes.Structure):
+    """abt_merge_desc"""
+    _fields_ = [
+        ("A_copies", ctypes.POINTER(ctypes.c_void_p)),
+        ("B_copies", ctypes.POINTER(ctypes.c_void_p)),
+        ("G", ctypes.c_int32),
+        ("mode", ctypes.c_int32),
+        ("m", ctypes.c_int64), ("n", ctypes.c_int64), ("k", ctypes.c_int64),
+        ("tau", ctypes.c_float),
+        ("k_fixed", ctypes.c_int64),
+        ("A_out", ctypes.c_void_p), ("B_out", ctypes.c_void_p), ("S_out", ctypes.c_void_p),
+        ("k_out", ctypes.c_void_p),
+        ("k_cap", ctypes.c_int64),
+        ("W_out", ctypes.c_void_p),
+    ]
+
+
+def load():
+    """dlopen the library and declare the prototypes.  Needs no GPU."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise AbtError(f"{_LIB_PATH} is missing: run `python __graft_entry__.py` (build) first")
+    lib = ctypes.CDLL(_LIB_PATH)
+    for name in EXPORTS:
+        if not hasattr(lib, name):
+            raise AbtError(f"libabtrain.so does not export {name}")
+    i64, vp, sz, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    lib.abt_status_string.restype = ctypes.c_char_p
+    lib.abt_status_string.argtypes = [ci]
+    lib.abt_set_jacobi_max_sweeps.restype = ci
+    lib.abt_set_jacobi_max_sweeps.argtypes = [ci]
+    lib.lr_linear_fwd.restype = ci
+    lib.lr_linear_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, vp, sz, vp]
+    lib.lr_linear_fwd_workspace_bytes.restype = sz
+    lib.lr_linear_fwd_workspace_bytes.argtypes = [i64, i64, i64, i64, ci]
+    lib.lr_linear_bwd.restype = ci
+    lib.lr_linear_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, vp, sz, vp]
+    lib.lr_linear_bwd_workspace_bytes.restype = sz
+    lib.lr_linear_bwd_workspace_bytes.argtypes = [i64, i64, i64, i64, ci]
+    pvp = ctypes.POINTER(ctypes.c_void_p)
+    lib.ab_merge.restype = ci
+    lib.ab_merge.argtypes = [pvp, pvp, ci, i64, i64, i64, ctypes.c_float, i64, ci,
+                             vp, vp, vp, vp, i64, vp, vp, sz, vp]
+    lib.ab_merge_workspace_bytes.restype = sz
+    lib.ab_merge_workspace_bytes.argtypes = [ci, i64, i64, i64, i64, ci]
+    lib.ab_merge_batched.restype = ci
+    lib.ab_merge_batched.argtypes = [ctypes.POINTER(MergeDesc), ci, vp, sz, vp]
+    lib.ab_merge_batched_workspace_bytes.restype = sz
+    lib.ab_merge_batched_workspace_bytes.argtypes = [ctypes.POINTER(MergeDesc), ci]
+    lib.ab_merge_info.restype = ci
+    lib.ab_merge_info.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32), vp]
+    _lib = lib
+    return lib
+
+
+def status_string(code: int) -> str:
+    return load().abt_status_string(int(code)).decode()
+
+
+def _check(code: int, what: str):
+    if code != 0:
+        raise AbtError(f"{what} failed: {status_string(code)} ({code})")
+
+
+def set_jacobi_max_sweeps(n: int) -> int:
+    return load().abt_set_jacobi_max_sweeps(int(n))
+
+
+# --------------------------------------------------------------------------------------
+# torch-facing wrappers (allocation of outputs/workspace + pointer marshalling only)
+# --------------------------------------------------------------------------------------
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dt(t):
+    torch = _torch()
+    if t.dtype == torch.bfloat16:
+        return ABT_BF16
+    if t.dtype == torch.float32:
+        return ABT_F32
+    raise AbtError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _stream():
+    return ctypes.c_void_p(_torch().cuda.current_stream().cuda_stream)
+
+
+def _dev_tensor(t, name):
+    if not t.is_cuda:
+        raise AbtError(f"{name} must live on the GPU: the library has no CPU path")
+    if not t.is_contiguous():
+        raise AbtError(f"{name} must be contiguous")
+    return t
+
+
+def _workspace(nbytes: int, device, workspace=None):
+    torch = _torch()
+    if workspace is not None:
+        if workspace.numel() * workspace.element_size() < nbytes:
+            raise AbtError("workspace tensor too small")
+        return workspace
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def lr_linear_fwd(X, A, B, save_T: bool = True, Y=None, T=None, workspace=None):
+    """Y = (X B^T) A^T.  Returns (Y, T) (T is None when save_T is False)."""
+    torch = _torch()
+    lib = load()
+    X, A, B = _dev_tensor(X, "X"), _dev_tensor(A, "A"), _dev_tensor(B, "B")
+    M, n = X.shape
+    m, r = A.shape
+    if tuple(B.shape) != (r, n) or A.dtype != X.dtype or B.dtype != X.dtype:
+        raise AbtError("shape/dtype mismatch: X [M,n], A [m,r], B [r,n], one dtype")
+    dt = _dt(X)
+    if Y is None:
+        Y = torch.empty((M, m), dtype=X.dtype, device=X.device)
+    if save_T and T is None:
+        T = torch.empty((M, r), dtype=X.dtype, device=X.device)
+    nbytes = lib.lr_linear_fwd_workspace_bytes(M, m, n, r, dt)
+    ws = _workspace(nbytes, X.device, workspace)
+    _check(lib.lr_linear_fwd(_ptr(X), _ptr(A), _ptr(B), _ptr(Y), _ptr(T if save_T else None),
+                             M, m, n, r, dt, _ptr(ws), ws.numel(), _stream()), "lr_linear_fwd")
+    return Y, (T if save_T else None)
+
+
+def lr_linear_bwd(dY, X, T, A, B, need_dX: bool = True, need_dA: bool = True, need_dB: bool = True,
+                  dX=None, dA=None, dB=None, accumulate: bool = False, workspace=None):
+    """dX = (dY A) B, dA = dY^T T, dB = (dY A)^T X.  T may be None (recomputed).
+    Returns (dX, dA, dB); skipped gradients are None."""
+    torch = _torch()
+    lib = load()
+    dY, X, A, B = (_dev_tensor(t, nm) for t, nm in ((dY, "dY"), (X, "X"), (A, "A"), (B, "B")))
+    M, n = X.shape
+    m, r = A.shape
+    if tuple(dY.shape) != (M, m) or tuple(B.shape) != (r, n):
+        raise AbtError("shape mismatch: dY [M,m], X [M,n], A [m,r], B [r,n]")
+    if T is not None and tuple(_dev_tensor(T, "T").shape) != (M, r):
+        raise AbtError("T must be [M,r]")
+    dt = _dt(X)
+    if need_dX and dX is None:
+        dX = torch.empty((M, n), dtype=X.dtype, device=X.device)
+    if need_dA and dA is None:
+        if accumulate:
+            raise AbtError("accumulate needs existing dA")
+        dA = torch.empty((m, r), dtype=torch.float32, device=X.device)
+    if need_dB and dB is None:
+        if accumulate:
+            raise AbtError("accumulate needs existing dB")
+        dB = torch.empty((r, n), dtype=torch.float32, device=X.device)
+    nbytes = lib.lr_linear_bwd_workspace_bytes(M, m, n, r, dt)
+    ws = _workspace(nbytes, X.device, workspace)
+    _check(lib.lr_linear_bwd(_ptr(dY), _ptr(X), _ptr(T), _ptr(A), _ptr(B),
+                             _ptr(dX if need_dX else None), _ptr(dA if need_dA else None),
+                             _ptr(dB if need_dB else None), M, m, n, r, dt, int(bool(accumulate)),
+                             _ptr(ws), ws.numel(), _stream()), "lr_linear_bwd")
+    return (dX if need_dX else None), (dA if need_dA else None), (dB if need_dB else None)
+
+
+def _ptr_array(tensors: Sequence):
+    arr = (ctypes.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+    return arr
+
+
+def ab_merge(A_copies: Sequence, B_copies: Sequence, tau: float, k_fixed: int = 0, mode: int = 0,
+             k_cap: Optional[int] = None, want_W: bool = False, workspace=None, check_converged: bool = True):
+    """Merge G copies of one layer.  Returns dict(A [m,k_cap], B [k_cap,n], S [k_cap], k (0-d int32
+    tensor on the GPU), W or None, workspace)."""
+    outs = ab_merge_batched([dict(A_copies=A_copies, B_copies=B_copies, tau=tau, k_fixed=k_fixed,
+                                  mode=mode, k_cap=k_cap, want_W=want_W)], workspace=workspace,
+                            check_converged=check_converged, _single=True)
+    return outs[0]
+
+
+def ab_merge_batched(layers: List[dict], workspace=None, check_converged: bool = True, _single: bool = False):
+    """Merge L layers in one call.  Each layer dict: A_copies, B_copies (lists of fp32 GPU tensors),
+    tau, and optionally k_fixed, mode, k_cap, want_W, or preallocated A_out/B_out/S_out/k_out/W_out."""
+    torch = _torch()
+    lib = load()
+    L = len(layers)
+    descs = (MergeDesc * L)()
+    keep = []
+    outs = []
+    dev = None
+    for i, lay in enumerate(layers):
+        As = [_dev_tensor(a, "A copy") for a in lay["A_copies"]]
+        Bs = [_dev_tensor(b, "B copy") for b in lay["B_copies"]]
+        G = len(As)
+        if G < 1 or len(Bs) != G:
+            raise AbtError("need G >= 1 copies of A and of B")
+        m, k = As[0].shape
+        k2, n = Bs[0].shape
+        for a, b in zip(As, Bs):
+            if tuple(a.shape) != (m, k) or tuple(b.shape) != (k, n) or a.dtype != torch.float32 or b.dtype != torch.float32:
+                raise AbtError("all copies must be fp32 with identical shapes A [m,k], B [k,n]")
+        dev = As[0].device
+        mode = int(lay.get("mode", 0))
+        K = k if mode == 0 else k * G
+        k_cap = lay.get("k_cap") or K
+        A_out = lay.get("A_out")
+        if A_out is None:
+            A_out = torch.empty((m, k_cap), dtype=torch.float32, device=dev)
+        B_out = lay.get("B_out")
+        if B_out is None:
+            B_out = torch.empty((k_cap, n), dtype=torch.float32, device=dev)
+        S_out = lay.get("S_out")
+        if S_out is None:
+            S_out = torch.empty((k_cap,), dtype=torch.float32, device=dev)
+        k_out = lay.get("k_out")
+        if k_out is None:
+            k_out = torch.zeros((), dtype=torch.int32, device=dev)
+        W_out = lay.get("W_out")
+        if W_out is None and lay.get("want_W"):
+            W_out = torch.empty((m, n), dtype=torch.float32, device=dev)
+        pa, pb = _ptr_array(As), _ptr_array(Bs)
+        keep.append((As, Bs, pa, pb))
+        d = descs[i]
+        d.A_copies = ctypes.cast(pa, ctypes.POINTER(ctypes.c_void_p))
+        d.B_copies = ctypes.cast(pb, ctypes.POINTER(ctypes.c_void_p))
+        d.G, d.mode, d.m, d.n, d.k = G, mode, m, n, k
+        d.tau, d.k_fixed = float(lay["tau"]), int(lay.get("k_fixed", 0))
+        d.A_out, d.B_out, d.S_out, d.k_out = A_out.data_ptr(), B_out.data_ptr(), S_out.data_ptr(), k_out.data_ptr()
+        d.k_cap = int(k_cap)
+        d.W_out = W_out.data_ptr() if W_out is not None else None
+        outs.append({"A": A_out, "B": B_out, "S": S_out, "k": k_out, "W": W_out})
+    nbytes = lib.ab_merge_batched_workspace_bytes(descs, L)
+    if nbytes == 0:
+        raise AbtError("ab_merge_batched_workspace_bytes rejected the layer list")
+    ws = _workspace(nbytes, dev, workspace)
+    _check(lib.ab_merge_batched(descs, L, _ptr(ws), ws.numel(), _stream()), "ab_merge_batched")
+    for o in outs:
+        o["workspace"] = ws
+    if check_converged:
+        for i in range(L):
+            sweeps, nsig = merge_info(ws, i)
+            outs[i]["sweeps"] = sweeps
+    return outs
+
+
+def merge_info(workspace, layer: int = 0):
+    """(sweeps, n_sigma) of a finished merge; raises if the Jacobi sweep cap was hit."""
+    lib = load()
+    sweeps, nsig = ctypes.c_int32(0), ctypes.c_int32(0)
+    code = lib.ab_merge_info(_ptr(workspace), int(layer), ctypes.byref(sweeps), ctypes.byref(nsig), _stream())
+    _check(code, "ab_merge_info")
+    return sweeps.value, nsig.value

@@ -1,0 +1,249 @@
+// C ABI of the library: argument validation, workspace carving and the launch sequences.
+// Every operation is documented in include/abtrain.h.
+#include <vector>
+
+#include "common.h"
+
+using namespace abt;
+
+namespace {
+
+int g_max_sweeps = 16;
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline size_t esize(int dt) { return dt == ABT_BF16 ? 2 : 4; }
+
+int check_lr_shapes(int64_t M, int64_t m, int64_t n, int64_t r, int dt) {
+    if (dt != ABT_F32 && dt != ABT_BF16) return ABT_EDTYPE;
+    if (M < 1 || m < 1 || n < 1 || r < 1) return ABT_ESHAPE;
+    if (M > 0x7fffffff || m > 0x7fffffff || n > 0x7fffffff || r > 0x7fffffff) return ABT_ESHAPE;
+    if (dt == ABT_BF16) {
+        if (m % 64 || n % 64 || r % 32 || r > 384) return ABT_ESHAPE;
+    }
+    return ABT_OK;
+}
+
+GemmF32 gemm(const float* A, const float* B, float* C, int64_t P, int64_t Q, int64_t K,
+             int64_t lda, int64_t ldb, int64_t ldc, int tA, int tB, int acc) {
+    GemmF32 g{};
+    g.A = A; g.B = B; g.C = C; g.P = (int)P; g.Q = (int)Q; g.K = (int)K;
+    g.lda = (int)lda; g.ldb = (int)ldb; g.ldc = (int)ldc;
+    g.transA = tA; g.transB = tB; g.accumulate = acc; g.alpha = 1.0f;
+    return g;
+}
+
+struct BwdLayout {  // bf16 backward workspace
+    size_t At, Bt, dT, T, partials, total;
+};
+
+BwdLayout bwd_layout_bf16(int64_t M, int64_t m, int64_t n, int64_t r) {
+    BwdLayout w{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    w.At = take((size_t)r * m * 2);
+    w.Bt = take((size_t)n * r * 2);
+    w.dT = take((size_t)M * r * 2);
+    w.T = take((size_t)M * r * 2);
+    // the split count depends on which gradients are requested: size for the worst subset
+    TnJob jobs[2] = {{nullptr, nullptr, nullptr, (int)m, 0}, {nullptr, nullptr, nullptr, (int)n, 1}};
+    size_t part = tn_partials_bytes(M, jobs, 2, (int)r);
+    const size_t only_a = tn_partials_bytes(M, jobs, 1, (int)r), only_b = tn_partials_bytes(M, jobs + 1, 1, (int)r);
+    if (only_a > part) part = only_a;
+    if (only_b > part) part = only_b;
+    w.partials = take(part);
+    w.total = off;
+    return w;
+}
+
+int check_merge_layer(const abt_merge_desc& d) {
+    if (!d.A_copies || !d.B_copies || !d.A_out || !d.B_out || !d.S_out || !d.k_out) return ABT_EINVAL;
+    if (d.G < 1 || (d.mode != 0 && d.mode != 1)) return ABT_EINVAL;
+    if (!(d.tau >= 0.0f && d.tau <= 1.0f) || d.k_fixed < 0) return ABT_EINVAL;
+    if (d.m < 1 || d.n < 1 || d.k < 1 || d.k_cap < 1) return ABT_ESHAPE;
+    if (d.k % 32) return ABT_ESHAPE;
+    const int64_t K = d.mode == 0 ? d.k : d.k * d.G;
+    if (K > 2048 || d.m > 0x7fffffff || d.n > 0x7fffffff || d.k_cap > 0x7fffffff) return ABT_ESHAPE;
+    for (int g = 0; g < d.G; ++g) {
+        if (!d.A_copies[g] || !d.B_copies[g]) return ABT_EINVAL;
+        if (!aligned(d.A_copies[g], 16) || !aligned(d.B_copies[g], 16)) return ABT_EALIGN;
+    }
+    if (!aligned(d.A_out, 16) || !aligned(d.B_out, 16) || !aligned(d.S_out, 4) || !aligned(d.k_out, 4))
+        return ABT_EALIGN;
+    if (d.W_out && !aligned(d.W_out, 16)) return ABT_EALIGN;
+    return ABT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* abt_status_string(int status) {
+    switch (status) {
+        case ABT_OK: return "ABT_OK";
+        case ABT_EINVAL: return "ABT_EINVAL: invalid argument";
+        case ABT_ESHAPE: return "ABT_ESHAPE: unsupported shape";
+        case ABT_EALIGN: return "ABT_EALIGN: misaligned pointer";
+        case ABT_EWORKSPACE: return "ABT_EWORKSPACE: workspace missing or too small";
+        case ABT_EDTYPE: return "ABT_EDTYPE: unknown dtype";
+        case ABT_ENOCONV: return "ABT_ENOCONV: Jacobi sweep cap reached";
+        case ABT_EHIP: return "ABT_EHIP: HIP runtime error";
+        default: return "unknown abt_status";
+    }
+}
+
+int abt_set_jacobi_max_sweeps(int max_sweeps) {
+    const int prev = g_max_sweeps;
+    g_max_sweeps = max_sweeps < 1 ? 1 : (max_sweeps > 64 ? 64 : max_sweeps);
+    return prev;
+}
+
+size_t lr_linear_fwd_workspace_bytes(int64_t M, int64_t m, int64_t n, int64_t r, int dt) {
+    if (check_lr_shapes(M, m, n, r, dt) != ABT_OK) return 0;
+    return dt == ABT_F32 ? align_up((size_t)M * r * 4, 256) : 0;
+}
+
+size_t lr_linear_bwd_workspace_bytes(int64_t M, int64_t m, int64_t n, int64_t r, int dt) {
+    if (check_lr_shapes(M, m, n, r, dt) != ABT_OK) return 0;
+    if (dt == ABT_F32) return 2 * align_up((size_t)M * r * 4, 256);
+    return bwd_layout_bf16(M, m, n, r).total;
+}
+
+int lr_linear_fwd(const void* X, const void* A, const void* B, void* Y, void* T_save,
+                  int64_t M, int64_t m, int64_t n, int64_t r, int dt,
+                  void* workspace, size_t workspace_bytes, void* stream) {
+    int st = check_lr_shapes(M, m, n, r, dt);
+    if (st != ABT_OK) return st;
+    if (!X || !A || !B || !Y) return ABT_EINVAL;
+    if (!aligned(X, 16) || !aligned(A, 16) || !aligned(B, 16) || !aligned(Y, 16) || !aligned(T_save, 16))
+        return ABT_EALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    if (dt == ABT_BF16) {
+        return launch_chain_bf16(X, B, A, Y, T_save, M, (int)n, (int)m, (int)r, s) == hipSuccess ? ABT_OK : ABT_EHIP;
+    }
+    float* T = (float*)T_save;
+    if (!T) {
+        if (!workspace || workspace_bytes < lr_linear_fwd_workspace_bytes(M, m, n, r, dt)) return ABT_EWORKSPACE;
+        if (!aligned(workspace, 256)) return ABT_EALIGN;
+        T = (float*)workspace;
+    }
+    // T = X B^T ; Y = T A^T
+    if (launch_gemm_f32_one(gemm((const float*)X, (const float*)B, T, M, r, n, n, n, r, 0, 1, 0), s) != hipSuccess) return ABT_EHIP;
+    if (launch_gemm_f32_one(gemm(T, (const float*)A, (float*)Y, M, m, r, r, r, m, 0, 1, 0), s) != hipSuccess) return ABT_EHIP;
+    return ABT_OK;
+}
+
+int lr_linear_bwd(const void* dY, const void* X, const void* T, const void* A, const void* B,
+                  void* dX, float* dA, float* dB,
+                  int64_t M, int64_t m, int64_t n, int64_t r, int dt, int accumulate,
+                  void* workspace, size_t workspace_bytes, void* stream) {
+    int st = check_lr_shapes(M, m, n, r, dt);
+    if (st != ABT_OK) return st;
+    if (!dY || !X || !A || !B) return ABT_EINVAL;
+    if (!aligned(dY, 16) || !aligned(X, 16) || !aligned(T, 16) || !aligned(A, 16) || !aligned(B, 16) ||
+        !aligned(dX, 16) || !aligned(dA, 16) || !aligned(dB, 16))
+        return ABT_EALIGN;
+    if (!workspace || workspace_bytes < lr_linear_bwd_workspace_bytes(M, m, n, r, dt)) return ABT_EWORKSPACE;
+    if (!aligned(workspace, 256)) return ABT_EALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    char* ws = (char*)workspace;
+    const int acc = accumulate ? 1 : 0;
+    if (!dX && !dA && !dB) return ABT_OK;
+
+    if (dt == ABT_F32) {
+        float* dT = (float*)ws;
+        const float* Tp = (const float*)T;
+        const bool need_dT = dX || dB;
+        if (!Tp && dA) {
+            float* Tw = (float*)(ws + align_up((size_t)M * r * 4, 256));
+            if (launch_gemm_f32_one(gemm((const float*)X, (const float*)B, Tw, M, r, n, n, n, r, 0, 1, 0), s) != hipSuccess) return ABT_EHIP;
+            Tp = Tw;
+        }
+        if (need_dT &&
+            launch_gemm_f32_one(gemm((const float*)dY, (const float*)A, dT, M, r, m, m, r, r, 0, 0, 0), s) != hipSuccess) return ABT_EHIP;
+        if (dX &&
+            launch_gemm_f32_one(gemm(dT, (const float*)B, (float*)dX, M, n, r, r, n, n, 0, 0, 0), s) != hipSuccess) return ABT_EHIP;
+        if (dA &&
+            launch_gemm_f32_one(gemm((const float*)dY, Tp, dA, m, r, M, m, r, r, 1, 0, acc), s) != hipSuccess) return ABT_EHIP;
+        if (dB &&
+            launch_gemm_f32_one(gemm(dT, (const float*)X, dB, r, n, M, r, n, n, 1, 0, acc), s) != hipSuccess) return ABT_EHIP;
+        return ABT_OK;
+    }
+
+    const BwdLayout w = bwd_layout_bf16(M, m, n, r);
+    void* At = ws + w.At; void* Bt = ws + w.Bt; void* dT = ws + w.dT;
+    const void* Tp = T;
+    hipError_t e = hipSuccess;
+    if (!Tp && dA) {  // recompute T = X B^T (first stage of the chain only)
+        e = launch_chain_bf16(X, B, nullptr, nullptr, ws + w.T, M, (int)n, (int)m, (int)r, s);
+        if (e != hipSuccess) return ABT_EHIP;
+        Tp = ws + w.T;
+    }
+    if (dX || dB) {
+        // dT = dY A = dY (A^T)^T and dX = dT B = dT (B^T)^T: the forward chain on transposed factors
+        e = launch_transpose_bf16(A, At, (int)m, (int)r, s);
+        if (e != hipSuccess) return ABT_EHIP;
+        if (dX) {
+            e = launch_transpose_bf16(B, Bt, (int)r, (int)n, s);
+            if (e != hipSuccess) return ABT_EHIP;
+        }
+        e = launch_chain_bf16(dY, At, dX ? Bt : nullptr, dX, dT, M, (int)m, (int)n, (int)r, s);
+        if (e != hipSuccess) return ABT_EHIP;
+    }
+    TnJob jobs[2];
+    int nj = 0;
+    if (dA) jobs[nj++] = TnJob{dY, Tp, dA, (int)m, 0};
+    if (dB) jobs[nj++] = TnJob{X, dT, dB, (int)n, 1};
+    if (nj) {
+        e = launch_tn_bf16(jobs, nj, M, (int)r, acc, (float*)(ws + w.partials), s);
+        if (e != hipSuccess) return ABT_EHIP;
+    }
+    return ABT_OK;
+}
+
+size_t ab_merge_batched_workspace_bytes(const abt_merge_desc* layers, int L) {
+    if (!layers || L < 1) return 0;
+    for (int l = 0; l < L; ++l)
+        if (layers[l].G < 1 || layers[l].m < 1 || layers[l].n < 1 || layers[l].k < 1 || layers[l].k_cap < 1 ||
+            (layers[l].mode != 0 && layers[l].mode != 1))
+            return 0;
+    return merge_workspace_bytes(layers, L);
+}
+
+int ab_merge_batched(const abt_merge_desc* layers, int L, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!layers || L < 1) return ABT_EINVAL;
+    for (int l = 0; l < L; ++l) {
+        const int st = check_merge_layer(layers[l]);
+        if (st != ABT_OK) return st;
+    }
+    if (!workspace || workspace_bytes < merge_workspace_bytes(layers, L)) return ABT_EWORKSPACE;
+    if (!aligned(workspace, 256)) return ABT_EALIGN;
+    return merge_run(layers, L, workspace, g_max_sweeps, (hipStream_t)stream) == hipSuccess ? ABT_OK : ABT_EHIP;
+}
+
+size_t ab_merge_workspace_bytes(int G, int64_t m, int64_t n, int64_t k, int64_t k_cap, int mode) {
+    abt_merge_desc d{};
+    d.G = G; d.m = m; d.n = n; d.k = k; d.k_cap = k_cap; d.mode = mode;
+    return ab_merge_batched_workspace_bytes(&d, 1);
+}
+
+int ab_merge(const float* const* A_copies, const float* const* B_copies, int G,
+             int64_t m, int64_t n, int64_t k, float tau, int64_t k_fixed, int mode,
+             float* A_out, float* B_out, float* S_out, int32_t* k_out, int64_t k_cap,
+             float* W_out, void* workspace, size_t workspace_bytes, void* stream) {
+    abt_merge_desc d{};
+    d.A_copies = A_copies; d.B_copies = B_copies; d.G = G; d.mode = mode;
+    d.m = m; d.n = n; d.k = k; d.tau = tau; d.k_fixed = k_fixed;
+    d.A_out = A_out; d.B_out = B_out; d.S_out = S_out; d.k_out = k_out; d.k_cap = k_cap; d.W_out = W_out;
+    return ab_merge_batched(&d, 1, workspace, workspace_bytes, stream);
+}
+
+int ab_merge_info(const void* workspace, int layer, int32_t* sweeps, int32_t* n_sigma, void* stream) {
+    if (!workspace || layer < 0) return ABT_EINVAL;
+    int32_t info[4] = {0, 0, 0, 0};
+    if (merge_read_info(workspace, layer, info, (hipStream_t)stream) != hipSuccess) return ABT_EHIP;
+    if (sweeps) *sweeps = info[0];
+    if (n_sigma) *n_sigma = info[1];
+    return info[2] ? ABT_OK : ABT_ENOCONV;
+}
+
+}  // extern "C"

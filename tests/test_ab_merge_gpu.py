@@ -1,0 +1,228 @@
+"""Parity of the HIP merge (ab_merge / ab_merge_batched, through the C ABI) against the CPU oracle.
+
+Singular vectors are only defined up to sign (and rotation inside clusters), so the comparison
+uses what is unique: the singular values (1e-4 relative on the kept ones), the selected rank
+(exact; the test spectra have a gap at the threshold), the product A'B' and the projectors
+U'U'^T, V'V'^T (1e-4 relative Frobenius), plus the balanced split A'^T A' = Sigma = B' B'^T."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ab_oracle as orc
+from paper_2405_01067_amd import binding as abt
+from paper_2405_01067_amd import inputs as gen
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+def rel(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to("cuda:0")
+
+
+def host(t):
+    return t.detach().cpu().numpy().astype(np.float64)
+
+
+def compare(out, ref, tol=TOL, expect_k=None, check_W=False):
+    k = int(out["k"].item())
+    assert k == ref["k"], (k, ref["k"])
+    if expect_k is not None:
+        assert k == expect_k
+    S = host(out["S"])
+    s_err = float(np.max(np.abs(S[:k] - ref["s"][:k]) / ref["s"][:k]))
+    A, B = host(out["A"]), host(out["B"])
+    assert not A[:, k:].any() and not B[k:, :].any(), "columns/rows beyond k' must be zero"
+    A, B = A[:, :k], B[:k, :]
+    errs = {"sigma": s_err, "AB": rel(A @ B, ref["A"] @ ref["B"])}
+    # balanced split of Eq. 3: A'^T A' = Sigma_k' = B' B'^T
+    errs["AtA"] = rel(A.T @ A, np.diag(ref["s"][:k]))
+    errs["BBt"] = rel(B @ B.T, np.diag(ref["s"][:k]))
+    # singular subspaces, sign- and rotation-invariant
+    U = A / np.sqrt(ref["s"][:k])[None, :]
+    V = (B / np.sqrt(ref["s"][:k])[:, None]).T
+    errs["projU"] = float(np.linalg.norm(U @ U.T - ref["U"] @ ref["U"].T) / math.sqrt(k))
+    errs["projV"] = float(np.linalg.norm(V @ V.T - ref["V"] @ ref["V"].T) / math.sqrt(k))
+    if check_W:
+        errs["W"] = rel(host(out["W"]), ref["W"])
+    assert all(e < tol for e in errs.values()), errs
+    return errs
+
+
+def gap_tau(sigma, gap):
+    return float(math.sqrt(sigma[gap - 1] * sigma[gap]) / sigma[0])
+
+
+# ------------------------------------------------------------------ config 1
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_config1_merge(mode):
+    c = gen.config1_dense(0)
+    A, B, _, _ = orc.ab_decomposition(c["W"], k=32)
+    As = [A.astype(np.float32), (A + c["noise_A"]).astype(np.float32)]
+    Bs = [B.astype(np.float32), (B + c["noise_B"]).astype(np.float32)]
+    out = abt.ab_merge([dev(a) for a in As], [dev(b) for b in Bs], tau=c["tau"], mode=mode, want_W=True)
+    ref = orc.ab_merge(As, Bs, tau=c["tau"], mode=mode)
+    # the 32 kept values lie within 1.3x of each other: subspace of the whole kept cluster is unique
+    compare(out, ref, expect_k=32, check_W=True)
+
+
+# ------------------------------------------------------------------ planted spectra, both modes, ragged shapes
+
+@pytest.mark.parametrize("m,n,k_in,G,gap,mode", [
+    (192, 128, 64, 3, 20, 0),
+    (128, 320, 96, 2, 40, 0),     # n > m
+    (200, 136, 32, 4, 9, 0),      # m, n not multiples of the tile sizes
+    (256, 192, 32, 2, 12, 1),     # K = 64 by concatenation
+    (160, 224, 64, 3, 30, 1),     # K = 192 > min(m,n) = 160: rank-deficient core
+])
+def test_planted_gap(m, n, k_in, G, gap, mode):
+    lay = gen.merge_layer(m, n, seed=1000 + m + k_in, k_in=k_in, g=G, gap_at=gap)
+    tau = gap_tau(lay["sigma_planted"], gap)
+    out = abt.ab_merge([dev(a) for a in lay["A_copies"]], [dev(b) for b in lay["B_copies"]],
+                       tau=tau, mode=mode, want_W=True)
+    ref = orc.ab_merge(lay["A_copies"], lay["B_copies"], tau=tau, mode=mode)
+    compare(out, ref, expect_k=gap, check_W=True)
+
+
+def test_identical_copies_are_a_fixed_point():
+    rng = np.random.default_rng(3)
+    sigma = np.linspace(4.0, 1.0, 32)
+    L, R, _, _ = gen.planted_factor_pair(rng, 160, 96, sigma)
+    L32, R32 = L.astype(np.float32), R.astype(np.float32)
+    for mode in (0, 1):   # mode 1: the concatenation has exactly dependent columns
+        out = abt.ab_merge([dev(L32)] * 3, [dev(R32)] * 3, tau=0.1, mode=mode)
+        ref = orc.ab_merge([L32] * 3, [R32] * 3, tau=0.1, mode=mode)
+        compare(out, ref, expect_k=32)
+        assert rel(host(out["S"])[:32], sigma) < 1e-5
+
+
+def test_scaling_separates_mean_of_factors_from_mean_of_products():
+    rng = np.random.default_rng(4)
+    sigma = np.array([3.0, 2.0, 1.5] + [1.0 / (i + 2) for i in range(29)])
+    L, R, _, _ = gen.planted_factor_pair(rng, 96, 64, sigma)
+    As = [dev(1.0 * L), dev(3.0 * L)]
+    Bs = [dev(2.0 * R), dev(6.0 * R)]
+    s0 = host(abt.ab_merge(As, Bs, tau=0.0, mode=0)["S"])[:32]
+    s1 = host(abt.ab_merge(As, Bs, tau=0.0, mode=1)["S"])[:32]
+    assert rel(s0, 8.0 * sigma) < 1e-5      # mean(1,3) * mean(2,6)
+    assert rel(s1, 10.0 * sigma) < 1e-5     # mean(1*2, 3*6)
+
+
+def test_k_fixed_k_cap_and_threshold_extremes():
+    lay = gen.merge_layer(128, 96, seed=77, k_in=32, g=2, gap_at=10)
+    As = [dev(a) for a in lay["A_copies"]]
+    Bs = [dev(b) for b in lay["B_copies"]]
+    ref = orc.ab_merge(lay["A_copies"], lay["B_copies"], tau=0.0, k_fixed=7)
+    out = abt.ab_merge(As, Bs, tau=0.5, k_fixed=7)
+    compare(out, ref, expect_k=7)
+    # k_cap smaller than the rank the threshold would select clips k'
+    out = abt.ab_merge(As, Bs, tau=gap_tau(lay["sigma_planted"], 10), k_cap=6)
+    assert int(out["k"].item()) == 6 and out["A"].shape == (128, 6)
+    ref6 = orc.ab_merge(lay["A_copies"], lay["B_copies"], tau=0.0, k_fixed=6)
+    assert rel(host(out["A"]) @ host(out["B"]), ref6["A"] @ ref6["B"]) < TOL
+    # k_cap larger than K: the extra columns / rows / values are zero
+    out = abt.ab_merge(As, Bs, tau=gap_tau(lay["sigma_planted"], 10), k_cap=48)
+    assert int(out["k"].item()) == 10 and not host(out["S"])[32:].any() and not host(out["A"])[:, 10:].any()
+    # tau = 1 keeps only the largest, tau = 0 keeps every computed value
+    assert int(abt.ab_merge(As, Bs, tau=1.0)["k"].item()) == 1
+    assert int(abt.ab_merge(As, Bs, tau=0.0)["k"].item()) == 32
+
+
+def test_single_copy_and_reruns_are_bit_identical():
+    lay = gen.merge_layer(192, 160, seed=8, k_in=64, g=1, gap_at=25)
+    As, Bs = [dev(lay["A_copies"][0])], [dev(lay["B_copies"][0])]
+    tau = gap_tau(lay["sigma_planted"], 25)
+    o1 = abt.ab_merge(As, Bs, tau=tau)
+    o2 = abt.ab_merge(As, Bs, tau=tau)
+    torch.cuda.synchronize()
+    assert torch.equal(o1["A"], o2["A"]) and torch.equal(o1["B"], o2["B"]) and torch.equal(o1["S"], o2["S"])
+    compare(o1, orc.ab_merge(lay["A_copies"], lay["B_copies"], tau=tau), expect_k=25)
+
+
+def test_batched_mixed_layers_match_single_calls():
+    specs = [(192, 128, 64, 3, 20, 0), (128, 256, 32, 2, 10, 0), (160, 96, 32, 2, 8, 1), (320, 192, 96, 4, 50, 0)]
+    layers, refs = [], []
+    for i, (m, n, k_in, G, gap, mode) in enumerate(specs):
+        lay = gen.merge_layer(m, n, seed=500 + i, k_in=k_in, g=G, gap_at=gap)
+        tau = gap_tau(lay["sigma_planted"], gap)
+        layers.append(dict(A_copies=[dev(a) for a in lay["A_copies"]], B_copies=[dev(b) for b in lay["B_copies"]],
+                           tau=tau, mode=mode, want_W=(i % 2 == 0)))
+        refs.append((orc.ab_merge(lay["A_copies"], lay["B_copies"], tau=tau, mode=mode), gap))
+    outs = abt.ab_merge_batched(layers)
+    for out, (ref, gap), lay in zip(outs, refs, layers):
+        compare(out, ref, expect_k=gap, check_W=lay["want_W"])
+        assert 1 <= out["sweeps"] <= 16
+
+
+def test_sweep_cap_is_reported():
+    lay = gen.merge_layer(128, 128, seed=9, k_in=64, g=2, gap_at=20, noise_std=0.05)
+    As = [dev(a) for a in lay["A_copies"]]
+    Bs = [dev(b) for b in lay["B_copies"]]
+    prev = abt.set_jacobi_max_sweeps(1)
+    try:
+        with pytest.raises(abt.AbtError, match="ENOCONV"):
+            abt.ab_merge(As, Bs, tau=0.1)
+    finally:
+        abt.set_jacobi_max_sweeps(prev)
+    out = abt.ab_merge(As, Bs, tau=0.1)
+    assert out["sweeps"] >= 2
+
+
+# ------------------------------------------------------------------ config 5 at full size
+
+def _cfg5_layer_inputs(idx_list):
+    table = gen.config5_layers()
+    for idx in idx_list:
+        _, name, m, n, seed = table[idx]
+        yield idx, name, gen.merge_layer(m, n, seed)
+
+
+def test_config5_one_block_full_check():
+    """The four layer shapes of one ViT-B/16 block, G = 4, k_in = 384: full invariant check in both
+    sub-cases (literal tau = 0.1; gap-centred tau -> k' = 192)."""
+    lays = list(_cfg5_layer_inputs([0, 1, 2, 3]))
+    for tau, expect in ((gen.CFG5_TAU_GAP, gen.CFG5_GAP_AT), (gen.CFG5_TAU_LITERAL, None)):
+        layers = [dict(A_copies=[dev(a) for a in lay["A_copies"]], B_copies=[dev(b) for b in lay["B_copies"]],
+                       tau=tau, want_W=(idx == 1)) for idx, _, lay in lays]
+        outs = abt.ab_merge_batched(layers)
+        for out, (idx, name, lay) in zip(outs, lays):
+            ref = orc.ab_merge(lay["A_copies"], lay["B_copies"], tau=tau)
+            if expect is None:
+                # literal threshold: sigma_17 and sigma_18 straddle tau*sigma_1 by under 1 %; make sure
+                # the seed leaves a margin that fp32 rounding cannot cross, then demand the same rank
+                kk = ref["k"]
+                margin = min(ref["s"][kk - 1] / (tau * ref["s"][0]) - 1, 1 - ref["s"][kk] / (tau * ref["s"][0]))
+                assert margin > 1e-3, (name, margin)
+            errs = compare(out, ref, expect_k=expect, check_W=(idx == 1))
+            print(name, "tau", tau, "k'", int(out["k"].item()), "sweeps", out["sweeps"], errs)
+
+
+def test_config5_full_layer_set_ranks_and_spectra():
+    """All 48 layers in one batched call in the bench's launch configuration: the selected rank of
+    every layer equals the oracle's (and 192), kept singular values within 1e-4."""
+    table = gen.config5_layers()
+    layers, host_in = [], []
+    for idx, name, m, n, seed in table:
+        lay = gen.merge_layer(m, n, seed)
+        host_in.append(lay)
+        layers.append(dict(A_copies=[dev(a) for a in lay["A_copies"]], B_copies=[dev(b) for b in lay["B_copies"]],
+                           tau=gen.CFG5_TAU_GAP, k_cap=gen.CFG5_K_IN))
+    outs = abt.ab_merge_batched(layers)
+    torch.cuda.synchronize()
+    for (idx, name, m, n, seed), lay, out in zip(table, host_in, outs):
+        s = orc.merged_spectrum(lay["A_copies"], lay["B_copies"], 0)
+        k_ref = orc.select_rank(s, gen.CFG5_TAU_GAP)
+        k = int(out["k"].item())
+        assert k == k_ref == gen.CFG5_GAP_AT, (name, k, k_ref)
+        S = host(out["S"])
+        assert np.max(np.abs(S[:k] - s[:k]) / s[:k]) < TOL, name

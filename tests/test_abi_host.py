@@ -1,0 +1,121 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every symbol the header
+declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from conftest import ROOT
+from paper_2405_01067_amd import binding as abt
+
+HEADER = os.path.join(ROOT, "include", "abtrain.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(abt._LIB_PATH):
+        import __graft_entry__ as ge
+        ge.build()
+    return abt.load()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:const\s+char\s*\*|int|size_t)\s+(\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_header_functions_are_exported(lib):
+    names = declared_functions()
+    assert {"lr_linear_fwd", "lr_linear_bwd", "ab_merge", "ab_merge_batched"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(abt.EXPORTS)
+
+
+def test_status_strings(lib):
+    assert abt.status_string(0) == "ABT_OK"
+    for code in range(-7, 0):
+        s = abt.status_string(code)
+        assert s.startswith("ABT_E"), s
+    assert "unknown" in abt.status_string(-99)
+
+
+def test_workspace_queries(lib):
+    # bf16 forward keeps T on chip: no workspace
+    assert lib.lr_linear_fwd_workspace_bytes(12608, 3072, 768, 192, abt.ABT_BF16) == 0
+    assert lib.lr_linear_fwd_workspace_bytes(64, 256, 256, 32, abt.ABT_F32) >= 64 * 32 * 4
+    b = lib.lr_linear_bwd_workspace_bytes(12608, 3072, 768, 192, abt.ABT_BF16)
+    # A^T, B^T, dT, T and at least one fp32 partial of dA and dB
+    assert b >= 2 * (3072 * 192 + 768 * 192 + 2 * 12608 * 192) + 4 * (3072 + 768) * 192
+    assert b % 256 == 0
+    # unsupported shapes report 0
+    assert lib.lr_linear_bwd_workspace_bytes(128, 100, 768, 192, abt.ABT_BF16) == 0
+    assert lib.lr_linear_bwd_workspace_bytes(128, 128, 128, 416, abt.ABT_BF16) == 0
+    w0 = lib.ab_merge_workspace_bytes(4, 3072, 768, 384, 384, 0)
+    w1 = lib.ab_merge_workspace_bytes(4, 3072, 768, 96, 384, 1)  # same K = 384 by concatenation
+    assert w0 > 0 and w1 > 0
+    assert w0 >= 4 * (3072 + 768) * 384 + 5 * 8 * 384 * 384
+    assert lib.ab_merge_workspace_bytes(0, 10, 10, 32, 32, 0) == 0
+
+
+def test_argument_validation_without_device(lib):
+    buf = ctypes.create_string_buffer(4096 + 256)
+    base = (ctypes.addressof(buf) + 255) // 256 * 256          # fake, aligned, never dereferenced
+    p = ctypes.c_void_p(base)
+    null = ctypes.c_void_p(0)
+    odd = ctypes.c_void_p(base + 2)
+    f = lib.lr_linear_fwd
+    assert f(null, p, p, p, null, 64, 256, 256, 32, abt.ABT_BF16, null, 0, null) == -1      # EINVAL
+    assert f(p, p, p, p, null, 64, 256, 256, 32, 7, null, 0, null) == -5                    # EDTYPE
+    assert f(p, p, p, p, null, 0, 256, 256, 32, abt.ABT_BF16, null, 0, null) == -2          # ESHAPE
+    assert f(p, p, p, p, null, 64, 250, 256, 32, abt.ABT_BF16, null, 0, null) == -2
+    assert f(p, p, p, p, null, 64, 256, 256, 48, abt.ABT_BF16, null, 0, null) == -2
+    assert f(p, p, p, p, null, 64, 256, 256, 512, abt.ABT_BF16, null, 0, null) == -2
+    assert f(odd, p, p, p, null, 64, 256, 256, 32, abt.ABT_BF16, null, 0, null) == -3       # EALIGN
+    assert f(p, p, p, p, null, 64, 256, 256, 32, abt.ABT_F32, null, 0, null) == -4          # EWORKSPACE (T needs a home)
+    g = lib.lr_linear_bwd
+    assert g(p, p, p, p, p, p, p, p, 64, 256, 256, 32, abt.ABT_BF16, 0, null, 0, null) == -4
+    assert g(null, p, p, p, p, p, p, p, 64, 256, 256, 32, abt.ABT_BF16, 0, p, 1 << 30, null) == -1
+    assert g(p, p, p, p, p, p, p, p, 64, 256, 256, 33, abt.ABT_BF16, 0, p, 1 << 30, null) == -2
+
+    ptrs = (ctypes.c_void_p * 2)(base, base)
+    pp = ctypes.cast(ptrs, ctypes.POINTER(ctypes.c_void_p))
+    h = lib.ab_merge
+    ok_args = dict(G=2, m=64, n=64, k=32, tau=0.1, k_fixed=0, mode=0)
+
+    def call(**kw):
+        a = dict(ok_args); a.update(kw)
+        return h(pp, pp, a["G"], a["m"], a["n"], a["k"], a["tau"], a["k_fixed"], a["mode"],
+                 a.get("A_out", p), p, p, p, a.get("k_cap", 32), null, a.get("ws", null), a.get("wsb", 0), null)
+
+    assert call() == -4                       # no workspace
+    assert call(G=0) == -1
+    assert call(tau=1.5) == -1
+    assert call(tau=-0.1) == -1
+    assert call(mode=2) == -1
+    assert call(k=40) == -2
+    assert call(k=1024, G=4, mode=1) == -2    # K = G k > 2048
+    assert call(k_cap=0) == -2
+    assert call(A_out=null) == -1
+    assert call(A_out=odd) == -3
+    assert call(ws=odd, wsb=1 << 40) == -3
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+    x = torch.zeros(4, 64, dtype=torch.bfloat16)
+    a = torch.zeros(64, 32, dtype=torch.bfloat16)
+    b = torch.zeros(32, 64, dtype=torch.bfloat16)
+    with pytest.raises(abt.AbtError):
+        abt.lr_linear_fwd(x, a, b)
+    with pytest.raises(abt.AbtError):
+        abt.ab_merge([a.float()], [b.float()], tau=0.1)
+
+
+def test_sweep_cap_setter(lib):
+    prev = abt.set_jacobi_max_sweeps(5)
+    assert abt.set_jacobi_max_sweeps(1000) == 5
+    assert abt.set_jacobi_max_sweeps(prev) == 64

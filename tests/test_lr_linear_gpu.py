@@ -1,0 +1,187 @@
+"""Parity of the HIP factored-layer step (lr_linear_fwd / lr_linear_bwd, through the C ABI)
+against the CPU oracle, element by element on the same seeded inputs.
+
+Tolerances (relative Frobenius error): 1e-2 for the bf16 path, 1e-4 for the fp32 path.
+At the full benchmark sizes the oracle is evaluated on sampled rows (Y, dX are row-independent)
+and on sampled columns of dA / rows of dB (each needs only one column of T / dT)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ab_oracle as orc
+from paper_2405_01067_amd import binding as abt
+from paper_2405_01067_amd import inputs as gen
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 1e-2
+TOL_F32 = 1e-4
+
+
+def rel(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def dev(x, dtype):
+    return torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0").to(dtype)
+
+
+def host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def run_step(c, dtype, **bwd_kw):
+    X, dY, A, B = (dev(c[k], dtype) for k in ("X", "dY", "A", "B"))
+    Y, T = abt.lr_linear_fwd(X, A, B, save_T=True)
+    dX, dA, dB = abt.lr_linear_bwd(dY, X, T, A, B, **bwd_kw)
+    torch.cuda.synchronize()
+    return X, dY, A, B, Y, T, dX, dA, dB
+
+
+def check_full(c, dtype, tol):
+    X, dY, A, B, Y, T, dX, dA, dB = run_step(c, dtype)
+    Yo, To = orc.lr_linear_fwd(c["X"], c["A"], c["B"])
+    dXo, dAo, dBo, _ = orc.lr_linear_bwd(c["dY"], c["X"], c["A"], c["B"])
+    errs = {"T": rel(host(T), To), "Y": rel(host(Y), Yo), "dX": rel(host(dX), dXo),
+            "dA": rel(host(dA), dAo), "dB": rel(host(dB), dBo)}
+    assert all(e < tol for e in errs.values()), errs
+    return errs
+
+
+# ------------------------------------------------------------------ config 1 (fp32)
+
+def test_config1_fp32_step():
+    c1 = gen.config1_dense(0)
+    A, B, _, _ = orc.ab_decomposition(c1["W"], k=c1["r"])
+    c = {"X": c1["X"], "dY": c1["dY"], "A": A.astype(np.float32), "B": B.astype(np.float32)}
+    check_full(c, torch.float32, TOL_F32)
+
+
+@pytest.mark.parametrize("M,m,n,r", [(1, 8, 8, 1), (130, 200, 72, 24), (257, 129, 131, 33), (300, 64, 640, 160)])
+def test_fp32_ragged_shapes(M, m, n, r):
+    c = gen.lr_case(M, m, n, r, seed=M + r, bf16=False, dy_std=1.0)
+    check_full(c, torch.float32, TOL_F32)
+
+
+# ------------------------------------------------------------------ bf16: every rank, several tiles, ragged tail
+
+@pytest.mark.parametrize("r", [32, 64, 96, 128, 160, 192, 224, 256, 288, 320, 352, 384])
+def test_bf16_every_rank(r):
+    c = gen.lr_case(M=128 * 2 + 45, m=192, n=320, r=r, seed=40 + r)
+    check_full(c, torch.bfloat16, TOL_BF16)
+
+
+@pytest.mark.parametrize("M", [1, 31, 32, 33, 127, 128, 129, 1000])
+def test_bf16_row_counts(M):
+    c = gen.lr_case(M=M, m=128, n=64, r=64, seed=900 + M)
+    check_full(c, torch.bfloat16, TOL_BF16)
+
+
+def test_bf16_many_splits_and_wide():
+    # enough rows for several row splits of the dA / dB reduction, wide n and m
+    c = gen.lr_case(M=5000, m=640, n=1216, r=96, seed=77)
+    check_full(c, torch.bfloat16, TOL_BF16)
+
+
+def test_bf16_relu_inputs_half_zero():
+    c = gen.lr_case(M=777, m=256, n=1152, r=64, seed=78, relu_x=True)
+    assert 0.45 < np.mean(c["X"] == 0) < 0.55
+    check_full(c, torch.bfloat16, TOL_BF16)
+
+
+# ------------------------------------------------------------------ options
+
+def test_bwd_skips_accumulate_recompute_and_determinism():
+    c = gen.lr_case(M=700, m=256, n=192, r=96, seed=5)
+    X, dY, A, B, Y, T, dX, dA, dB = run_step(c, torch.bfloat16)
+    # frozen-factor variants: a group that trains A skips dB and vice versa
+    dX2, dA2, dB2 = abt.lr_linear_bwd(dY, X, T, A, B, need_dB=False)
+    assert dB2 is None and torch.equal(dA2, dA) and torch.equal(dX2, dX)
+    dX3, dA3, dB3 = abt.lr_linear_bwd(dY, X, T, A, B, need_dA=False, need_dX=False)
+    assert dA3 is None and dX3 is None and torch.equal(dB3, dB)
+    # T = None: recomputed from X and B, same values the forward saved
+    dX4, dA4, dB4 = abt.lr_linear_bwd(dY, X, None, A, B)
+    assert torch.equal(dA4, dA) and torch.equal(dB4, dB) and torch.equal(dX4, dX)
+    # accumulate adds into existing gradients
+    accA, accB = dA.clone(), dB.clone()
+    abt.lr_linear_bwd(dY, X, T, A, B, need_dX=False, dA=accA, dB=accB, accumulate=True)
+    torch.cuda.synchronize()
+    assert rel(host(accA), 2 * host(dA)) < 1e-6 and rel(host(accB), 2 * host(dB)) < 1e-6
+    # forward without saving T gives the same Y
+    Y2, T2 = abt.lr_linear_fwd(X, A, B, save_T=False)
+    assert T2 is None and torch.equal(Y2, Y)
+    # bit-identical reruns (fixed split and summation order)
+    for _ in range(3):
+        _, _, _, _, Yr, Tr, dXr, dAr, dBr = run_step(c, torch.bfloat16)
+        assert torch.equal(Yr, Y) and torch.equal(dXr, dX) and torch.equal(dAr, dA) and torch.equal(dBr, dB)
+
+
+def test_saved_T_is_what_stage_two_consumed():
+    # T_save holds T rounded to bf16; Y must equal the oracle's second product applied to exactly it
+    c = gen.lr_case(M=200, m=128, n=256, r=64, seed=9)
+    X, dY, A, B, Y, T, *_ = run_step(c, torch.bfloat16)
+    Y_from_T = host(T) @ c["A"].astype(np.float64).T
+    assert rel(host(Y), Y_from_T) < 3e-3      # only the final bf16 rounding of Y remains
+
+
+def test_fp32_options():
+    c = gen.lr_case(M=150, m=96, n=80, r=16, seed=3, bf16=False, dy_std=1.0)
+    X, dY, A, B, Y, T, dX, dA, dB = run_step(c, torch.float32)
+    dX4, dA4, dB4 = abt.lr_linear_bwd(dY, X, None, A, B)
+    torch.cuda.synchronize()
+    assert torch.equal(dA4, dA) and torch.equal(dB4, dB)
+    accA = dA.clone()
+    abt.lr_linear_bwd(dY, X, T, A, B, need_dX=False, need_dB=False, dA=accA, accumulate=True)
+    torch.cuda.synchronize()
+    assert rel(host(accA), 2 * host(dA)) < 1e-6
+
+
+# ------------------------------------------------------------------ full benchmark sizes, sampled oracle
+
+def sampled_check(c, tol, n_rows=384, n_cols=8, seed=0):
+    M, m, n, r = c["M"], c["m"], c["n"], c["r"]
+    X, dY, A, B, Y, T, dX, dA, dB = run_step(c, torch.bfloat16)
+    rng = np.random.default_rng(seed)
+    rows = np.unique(np.concatenate([np.arange(0, 40), np.arange(M - 70, M),
+                                     rng.integers(0, M, size=n_rows)]))
+    A64, B64 = c["A"].astype(np.float64), c["B"].astype(np.float64)
+    Yo, To = orc.lr_linear_fwd(c["X"][rows], A64, B64)
+    dXo, _, _, dTo = orc.lr_linear_bwd(c["dY"][rows], c["X"][rows], A64, B64)
+    errs = {"T": rel(host(T[rows]), To), "Y": rel(host(Y[rows]), Yo), "dX": rel(host(dX[rows]), dXo)}
+    # dA[:, j] = dY^T T[:, j] and dB[i, :] = dT[:, i]^T X need one column of T / dT over ALL rows:
+    # the oracle's own products restricted to that column (B[j,:] resp. A[:, i])
+    js = np.unique(np.concatenate([[0, r - 1], rng.integers(0, r, size=n_cols)]))
+    # with A, B restricted to the columns/rows js, T and dT restrict the same way
+    # (T[:, js] = X B[js]^T, dT[:, js] = dY A[:, js]), so the oracle returns dA[:, js] and dB[js, :]
+    _, dA_cols, dB_rows, _ = orc.lr_linear_bwd(c["dY"], c["X"], A64[:, js], B64[js, :])
+    errs["dA"] = rel(host(dA[:, js]), dA_cols)
+    errs["dB"] = rel(host(dB[js, :]), dB_rows)
+    assert all(e < tol for e in errs.values()), errs
+    return errs
+
+
+def test_config2_full_size():
+    c = gen.config2()
+    assert (c["M"], c["m"], c["n"], c["r"]) == (12608, 3072, 768, 192)
+    errs = check_full(c, torch.bfloat16, TOL_BF16)
+    print("config 2 errors:", errs)
+
+
+@pytest.mark.parametrize("case", [cs for cs in gen.config3_cases()
+                                  if cs[0] in ("qkv_r96", "proj_r384", "fc1_r192", "fc2_r192", "fc1_r384")],
+                         ids=lambda cs: cs[0])
+def test_config3_full_size_sampled(case):
+    name, M, m, n, r, seed = case
+    c = gen.lr_case(M, m, n, r, seed)
+    errs = sampled_check(c, TOL_BF16, seed=seed)
+    print(name, errs)
+
+
+@pytest.mark.parametrize("case", gen.config4_cases(), ids=lambda cs: cs[0])
+def test_config4_full_size_sampled(case):
+    name, M, m, n, r, seed = case
+    c = gen.lr_case(M, m, n, r, seed, relu_x=True)
+    errs = sampled_check(c, TOL_BF16, seed=seed)
+    print(name, errs)
