@@ -1,5 +1,6 @@
 // C ABI of the library: argument validation, workspace carving and the launch sequences.
 // Every operation is documented in include/abtrain.h.
+#include <cstdlib>
 #include <vector>
 
 #include "common.h"
@@ -9,6 +10,15 @@ using namespace abt;
 namespace {
 
 int g_max_sweeps = 16;
+
+// Chain kernel choice: the 64-row / 8-wave kernel wherever it supports the rank, else the
+// 128-row kernel.  ABT_CHAIN=1 in the environment forces the 128-row kernel (for comparisons).
+hipError_t chain(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
+                 int64_t M, int p, int q, int R, hipStream_t s) {
+    static const int forced = [] { const char* e = getenv("ABT_CHAIN"); return e ? atoi(e) : 0; }();
+    if (forced != 1 && chain2_supports(R, p)) return launch_chain2_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
+    return launch_chain_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
+}
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline size_t esize(int dt) { return dt == ABT_BF16 ? 2 : 4; }
@@ -118,7 +128,7 @@ int lr_linear_fwd(const void* X, const void* A, const void* B, void* Y, void* T_
         return ABT_EALIGN;
     hipStream_t s = (hipStream_t)stream;
     if (dt == ABT_BF16) {
-        return launch_chain_bf16(X, B, A, Y, T_save, M, (int)n, (int)m, (int)r, s) == hipSuccess ? ABT_OK : ABT_EHIP;
+        return chain(X, B, A, Y, T_save, M, (int)n, (int)m, (int)r, s) == hipSuccess ? ABT_OK : ABT_EHIP;
     }
     float* T = (float*)T_save;
     if (!T) {
@@ -174,7 +184,7 @@ int lr_linear_bwd(const void* dY, const void* X, const void* T, const void* A, c
     const void* Tp = T;
     hipError_t e = hipSuccess;
     if (!Tp && dA) {  // recompute T = X B^T (first stage of the chain only)
-        e = launch_chain_bf16(X, B, nullptr, nullptr, ws + w.T, M, (int)n, (int)m, (int)r, s);
+        e = chain(X, B, nullptr, nullptr, ws + w.T, M, (int)n, (int)m, (int)r, s);
         if (e != hipSuccess) return ABT_EHIP;
         Tp = ws + w.T;
     }
@@ -186,7 +196,7 @@ int lr_linear_bwd(const void* dY, const void* X, const void* T, const void* A, c
             e = launch_transpose_bf16(B, Bt, (int)r, (int)n, s);
             if (e != hipSuccess) return ABT_EHIP;
         }
-        e = launch_chain_bf16(dY, At, dX ? Bt : nullptr, dX, dT, M, (int)m, (int)n, (int)r, s);
+        e = chain(dY, At, dX ? Bt : nullptr, dX, dT, M, (int)m, (int)n, (int)r, s);
         if (e != hipSuccess) return ABT_EHIP;
     }
     TnJob jobs[2];

@@ -37,6 +37,11 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // Yout or Tout may be NULL.  p, q multiples of 64; R in {32..384 step 32}.
 hipError_t launch_chain_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                              int64_t M, int p, int q, int R, hipStream_t s);
+// The same chain with 64-row work-groups, 8 waves and direct-to-LDS slab rings; covers
+// R in {32, 64, 96, 128, 192, 256, 384} (chain2_supports).
+bool chain2_supports(int R, int p);
+hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
+                              int64_t M, int p, int q, int R, hipStream_t s);
 // dst[c, r] = src[r, c] for a bf16 matrix of `rows` x `cols`.
 hipError_t launch_transpose_bf16(const void* src, void* dst, int rows, int cols, hipStream_t s);
 // part[split][P,Q] = U[rows of split, P]^T . V[rows of split, Q]  (bf16 in, fp32 partials)

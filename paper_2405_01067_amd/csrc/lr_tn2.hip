@@ -1,0 +1,313 @@
+// Factor gradients of the factored layer (bf16 in, fp32 out):
+//     dA[m,R] = dY[M,m]^T . T[M,R]          dB[R,n] = dT[M,R]^T . X[M,n]
+// Both are contractions over the M batch rows, the slow dimension of every operand.  One generic
+// job:  part[split][P,R] = U[rows of split, P]^T . V[rows of split, R]   (dA: U = dY, V = T;
+// dB: U = X, V = dT, result stored transposed), followed by a fixed-order sum over the splits.
+//
+// Work-group: 128 columns of U x all R columns of V, 4 waves, slabs of 32 batch rows.  Slabs go
+// global -> LDS with direct-to-LDS loads exactly as they lie in memory (batch row major), through
+// a ring of three; the MFMA operands, which need 8 consecutive batch rows per lane, are read with
+// the transposing LDS load of gfx950 (ds_read_b64_tr_b16): in every group of 16 lanes, lane s
+// supplies the address of 4 consecutive columns of batch row k0 + s/4 (columns 4 (s%4) ..), and
+// lane l receives column l of the four rows k0 .. k0+3.
+// LDS rows are a multiple of 256 bytes; their 64-byte units are XOR-swizzled with the low two bits
+// of the row, so the four rows one transposing load touches lie in different banks.
+#include "common.h"
+
+namespace abt {
+
+namespace {
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+__device__ __forceinline__ void dma16(const void* g, unsigned char* lds_block) {
+    const uint32_t off = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void*)lds_block);
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(off) : "memory");
+}
+__device__ __forceinline__ void wait_vm(int n) {
+#define ABT_VM(N) case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
+    switch (n) {
+        ABT_VM(0) ABT_VM(1) ABT_VM(2) ABT_VM(3) ABT_VM(4) ABT_VM(5) ABT_VM(6) ABT_VM(7) ABT_VM(8)
+        ABT_VM(9) ABT_VM(10) ABT_VM(11) ABT_VM(12) ABT_VM(13) ABT_VM(14) ABT_VM(15) ABT_VM(16)
+        ABT_VM(17) ABT_VM(18) ABT_VM(19) ABT_VM(20)
+        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    }
+#undef ABT_VM
+}
+__device__ __forceinline__ void ring_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+__device__ __forceinline__ f32x16 mfma16(u32x4 a, u32x4 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+// transposing LDS read: 4 x b16 for this lane (see the header comment)
+__device__ __forceinline__ u32x2 ds_tr(const unsigned char* p) {
+    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(lds_void*)p);
+    return __builtin_bit_cast(u32x2, v);
+}
+
+constexpr int TP = 128;      // U columns per work-group
+constexpr int BKM = 32;      // batch rows per slab
+constexpr int NST = 3;       // ring depth
+constexpr int UPITCH = TP * 2;
+
+template <int R>
+struct Tn2 {
+    static constexpr int RB = R / 32;
+    static constexpr bool even = (RB % 2) == 0;
+    static constexpr int WGP = even ? 2 : 4, WGQ = even ? 2 : 1;
+    static constexpr int PB = even ? 2 : 1, QB = even ? RB / 2 : RB;
+    static constexpr int RP = (R + 127) / 128 * 128;        // padded V columns in LDS
+    static constexpr int VPITCH = RP * 2;
+    static constexpr int slab = BKM * (UPITCH + VPITCH);
+    static constexpr int lds_bytes = NST * slab;
+    static constexpr int NIU = BKM * (TP / 8) / 64;          // wave instructions for the U part
+    static constexpr int NIV = BKM * (RP / 8) / 64;
+    static constexpr int LPW = (NIU + NIV) / 4;              // per wave
+};
+
+struct Tn2Job { const uint16_t* U; const uint16_t* V; float* part; int P; int tile_begin; int transposed; };
+struct Tn2Args { Tn2Job job[2]; int njobs; int64_t M; int64_t rows_per_split; };
+
+template <int R>
+__global__ __launch_bounds__(256) void tn2_bf16_kernel(Tn2Args args) {
+    extern __shared__ __align__(1024) unsigned char lds[];
+    using C = Tn2<R>;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lj = lane & 31, lh = lane >> 5;
+
+    const int jid = (args.njobs > 1 && (int)blockIdx.x >= args.job[1].tile_begin) ? 1 : 0;
+    const Tn2Job job = args.job[jid];
+    const int p0 = ((int)blockIdx.x - job.tile_begin) * TP;
+    const int64_t k_begin = (int64_t)blockIdx.y * args.rows_per_split;
+    int64_t k_end = k_begin + args.rows_per_split;
+    if (k_end > args.M) k_end = args.M;
+    const int64_t nrows = k_end > k_begin ? k_end - k_begin : 0;
+    const int nslab = (int)((nrows + BKM - 1) / BKM);
+
+    const int wp = (wave / C::WGQ) * (C::PB * 32);
+    const int wq = (wave % C::WGQ) * (C::QB * 32);
+
+    f32x16 acc[C::PB][C::QB];
+#pragma unroll
+    for (int a = 0; a < C::PB; ++a)
+#pragma unroll
+        for (int b = 0; b < C::QB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+
+    // Every lane always loads from a valid address (rows and columns are clamped), so each wave
+    // issues exactly LPW transfers per slab and the vmcnt bookkeeping stays uniform.  Junk that lands
+    // in padding columns is never read; junk rows past the end of the split are zeroed below.
+    auto issue = [&](int s) {
+        unsigned char* base = lds + (s % NST) * C::slab;
+        const int64_t kr0 = k_begin + (int64_t)s * BKM;
+#pragma unroll
+        for (int e = 0; e < C::LPW; ++e) {
+            const int inst = e * 4 + wave;
+            const uint16_t* g;
+            if (inst < C::NIU) {
+                const int li = inst * 64 + lane;
+                const int row = li / (TP / 8), cpos = li % (TP / 8);
+                const int gc = (((cpos >> 2) ^ (row & 3)) << 2) | (cpos & 3);   // un-swizzled source chunk
+                int64_t kr = kr0 + row;
+                if (kr >= args.M) kr = args.M - 1;
+                int col = p0 + gc * 8;
+                if (col >= job.P) col = job.P - 8;
+                g = job.U + kr * job.P + col;
+            } else {
+                const int li = (inst - C::NIU) * 64 + lane;
+                const int row = li / (C::RP / 8), cpos = li % (C::RP / 8);
+                int gc = (((cpos >> 2) ^ (row & 3)) << 2) | (cpos & 3);
+                if (gc >= R / 8) gc = R / 8 - 1;
+                int64_t kr = kr0 + row;
+                if (kr >= args.M) kr = args.M - 1;
+                g = job.V + kr * R + gc * 8;
+            }
+            dma16(g, base + inst * 1024);
+        }
+    };
+
+    for (int s = 0; s < NST - 1 && s < nslab; ++s) issue(s);
+    for (int s = 0; s < nslab; ++s) {
+        int ahead = nslab - 1 - s;
+        if (ahead > NST - 2) ahead = NST - 2;
+        wait_vm(ahead * C::LPW);
+        ring_barrier();
+        if (s + NST - 1 < nslab) issue(s + NST - 1);
+        unsigned char* base = lds + (s % NST) * C::slab;
+        const int valid = (int)((nrows - (int64_t)s * BKM) < BKM ? (nrows - (int64_t)s * BKM) : BKM);
+        if (valid < BKM) {   // ragged last slab: rows past the end of the split must contribute zero
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            for (int i = tid; i < (BKM - valid) * ((UPITCH + C::VPITCH) / 16); i += 256) {
+                const int row = valid + i / ((UPITCH + C::VPITCH) / 16), c = i % ((UPITCH + C::VPITCH) / 16);
+                unsigned char* dst = c < UPITCH / 16 ? base + row * UPITCH + c * 16
+                                                     : base + BKM * UPITCH + row * C::VPITCH + (c - UPITCH / 16) * 16;
+                *reinterpret_cast<u32x4*>(dst) = z;
+            }
+            __syncthreads();
+        }
+        const unsigned char* ub = base;
+        const unsigned char* vb = base + BKM * UPITCH;
+        // per lane: group g = lane / 16 selects (column half, row half); s = lane % 16
+        const int ls = lane & 15, lg = lane >> 4;
+        const int tr_row = 8 * (lg >> 1) + (ls >> 2);        // + 16 k16 + 4 rd
+        const int tr_col = 16 * (lg & 1) + 4 * (ls & 3);     // + block column
+#pragma unroll
+        for (int k16 = 0; k16 < BKM / 16; ++k16) {
+            u32x4 uf[C::PB], vf[C::QB];
+#pragma unroll
+            for (int a = 0; a < C::PB; ++a) {
+                const int col = wp + a * 32 + tr_col;
+                u32x2 r0, r1;
+                {
+                    const int row = 16 * k16 + tr_row;
+                    r0 = ds_tr(ub + row * UPITCH + (((col >> 5) ^ (row & 3)) << 6) + (col & 31) * 2);
+                    const int row1 = row + 4;
+                    r1 = ds_tr(ub + row1 * UPITCH + (((col >> 5) ^ (row1 & 3)) << 6) + (col & 31) * 2);
+                }
+                uf[a] = u32x4{r0[0], r0[1], r1[0], r1[1]};
+            }
+#pragma unroll
+            for (int b = 0; b < C::QB; ++b) {
+                const int col = wq + b * 32 + tr_col;
+                const int row = 16 * k16 + tr_row, row1 = row + 4;
+                const u32x2 r0 = ds_tr(vb + row * C::VPITCH + ((((col >> 5) & ~3) | (((col >> 5) & 3) ^ (row & 3))) << 6) + (col & 31) * 2);
+                const u32x2 r1 = ds_tr(vb + row1 * C::VPITCH + ((((col >> 5) & ~3) | (((col >> 5) & 3) ^ (row1 & 3))) << 6) + (col & 31) * 2);
+                vf[b] = u32x4{r0[0], r0[1], r1[0], r1[1]};
+            }
+#pragma unroll
+            for (int a = 0; a < C::PB; ++a)
+#pragma unroll
+                for (int b = 0; b < C::QB; ++b) acc[a][b] = mfma16(uf[a], vf[b], acc[a][b]);
+        }
+    }
+
+    // accumulator v of block (a,b): U column p0 + wp + 32a + 8(v/4) + 4 lh + v%4, V column wq + 32b + lj
+    float* part = job.part + (int64_t)blockIdx.y * job.P * R;
+#pragma unroll
+    for (int a = 0; a < C::PB; ++a)
+#pragma unroll
+        for (int b = 0; b < C::QB; ++b) {
+            const int rcol = wq + b * 32 + lj;
+            if (job.transposed) {      // part laid out [R, P]: four consecutive P per lane
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int prow = p0 + wp + a * 32 + 8 * g + 4 * lh;
+                    if (prow < job.P) {
+                        f32x4 o = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
+                        *reinterpret_cast<f32x4*>(part + (int64_t)rcol * job.P + prow) = o;
+                    }
+                }
+            } else {                   // part laid out [P, R]
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int prow = p0 + wp + a * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                    if (prow < job.P) part[(int64_t)prow * R + rcol] = acc[a][b][v];
+                }
+            }
+        }
+}
+
+// out (+)= sum over splits of part[split], element-wise (part already has the layout of out).
+struct Red2Job { const float* part; float* out; int64_t total; };
+struct Red2Args { Red2Job job[2]; int njobs; int splits; int accumulate; int blocks0; };
+
+__global__ __launch_bounds__(256) void tn2_reduce_kernel(Red2Args a) {
+    const int jid = (a.njobs > 1 && (int)blockIdx.x >= a.blocks0) ? 1 : 0;
+    const Red2Job j = a.job[jid];
+    const int64_t idx = ((int64_t)((int)blockIdx.x - (jid ? a.blocks0 : 0)) * 256 + threadIdx.x) * 4;
+    if (idx >= j.total) return;   // totals are multiples of 4 (R % 32 == 0)
+    f32x4 sum = *reinterpret_cast<const f32x4*>(j.part + idx);
+    for (int s = 1; s < a.splits; ++s) sum += *reinterpret_cast<const f32x4*>(j.part + (int64_t)s * j.total + idx);
+    if (a.accumulate) sum += *reinterpret_cast<const f32x4*>(j.out + idx);
+    *reinterpret_cast<f32x4*>(j.out + idx) = sum;
+}
+
+int tn2_total_tiles(const TnJob* jobs, int njobs) {
+    int tiles = 0;
+    for (int i = 0; i < njobs; ++i) tiles += (jobs[i].P + TP - 1) / TP;
+    return tiles;
+}
+
+int tn2_choose_splits(int64_t M, int total_tiles) {
+    // two 4-wave work-groups fit on a compute unit, but every work-group writes one fp32 partial
+    // tile: aim at 1.5 work-groups per compute unit, at least 8 slabs each
+    int64_t want = (384 + total_tiles - 1) / total_tiles;
+    int64_t max_by_rows = M / (8 * BKM);
+    if (max_by_rows < 1) max_by_rows = 1;
+    if (want > max_by_rows) want = max_by_rows;
+    if (want < 1) want = 1;
+    if (want > 64) want = 64;
+    return (int)want;
+}
+
+template <int R>
+hipError_t launch_tn2_r(const Tn2Args& args, int tiles, int splits, hipStream_t s) {
+    constexpr int lds_bytes = Tn2<R>::lds_bytes;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tn2_bf16_kernel<R>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(tn2_bf16_kernel<R>, dim3(tiles, splits), dim3(256), lds_bytes, s, args);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+size_t tn_partials_bytes(int64_t M, const TnJob* jobs, int njobs, int R) {
+    const int splits = tn2_choose_splits(M, tn2_total_tiles(jobs, njobs));
+    size_t elems = 0;
+    for (int i = 0; i < njobs; ++i) elems += (size_t)jobs[i].P * R;
+    return elems * splits * sizeof(float);
+}
+
+hipError_t launch_tn_bf16(const TnJob* jobs, int njobs, int64_t M, int R, int accumulate,
+                          float* partials, hipStream_t s) {
+    if (njobs < 1 || njobs > 2) return hipErrorInvalidValue;
+    const int tiles = tn2_total_tiles(jobs, njobs);
+    const int splits = tn2_choose_splits(M, tiles);
+    Tn2Args args{};
+    Red2Args red{};
+    args.njobs = red.njobs = njobs;
+    args.M = M;
+    int64_t rps = ceil_div(M, splits);
+    rps = ceil_div(rps, BKM) * BKM;
+    args.rows_per_split = rps;
+    red.splits = splits; red.accumulate = accumulate;
+    float* part = partials;
+    int tile_begin = 0, red_blocks = 0;
+    for (int i = 0; i < njobs; ++i) {
+        args.job[i].U = (const uint16_t*)jobs[i].U;
+        args.job[i].V = (const uint16_t*)jobs[i].V;
+        args.job[i].part = part;
+        args.job[i].P = jobs[i].P;
+        args.job[i].tile_begin = tile_begin;
+        args.job[i].transposed = jobs[i].transposed;
+        red.job[i].part = part;
+        red.job[i].out = jobs[i].out;
+        red.job[i].total = (int64_t)jobs[i].P * R;
+        tile_begin += (jobs[i].P + TP - 1) / TP;
+        const int blocks = (int)ceil_div((int64_t)jobs[i].P * R / 4, 256);
+        if (i == 0) red.blocks0 = blocks;
+        red_blocks += blocks;
+        part += (size_t)jobs[i].P * R * splits;
+    }
+    hipError_t e;
+    switch (R) {
+#define ABT_CASE(RR) case RR: e = launch_tn2_r<RR>(args, tiles, splits, s); break;
+        ABT_CASE(32) ABT_CASE(64) ABT_CASE(96) ABT_CASE(128) ABT_CASE(160) ABT_CASE(192)
+        ABT_CASE(224) ABT_CASE(256) ABT_CASE(288) ABT_CASE(320) ABT_CASE(352) ABT_CASE(384)
+#undef ABT_CASE
+        default: return hipErrorInvalidValue;
+    }
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(tn2_reduce_kernel, dim3(red_blocks), dim3(256), 0, s, red);
+    return hipGetLastError();
+}
+
+}  // namespace abt
