@@ -5,11 +5,13 @@
 // dB: U = X, V = dT, result stored transposed), followed by a fixed-order sum over the splits.
 //
 // Work-group: 128 columns of U x all R columns of V, 4 waves, slabs of 32 batch rows.  Slabs go
-// global -> LDS with direct-to-LDS loads exactly as they lie in memory (batch row major), through
-// a ring of three; the MFMA operands, which need 8 consecutive batch rows per lane, are read with
-// the transposing LDS load of gfx950 (ds_read_b64_tr_b16): in every group of 16 lanes, lane s
-// supplies the address of 4 consecutive columns of batch row k0 + s/4 (columns 4 (s%4) ..), and
-// lane l receives column l of the four rows k0 .. k0+3.
+// global -> registers -> LDS exactly as they lie in memory (batch row major); three slabs are in
+// flight in a ring of three register sets (the slab loop is unrolled by six so that ring and LDS
+// slot indices are compile-time constants), two LDS slots, one barrier per slab.  The MFMA
+// operands, which need 8 consecutive batch rows per lane, are read with the transposing LDS load
+// of gfx950 (ds_read_b64_tr_b16): in every group of 16 lanes, lane s supplies the address of 4
+// consecutive columns of batch row k0 + s/4 (columns 4 (s%4) ..), and lane l receives column l of
+// the four rows k0 .. k0+3.
 // LDS rows are a multiple of 256 bytes; their 64-byte units are XOR-swizzled with the low two bits
 // of the row, so the four rows one transposing load touches lie in different banks.
 #include "common.h"
@@ -21,20 +23,6 @@ namespace {
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-__device__ __forceinline__ void dma16(const void* g, unsigned char* lds_block) {
-    const uint32_t off = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void*)lds_block);
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(off) : "memory");
-}
-__device__ __forceinline__ void wait_vm(int n) {
-#define ABT_VM(N) case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
-    switch (n) {
-        ABT_VM(0) ABT_VM(1) ABT_VM(2) ABT_VM(3) ABT_VM(4) ABT_VM(5) ABT_VM(6) ABT_VM(7) ABT_VM(8)
-        ABT_VM(9) ABT_VM(10) ABT_VM(11) ABT_VM(12) ABT_VM(13) ABT_VM(14) ABT_VM(15) ABT_VM(16)
-        ABT_VM(17) ABT_VM(18) ABT_VM(19) ABT_VM(20)
-        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-    }
-#undef ABT_VM
-}
 __device__ __forceinline__ void ring_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
@@ -49,7 +37,7 @@ __device__ __forceinline__ u32x2 ds_tr(const unsigned char* p) {
 
 constexpr int TP = 128;      // U columns per work-group
 constexpr int BKM = 32;      // batch rows per slab
-constexpr int NST = 3;       // ring depth
+constexpr int NRS = 3;       // register sets (slabs in flight)
 constexpr int UPITCH = TP * 2;
 
 template <int R>
@@ -61,10 +49,9 @@ struct Tn2 {
     static constexpr int RP = (R + 127) / 128 * 128;        // padded V columns in LDS
     static constexpr int VPITCH = RP * 2;
     static constexpr int slab = BKM * (UPITCH + VPITCH);
-    static constexpr int lds_bytes = NST * slab;
-    static constexpr int NIU = BKM * (TP / 8) / 64;          // wave instructions for the U part
-    static constexpr int NIV = BKM * (RP / 8) / 64;
-    static constexpr int LPW = (NIU + NIV) / 4;              // per wave
+    static constexpr int lds_bytes = 2 * slab;
+    static constexpr int NU = BKM * (TP / 8) / 256;          // 16-byte chunks per thread, U part
+    static constexpr int NV = (BKM * (R / 8) + 255) / 256;   // V part (the last one may be partial)
 };
 
 struct Tn2Job { const uint16_t* U; const uint16_t* V; float* part; int P; int tile_begin; int transposed; };
@@ -97,63 +84,76 @@ __global__ __launch_bounds__(256) void tn2_bf16_kernel(Tn2Args args) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
-    // Every lane always loads from a valid address (rows and columns are clamped), so each wave
-    // issues exactly LPW transfers per slab and the vmcnt bookkeeping stays uniform.  Junk that lands
-    // in padding columns is never read; junk rows past the end of the split are zeroed below.
-    auto issue = [&](int s) {
-        unsigned char* base = lds + (s % NST) * C::slab;
+    // per-thread chunk coordinates
+    int urow[C::NU], uoff[C::NU];
+    const uint16_t* usrc[C::NU];
+    bool uok[C::NU];
+#pragma unroll
+    for (int e = 0; e < C::NU; ++e) {
+        const int ci = e * 256 + tid;
+        urow[e] = ci / (TP / 8);
+        const int ch = ci % (TP / 8);
+        uoff[e] = urow[e] * UPITCH + ((((ch >> 2) ^ (urow[e] & 3)) << 2) | (ch & 3)) * 16;
+        uok[e] = p0 + ch * 8 < job.P;
+        usrc[e] = job.U + (int64_t)urow[e] * job.P + (uok[e] ? p0 + ch * 8 : 0);
+    }
+    int vrow[C::NV], voff[C::NV];
+    const uint16_t* vsrc[C::NV];
+    bool vok[C::NV];
+#pragma unroll
+    for (int e = 0; e < C::NV; ++e) {
+        const int ci = e * 256 + tid;
+        vrow[e] = ci / (R / 8);
+        const int ch = ci % (R / 8);
+        vok[e] = ci < BKM * (R / 8);
+        voff[e] = vrow[e] * C::VPITCH + ((((ch >> 2) ^ (vrow[e] & 3)) << 2) | (ch & 3)) * 16;
+        vsrc[e] = job.V + (int64_t)vrow[e] * R + ch * 8;
+    }
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    u32x4 ur[NRS][C::NU], vr[NRS][C::NV];
+    // rows past the end of the split (ragged last slab) and columns past P load zeros
+    auto load = [&](u32x4 (&du)[C::NU], u32x4 (&dv)[C::NV], int s) {
         const int64_t kr0 = k_begin + (int64_t)s * BKM;
 #pragma unroll
-        for (int e = 0; e < C::LPW; ++e) {
-            const int inst = e * 4 + wave;
-            const uint16_t* g;
-            if (inst < C::NIU) {
-                const int li = inst * 64 + lane;
-                const int row = li / (TP / 8), cpos = li % (TP / 8);
-                const int gc = (((cpos >> 2) ^ (row & 3)) << 2) | (cpos & 3);   // un-swizzled source chunk
-                int64_t kr = kr0 + row;
-                if (kr >= args.M) kr = args.M - 1;
-                int col = p0 + gc * 8;
-                if (col >= job.P) col = job.P - 8;
-                g = job.U + kr * job.P + col;
-            } else {
-                const int li = (inst - C::NIU) * 64 + lane;
-                const int row = li / (C::RP / 8), cpos = li % (C::RP / 8);
-                int gc = (((cpos >> 2) ^ (row & 3)) << 2) | (cpos & 3);
-                if (gc >= R / 8) gc = R / 8 - 1;
-                int64_t kr = kr0 + row;
-                if (kr >= args.M) kr = args.M - 1;
-                g = job.V + kr * R + gc * 8;
-            }
-            dma16(g, base + inst * 1024);
-        }
+        for (int e = 0; e < C::NU; ++e)
+            du[e] = (uok[e] && kr0 + urow[e] < k_end) ? *reinterpret_cast<const u32x4*>(usrc[e] + kr0 * job.P) : zero4;
+#pragma unroll
+        for (int e = 0; e < C::NV; ++e)
+            dv[e] = (vok[e] && kr0 + vrow[e] < k_end) ? *reinterpret_cast<const u32x4*>(vsrc[e] + kr0 * R) : zero4;
+    };
+    auto store = [&](const u32x4 (&su)[C::NU], const u32x4 (&sv)[C::NV], int slot) {
+        unsigned char* base = lds + slot * C::slab;
+#pragma unroll
+        for (int e = 0; e < C::NU; ++e) *reinterpret_cast<u32x4*>(base + uoff[e]) = su[e];
+#pragma unroll
+        for (int e = 0; e < C::NV; ++e)
+            if (vok[e]) *reinterpret_cast<u32x4*>(base + BKM * UPITCH + voff[e]) = sv[e];
     };
 
-    for (int s = 0; s < NST - 1 && s < nslab; ++s) issue(s);
-    for (int s = 0; s < nslab; ++s) {
-        int ahead = nslab - 1 - s;
-        if (ahead > NST - 2) ahead = NST - 2;
-        wait_vm(ahead * C::LPW);
-        ring_barrier();
-        if (s + NST - 1 < nslab) issue(s + NST - 1);
-        unsigned char* base = lds + (s % NST) * C::slab;
-        const int valid = (int)((nrows - (int64_t)s * BKM) < BKM ? (nrows - (int64_t)s * BKM) : BKM);
-        if (valid < BKM) {   // ragged last slab: rows past the end of the split must contribute zero
-            const u32x4 z = {0u, 0u, 0u, 0u};
-            for (int i = tid; i < (BKM - valid) * ((UPITCH + C::VPITCH) / 16); i += 256) {
-                const int row = valid + i / ((UPITCH + C::VPITCH) / 16), c = i % ((UPITCH + C::VPITCH) / 16);
-                unsigned char* dst = c < UPITCH / 16 ? base + row * UPITCH + c * 16
-                                                     : base + BKM * UPITCH + row * C::VPITCH + (c - UPITCH / 16) * 16;
-                *reinterpret_cast<u32x4*>(dst) = z;
-            }
-            __syncthreads();
-        }
+    if (nslab > 0) {
+        load(ur[0], vr[0], 0);
+        store(ur[0], vr[0], 0);
+#pragma unroll
+        for (int d = 1; d <= NRS; ++d)
+            if (d < nslab) load(ur[d % NRS], vr[d % NRS], d);
+    }
+    ring_barrier();
+
+    // per lane: group g = lane / 16 selects (column half, row half); s = lane % 16
+    const int ls = lane & 15, lg = lane >> 4;
+    const int tr_row = 8 * (lg >> 1) + (ls >> 2);        // + 16 k16 + 4 rd
+    const int tr_col = 16 * (lg & 1) + 4 * (ls & 3);     // + block column
+
+    for (int s0 = 0; s0 < nslab; s0 += 6) {
+#pragma unroll
+        for (int d = 0; d < 6; ++d) {
+          const int s = s0 + d;
+          if (s < nslab) {
+            if (s + 1 < nslab) store(ur[(d + 1) % NRS], vr[(d + 1) % NRS], (d + 1) & 1);
+            if (s + 1 + NRS < nslab) load(ur[(d + 1) % NRS], vr[(d + 1) % NRS], s + 1 + NRS);
+            const unsigned char* base = lds + (d & 1) * C::slab;
         const unsigned char* ub = base;
         const unsigned char* vb = base + BKM * UPITCH;
-        // per lane: group g = lane / 16 selects (column half, row half); s = lane % 16
-        const int ls = lane & 15, lg = lane >> 4;
-        const int tr_row = 8 * (lg >> 1) + (ls >> 2);        // + 16 k16 + 4 rd
-        const int tr_col = 16 * (lg & 1) + 4 * (ls & 3);     // + block column
 #pragma unroll
         for (int k16 = 0; k16 < BKM / 16; ++k16) {
             u32x4 uf[C::PB], vf[C::QB];
@@ -181,6 +181,9 @@ __global__ __launch_bounds__(256) void tn2_bf16_kernel(Tn2Args args) {
             for (int a = 0; a < C::PB; ++a)
 #pragma unroll
                 for (int b = 0; b < C::QB; ++b) acc[a][b] = mfma16(uf[a], vf[b], acc[a][b]);
+        }
+            ring_barrier();
+          }
         }
     }
 
