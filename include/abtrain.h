@@ -58,7 +58,7 @@ const char* abt_status_string(int status);
  * X, A, B, Y are of type `dt`.  T_save is optional (NULL = T never leaves the chip in the
  * bf16 path); when given it receives T in type `dt` (bf16: T rounded to nearest-even, the
  * same values the second product consumes).
- * Shapes: M >= 1 arbitrary.  ABT_BF16: m, n multiples of 64, r a multiple of 32, r <= 384.
+ * Shapes: M >= 1 arbitrary.  ABT_BF16: m, n multiples of 64 and <= 2^20, r a multiple of 32, r <= 384.
  *         ABT_F32: any positive m, n, r.
  * Workspace: lr_linear_fwd_workspace_bytes (0 for ABT_BF16).
  * ------------------------------------------------------------------------------------- */

@@ -16,7 +16,7 @@ int g_max_sweeps = 16;
 hipError_t chain(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                  int64_t M, int p, int q, int R, hipStream_t s) {
     static const int forced = [] { const char* e = getenv("ABT_CHAIN"); return e ? atoi(e) : 0; }();
-    if (forced != 1 && chain2_supports(R, p)) return launch_chain2_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
+    if (forced != 1 && chain2_supports(R, p, q)) return launch_chain2_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
     return launch_chain_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
 }
 
@@ -29,6 +29,7 @@ int check_lr_shapes(int64_t M, int64_t m, int64_t n, int64_t r, int dt) {
     if (M > 0x7fffffff || m > 0x7fffffff || n > 0x7fffffff || r > 0x7fffffff) return ABT_ESHAPE;
     if (dt == ABT_BF16) {
         if (m % 64 || n % 64 || r % 32 || r > 384) return ABT_ESHAPE;
+        if (m > (1 << 20) || n > (1 << 20)) return ABT_ESHAPE;   // 32-bit byte offsets inside row blocks
     }
     return ABT_OK;
 }

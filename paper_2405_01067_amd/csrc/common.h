@@ -19,14 +19,32 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kWave = 64;
 
-// fp32 -> bf16 bits, round-to-nearest-even, NaN kept quiet.
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
+// Two fp32 -> packed bf16 (low half = lo), round-to-nearest-even: one v_cvt_pk_bf16_f32 on gfx950.
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// Buffer addressing: a wave-uniform 128-bit descriptor (base, byte count) + wave-uniform byte
+// offset + one 32-bit byte offset per lane.  Accesses past the byte count read zeros / are dropped.
+// Only the per-lane offset is range-checked, not the wave-uniform one.  A byte count beyond
+// kBufMaxBytes is clamped to it: per-lane offsets must stay below that (callers check sizes on the
+// host), and kBufNowhere is a per-lane offset that no descriptor covers.
+using rsrc_t = __amdgpu_buffer_rsrc_t;
+constexpr int kBufMaxBytes = 0x7ffffff0;
+constexpr int kBufNowhere = 0x7ffffff0;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, int64_t bytes) {
+    const int n = bytes > kBufMaxBytes ? kBufMaxBytes : (bytes < 0 ? 0 : (int)bytes);
+    // last word: raw buffer, 32-bit data format field as the gfx9 family expects for untyped access
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, n, 0x00020000);
+}
+__device__ __forceinline__ u32x4 buf_load16(rsrc_t r, int lane_off, int wave_off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, wave_off, 0);
+}
+__device__ __forceinline__ void buf_store16(u32x4 v, rsrc_t r, int lane_off, int wave_off) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, lane_off, wave_off, 0);
 }
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -37,9 +55,10 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // Yout or Tout may be NULL.  p, q multiples of 64; R in {32..384 step 32}.
 hipError_t launch_chain_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                              int64_t M, int p, int q, int R, hipStream_t s);
-// The same chain with 64-row work-groups, 8 waves and direct-to-LDS slab rings; covers
-// R in {32, 64, 96, 128, 192, 256, 384} (chain2_supports).
-bool chain2_supports(int R, int p);
+// The same chain with 64-row work-groups: four MFMA waves fed by four loader waves; covers
+// R in {32, 64, 96, 128, 160, 192, 256, 320, 384} with p a multiple of 64 and p, q <= 2^20
+// (32-bit byte offsets inside a work-group's rows and inside the factors) (chain2_supports).
+bool chain2_supports(int R, int p, int q);
 hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                               int64_t M, int p, int q, int R, hipStream_t s);
 // dst[c, r] = src[r, c] for a bf16 matrix of `rows` x `cols`.

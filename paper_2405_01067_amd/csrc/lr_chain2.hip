@@ -2,32 +2,46 @@
 // (bf16 in, fp32 accumulate).  Forward of the factored layer with (Xin,P,Q) = (X,B,A); the
 // dT/dX half of the backward with (dY, A^T, B^T).
 //
-// A work-group owns 64 rows and runs 8 waves (two per SIMD).
+// A work-group owns 64 rows and runs 8 waves, two per SIMD, in two roles:
+//   4 MFMA waves do all the matrix work: a wave owns all 64 rows (two MFMA row blocks), so every
+//     factor operand it reads from LDS feeds two MFMAs and no operand is read by two waves;
+//   4 loader waves issue every global load: whole slabs (activation and factor parts alike) go
+//     through a ring of register sets, several slabs deep and consumed strictly in issue order,
+//     so the in-order vector-memory counter tells a loader exactly when the oldest slab has
+//     landed.  They also store T and write the finished output tiles.
+//     The depth matters more than who loads: a CU needs roughly 64 KB of loads in flight at all
+//     times to draw its ~50 B/clk from L2 (latency under load is about a thousand cycles); with
+//     slabs fetched only one ahead the loop time was pinned to that latency.
+// The waves meet at one s_barrier per slab; LDS holds two slab slots.
 //
-//   stage 1: slabs of BK1 contraction columns: 64 rows of Xin and the R rows of P.  The waves form
-//            CS column groups x KS contraction groups; a wave keeps a 64 x (R/CS) block of T^T in
-//            accumulators and takes every KS-th k16 step.  The KS partial sums are then added in
-//            a fixed tree order through LDS.
-//   T:       rounded to bf16 once, written as a 64 x R tile to LDS (and to Tout), from where every
-//            wave loads all of it as MFMA operands: T stays in registers for the whole of stage 2.
-//   stage 2: a round produces 256 output columns, 32 per wave, from slabs of 256 rows of Q; the
-//            finished 64 x 256 tile is staged in LDS and leaves as full 512-byte row segments.
-//
-// Slabs travel global -> registers -> LDS (two LDS slots, one barrier per slab).  The factor
-// slabs come out of L2 and are fetched two slabs ahead (two register sets); the activation slab
-// of stage 1 comes from HBM and is fetched six slabs ahead (a ring of six register sets, the slab
-// loop is unrolled by six so that every ring index is a compile-time constant).
-// (The direct-to-LDS loads of gfx950 were measured at about half the rate of this path per wave
-// and are not used.)
+//   stage 1: slabs of 64 contraction columns: 64 rows of Xin and the R rows of P.  The MFMA waves
+//            form CS column groups x KS contraction groups; a wave keeps a 64 x (R/CS) block of
+//            T^T in accumulators and takes every KS-th k16 step.  The KS partial sums are then
+//            added in a fixed tree order through LDS.
+//   T:       rounded to bf16 once, written as a 64 x R tile to LDS (and from there to Tout); every
+//            MFMA wave loads all of it as MFMA operands: T stays in registers for all of stage 2.
+//   stage 2: a slab is 128 rows of Q (all R columns while that fits, else half) and yields a
+//            64 x 128 output tile, 32 columns per MFMA wave; the tile is staged in LDS (two
+//            buffers) and leaves one slab later as full 256-byte row segments.
+// (The direct-to-LDS loads of gfx950 were measured at about half the rate of register-staged
+// loads per wave and are not used.)
 //
 // LDS slab layout: row-major, 16-byte chunks XOR-swizzled inside each row so that the 16 rows a
 // quarter-wave reads for one MFMA operand fall on different banks.
 //
 // MFMA 32x32x16 bf16 layout (lane l, h = l/32): A operand = 8 values A[l%32][8h..8h+7], B operand
 // = B[8h..8h+7][l%32], accumulator v = C[8(v/4) + 4h + v%4][l%32].
-#include <cstdlib>
-
 #include "common.h"
+
+#ifdef ABT_TIMING
+__device__ long long abt_tbuf[2][64];
+#define TMARK(role, i) do { if (blockIdx.x == 5 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 4 : 0)) abt_tbuf[role][i] = __builtin_readcyclecounter(); } while (0)
+__device__ long long abt_tl[2][4][32];
+#define TSTAMP(role, k, it) do { if (blockIdx.x == 5 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 4 : 0) && (it) < 32) abt_tl[role][k][it] = __builtin_readcyclecounter(); } while (0)
+#else
+#define TMARK(role, i) do {} while (0)
+#define TSTAMP(role, k, it) do {} while (0)
+#endif
 
 namespace abt {
 
@@ -38,10 +52,10 @@ __device__ __forceinline__ f32x16 mfma16(u32x4 a, u32x4 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(a), as_bf(b), c, 0, 0, 0);
 }
 
-// Work-group barrier of the slab loops: this wave's LDS traffic has completed, then s_barrier.
-// Deliberately not __syncthreads(): that also drains the outstanding global loads, which are
-// exactly the prefetches that must stay in flight across the barrier.
-__device__ __forceinline__ void ring_barrier() {
+// The only barrier used in this kernel (both roles execute the same sequence of them): this wave's
+// LDS traffic has completed, then s_barrier.  Deliberately not __syncthreads(): that also drains
+// outstanding global loads, which are exactly the prefetches that must stay in flight.
+__device__ __forceinline__ void wg_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
@@ -54,54 +68,285 @@ __device__ __forceinline__ int swz(int chunk, int row) {
     else return chunk ^ ((row >> 2) & 3);
 }
 
+// Work split of the four MFMA waves in stage 1: CS column groups x KS contraction groups.
 template <int R> struct Ch2;
-template <> struct Ch2<32>  { static constexpr int CS = 1, KS = 8, BK1 = 128, BK2 = 32; };
-template <> struct Ch2<64>  { static constexpr int CS = 2, KS = 4, BK1 = 64,  BK2 = 64; };
-template <> struct Ch2<96>  { static constexpr int CS = 1, KS = 8, BK1 = 128, BK2 = 32; };
-template <> struct Ch2<128> { static constexpr int CS = 2, KS = 4, BK1 = 64,  BK2 = 64; };
-template <> struct Ch2<192> { static constexpr int CS = 2, KS = 4, BK1 = 64,  BK2 = 64; };
-template <> struct Ch2<256> { static constexpr int CS = 4, KS = 2, BK1 = 64,  BK2 = 64; };
-template <> struct Ch2<384> { static constexpr int CS = 4, KS = 2, BK1 = 64,  BK2 = 64; };
+template <> struct Ch2<32>  { static constexpr int CS = 1, KS = 4; };
+template <> struct Ch2<64>  { static constexpr int CS = 1, KS = 4; };
+template <> struct Ch2<96>  { static constexpr int CS = 1, KS = 4; };
+template <> struct Ch2<128> { static constexpr int CS = 2, KS = 2; };
+template <> struct Ch2<160> { static constexpr int CS = 1, KS = 4; };
+template <> struct Ch2<192> { static constexpr int CS = 2, KS = 2; };
+template <> struct Ch2<256> { static constexpr int CS = 2, KS = 2; };
+template <> struct Ch2<320> { static constexpr int CS = 2, KS = 2; };
+template <> struct Ch2<384> { static constexpr int CS = 4, KS = 1; };
 
-constexpr int DX = 6;   // activation slabs in flight (register ring); the slab loop is unrolled by DX
+constexpr int NMW = 4, NLW = 4;                 // MFMA waves, loader waves
+constexpr int NMT = 64 * NMW, NLT = 64 * NLW;   // threads per role
+constexpr int NT = NMT + NLT;
+constexpr int BK1 = 64, CPR1 = BK1 / 8;         // stage-1 slab: 64 contraction columns
+constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v / 2); }
+constexpr int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+constexpr int gcdi(int a, int b) { return b == 0 ? a : gcdi(b, a % b); }
 
 template <int R>
-struct Ch2Lds {
+struct Ch2Cfg {
     using C = Ch2<R>;
     static constexpr int CB = R / 32 / C::CS;
-    static constexpr int xslab = 64 * C::BK1 * 2, pslab = R * C::BK1 * 2;
-    static constexpr int stage1 = 2 * (xslab + pslab);
-    static constexpr int qslab = 256 * C::BK2 * 2;
-    static constexpr int ypitch = 256 * 2 + 16;
+    static constexpr int SPW = BK1 / (16 * C::KS);            // k16 steps per wave per slab
+    static constexpr int xpart = 64 * BK1 * 2;                // slot = [64 rows of Xin][R rows of P]
+    static constexpr int slab1 = (64 + R) * BK1 * 2;
+    static constexpr int NCHX = 64 * CPR1 / NLT;              // 16-byte chunks per loader thread (Xin part) = 2
+    static constexpr int NCHP = R * CPR1 / NLT;               // chunks per loader thread (P part) = R / 32
+    static constexpr int D1 = clampi(32 / (NCHX + NCHP), 2, 6);   // stage-1 slabs in flight (register ring depth)
+    // stage 2: a slab is 128 rows of Q times BK2 = R / KSL columns
+    static constexpr int KSL = R <= 224 ? 1 : 2;
+    static constexpr int BK2 = R / KSL, CPR2 = BK2 / 8;
+    static constexpr int slab2 = 128 * BK2 * 2;
+    static constexpr int NCHQ = 128 * CPR2 / NLT;             // chunks per loader thread = BK2 / 16
+    static constexpr int D2 = clampi(36 / NCHQ, 2, 6);        // stage-2 slabs in flight
+    static constexpr int U2 = D2 * KSL / gcdi(D2, KSL);       // stage-2 trip count is padded to a multiple of this
+    static constexpr int ypitch = 128 * 2 + 16;
     static constexpr int ytile = 64 * ypitch;
-    static constexpr int stage2 = 2 * qslab + ytile;
     static constexpr int red = (C::KS / 2) * C::CS * CB * 8192;   // first (largest) round of the tree
     static constexpr int tpitch = R * 2 + 16;
     static constexpr int ttile = 64 * tpitch;
-    static constexpr int mid = red + ttile;
-    static constexpr int ab = stage1 > stage2 ? stage1 : stage2;
-    static constexpr int bytes = ab > mid ? ab : mid;
+    static constexpr int a = 2 * slab1, b = red + ttile, c = 2 * slab2 + 2 * ytile;
+    static constexpr int lds_bytes = a > b ? (a > c ? a : c) : (b > c ? b : c);
+    static constexpr int n_mid_barriers = C::KS > 1 ? 2 * ilog2(C::KS) : 1;  // tree + T tile written
+    static_assert(SPW >= 1 && NCHX == 2 && R % 32 == 0 && BK2 % 16 == 0, "slab shape");
 };
 
 template <int R>
-__global__ __launch_bounds__(512) void chain2_bf16_kernel(const uint16_t* __restrict__ Xin,
-                                                          const uint16_t* __restrict__ Pm,
-                                                          const uint16_t* __restrict__ Qm,
-                                                          uint16_t* __restrict__ Yout,
-                                                          uint16_t* __restrict__ Tout,
-                                                          int64_t M, int p, int q) {
+__global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restrict__ Xin,
+                                                         const uint16_t* __restrict__ Pm,
+                                                         const uint16_t* __restrict__ Qm,
+                                                         uint16_t* __restrict__ Yout,
+                                                         uint16_t* __restrict__ Tout,
+                                                         int64_t M, int p, int q) {
     extern __shared__ __align__(1024) unsigned char lds[];
     using C = Ch2<R>;
-    using L = Ch2Lds<R>;
-    constexpr int CS = C::CS, KS = C::KS, CB = L::CB;
-    constexpr int BK1 = C::BK1, CPR1 = BK1 / 8, SPW = BK1 / (16 * KS);
-    constexpr int NX = 64 * CPR1 / 512;          // 16-byte chunks per thread: activation slab
-    constexpr int NPC = (R * CPR1 + 511) / 512;  // factor slab (the last one may be partial: guarded)
-    static_assert(SPW >= 1 && NX >= 1, "slab shape");
+    using L = Ch2Cfg<R>;
+    constexpr int CS = C::CS, KS = C::KS, CB = L::CB, SPW = L::SPW;
+    constexpr int BK2 = L::BK2, CPR2 = L::CPR2, KSL = L::KSL;
+    constexpr int D1 = L::D1, D2 = L::D2;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int lj = lane & 31, lh = lane >> 5;
     const int64_t row0 = (int64_t)blockIdx.x * 64;
+    const int ns1 = p / BK1;
+    const int n1p = (ns1 + D1 - 1) / D1 * D1;           // stage-1 trip count, padded to the loaders' ring
+    const int ntile = (q + 127) / 128;                  // stage-2 output tiles of 128 columns
+    const int ns2 = ntile * KSL;
+    const int n2p = (ns2 + L::U2 - 1) / L::U2 * L::U2;  // stage-2 trip count, padded likewise
+    unsigned char* const ttile = lds + L::red;
+    unsigned char* const ytile = lds + 2 * L::slab2;
+    // Work-groups walk the contraction slabs (stage 1) and the output tiles (stage 2) from
+    // different starting points, so that at any instant they touch different columns of
+    // Xin / Yout and different rows of the factors.
+    const int rot1 = (int)(blockIdx.x % (unsigned)ns1);
+    const int rot2 = (int)(blockIdx.x % (unsigned)ntile);
+    auto slab1_of = [&](int s) { if (s > ns1 - 1) s = ns1 - 1; s += rot1; return s >= ns1 ? s - ns1 : s; };
+    auto tile_of = [&](int t) { if (t > ntile - 1) t = ntile - 1; t += rot2; return t >= ntile ? t - ntile : t; };
+
+    if (wave >= NMW) {
+        // ================================================================== loader waves
+        // Every global access here is a buffer instruction: a wave-uniform descriptor and scalar
+        // offset plus one 32-bit offset per lane.  Loads addressed by 64-bit per-lane pointers issue
+        // at little more than half the rate while the MFMA waves on the same SIMDs are busy; buffer
+        // loads do not slow down.  The descriptors cover exactly this work-group's valid rows and the
+        // row offset is part of the per-lane offset (the only part the hardware range-checks), so
+        // rows past M read as zeros and stores to them are dropped.
+        const int lt = tid - NMT;
+        const int64_t rows_valid = M - row0 < 64 ? M - row0 : 64;
+        const rsrc_t xres = make_rsrc(Xin + row0 * p, rows_valid * p * 2);
+        const rsrc_t pres = make_rsrc(Pm, (int64_t)R * p * 2);
+        // stage-2 chunk assignment (computed first: the first Q slabs are requested before stage 1's
+        // epilogue so that their latency hides behind the reduction and the T tile)
+        int qoff[L::NCHQ], qsrc[L::NCHQ];
+#pragma unroll
+        for (int e = 0; e < L::NCHQ; ++e) {
+            const int ci = e * NLT + lt;
+            const int row = ci / CPR2, ch = ci % CPR2;
+            qsrc[e] = (row * R + ch * 8) * 2;
+            qoff[e] = row * (BK2 * 2) + swz<CPR2>(ch, row) * 16;
+        }
+        {
+            // stage 1: one ring entry = this thread's chunks of one slab (64 rows of Xin, then the R
+            // rows of P), D1 slabs ahead
+            int xsrc[L::NCHX], off[L::NCHX];
+#pragma unroll
+            for (int e = 0; e < L::NCHX; ++e) {
+                const int ci = e * NLT + lt;
+                const int row = ci / CPR1, ch = ci % CPR1;
+                off[e] = row * (BK1 * 2) + swz<CPR1>(ch, row) * 16;
+                xsrc[e] = (row * p + ch * 8) * 2;
+            }
+            // P chunk e of this thread: row 32 e + lt / 8, chunk lt % 8
+            const int prow0 = lt / CPR1, pch = lt % CPR1;
+            const int psrc = (prow0 * p + pch * 8) * 2;
+            const int pstep = (NLT / CPR1) * p * 2;      // 32 rows of P, in bytes
+            int poff[L::NCHP];
+#pragma unroll
+            for (int e = 0; e < L::NCHP; ++e) {
+                const int row = e * (NLT / CPR1) + prow0;
+                poff[e] = L::xpart + row * (BK1 * 2) + swz<CPR1>(pch, row) * 16;
+            }
+            u32x4 ring[D1][L::NCHX + L::NCHP];
+            auto load = [&](u32x4 (&dst)[L::NCHX + L::NCHP], int s) {
+                const int so = slab1_of(s) * (BK1 * 2);
+#pragma unroll
+                for (int e = 0; e < L::NCHX; ++e) dst[e] = buf_load16(xres, xsrc[e], so);
+#pragma unroll
+                for (int e = 0; e < L::NCHP; ++e) dst[L::NCHX + e] = buf_load16(pres, psrc, so + e * pstep);
+            };
+            auto store = [&](const u32x4 (&srcv)[L::NCHX + L::NCHP], int slot) {
+#pragma unroll
+                for (int e = 0; e < L::NCHX; ++e) *reinterpret_cast<u32x4*>(lds + slot * L::slab1 + off[e]) = srcv[e];
+#pragma unroll
+                for (int e = 0; e < L::NCHP; ++e)
+                    *reinterpret_cast<u32x4*>(lds + slot * L::slab1 + poff[e]) = srcv[L::NCHX + e];
+            };
+            // steady state: chunk e of slab s+1 goes to LDS (slot s&1 is being read) and the same
+            // chunk of slab s+1+D1 is requested, alternating: the LDS port and the vector-memory
+            // address path then both stay busy instead of taking turns
+            auto step1 = [&](u32x4 (&rg)[L::NCHX + L::NCHP], int s) {
+                const int slot = (s + 1) & 1;
+                const int so = slab1_of(s + 1 + D1) * (BK1 * 2);
+#pragma unroll
+                for (int e = 0; e < L::NCHX; ++e) {
+                    *reinterpret_cast<u32x4*>(lds + slot * L::slab1 + off[e]) = rg[e];
+                    rg[e] = buf_load16(xres, xsrc[e], so);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int e = 0; e < L::NCHP; ++e) {
+                    *reinterpret_cast<u32x4*>(lds + slot * L::slab1 + poff[e]) = rg[L::NCHX + e];
+                    rg[L::NCHX + e] = buf_load16(pres, psrc, so + e * pstep);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            load(ring[0], 0);
+            store(ring[0], 0);
+#pragma unroll
+            for (int d = 1; d <= D1; ++d) load(ring[d % D1], d);
+            TMARK(1, 0);
+            wg_barrier();                                   // slab 0 is in slot 0
+            for (int s0 = 0; s0 < n1p; s0 += D1) {
+#pragma unroll
+                for (int d = 0; d < D1; ++d) {
+                    step1(ring[(d + 1) % D1], s0 + d);
+                    wg_barrier();
+                }
+            }
+            TMARK(1, 1);
+        }
+        // stage-2 ring: D2 slabs of Q in flight.  The descriptor is rebuilt per slab (scalar work) to
+        // cover exactly the tile's rows: the wave-uniform offset of a buffer access is not range
+        // checked, only the per-lane part is.  Rows of a ragged last tile that lie past the end of Q
+        // then read as zeros; their output columns are never stored.
+        u32x4 ring2[D2][L::NCHQ];
+        auto load_q = [&](u32x4 (&dst)[L::NCHQ], int s) {
+            if (s > ns2 - 1) s = ns2 - 1;
+            const int t = tile_of(s / KSL);
+            const int rows = q - t * 128 < 128 ? q - t * 128 : 128;
+            const rsrc_t qres = make_rsrc(Qm + (int64_t)t * 128 * R, (int64_t)rows * R * 2);
+            const int so = (s % KSL) * BK2 * 2;
+#pragma unroll
+            for (int e = 0; e < L::NCHQ; ++e) dst[e] = buf_load16(qres, qsrc[e], so);
+        };
+        if (Yout != nullptr) {
+#pragma unroll
+            for (int d = 0; d < D2; ++d) load_q(ring2[d], d);
+        }
+#pragma unroll
+        for (int i = 0; i < L::n_mid_barriers; ++i) wg_barrier();
+        // T tile is in LDS: store it (the MFMA waves load their operands from it meanwhile)
+        if (Tout != nullptr) {
+            const rsrc_t tres = make_rsrc(Tout + row0 * R, rows_valid * R * 2);
+            constexpr int CPT = R / 8;   // 16-byte chunks per T row
+            for (int i = lt; i < 64 * CPT; i += NLT) {
+                const int row = i / CPT, ch = i % CPT;
+                buf_store16(*reinterpret_cast<const u32x4*>(ttile + row * L::tpitch + ch * 16), tres, i * 16, 0);
+            }
+        }
+        if (Yout == nullptr) return;
+        const rsrc_t yres = make_rsrc(Yout + row0 * q, rows_valid * q * 2);
+        wg_barrier();                                    // T tile consumed: LDS belongs to stage 2
+#pragma unroll
+        for (int e = 0; e < L::NCHQ; ++e) *reinterpret_cast<u32x4*>(lds + qoff[e]) = ring2[0][e];
+        load_q(ring2[0], D2);
+        wg_barrier();                                    // Q slab 0 is in slot 0
+        // stage 2: the Q slabs, and the finished output tiles: tile t was staged in LDS by the MFMA
+        // waves during the last slab of t and leaves here, one slab later, as full 256-byte rows, in
+        // four pieces per thread (64 rows x 16 chunks over 256 threads): the LDS reads are issued
+        // first, the stores are spread between the slab's loads.
+        u32x4 ypiece[4];
+        int ydst[4];
+        bool yleft[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int ci = e * NLT + lt;
+            ydst[e] = ((ci >> 4) * q + (ci & 15) * 8) * 2;
+            yleft[e] = (ci & 15) < 8;                    // in the left 64 columns: all a ragged last tile has
+        }
+        auto flush_read = [&](int seq) {
+            const unsigned char* yt = ytile + (seq & 1) * L::ytile;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int ci = e * NLT + lt;
+                ypiece[e] = *reinterpret_cast<const u32x4*>(yt + (ci >> 4) * L::ypitch + (ci & 15) * 16);
+            }
+        };
+        auto flush_store = [&](int seq, int e) {
+            const int t = tile_of(seq);
+            const bool whole = q - t * 128 >= 128;
+            if (whole || yleft[e]) buf_store16(ypiece[e], yres, ydst[e], t * 256);
+        };
+        auto step2 = [&](u32x4 (&rg)[L::NCHQ], int s, bool flush, int seq) {
+            const int slot = (s + 1) & 1;
+            int sn = s + 1 + D2;
+            if (sn > ns2 - 1) sn = ns2 - 1;
+            const int tn = tile_of(sn / KSL);
+            const int rows = q - tn * 128 < 128 ? q - tn * 128 : 128;
+            const rsrc_t qres = make_rsrc(Qm + (int64_t)tn * 128 * R, (int64_t)rows * R * 2);
+            const int so = (sn % KSL) * BK2 * 2;
+            if (flush) flush_read(seq);
+#pragma unroll
+            for (int e = 0; e < L::NCHQ; ++e) {
+                *reinterpret_cast<u32x4*>(lds + slot * L::slab2 + qoff[e]) = rg[e];
+                rg[e] = buf_load16(qres, qsrc[e], so);
+                __builtin_amdgcn_sched_barrier(0);
+                if (e < 4 && flush) flush_store(seq, e);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (flush) {
+#pragma unroll
+                for (int e = L::NCHQ; e < 4; ++e) flush_store(seq, e);
+            }
+        };
+        int flushed = 0;
+        for (int s0 = 0; s0 < n2p; s0 += D2) {
+#pragma unroll
+            for (int d = 0; d < D2; ++d) {
+                const int s = s0 + d;
+                const bool flush = s > 0 && s % KSL == 0 && flushed < ntile;
+                TSTAMP(1, 0, s);
+                step2(ring2[(d + 1) % D2], s, flush, flushed);
+                if (flush) ++flushed;
+                TSTAMP(1, 3, s);
+                wg_barrier();
+            }
+        }
+        if (flushed < ntile) {
+            flush_read(flushed);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) flush_store(flushed, e);
+        }
+        TMARK(1, 2);
+        return;
+    }
+
+    // ====================================================================== MFMA waves
+    const int lj = lane & 31, lh = lane >> 5;
     const int cs = wave % CS, ks = wave / CS;
 
     // ------------------------------------------------------------------ stage 1
@@ -113,135 +358,74 @@ __global__ __launch_bounds__(512) void chain2_bf16_kernel(const uint16_t* __rest
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc1[a][b][v] = 0.0f;
 
-    unsigned char* const xs = lds;                       // [2][64][BK1]
-    unsigned char* const ps = lds + 2 * L::xslab;        // [2][R][BK1]
-
-    // per-thread chunk coordinates (constant over the slabs)
-    int xoff[NX];
-    const uint16_t* xsrc[NX];
+    TMARK(0, 0);
+    wg_barrier();                                       // slab 0 is in slot 0
+    TMARK(0, 1);
+    for (int s = 0; s < n1p; ++s) {
+        if (s < ns1) {
+            const unsigned char* base = lds + (s & 1) * L::slab1;
 #pragma unroll
-    for (int e = 0; e < NX; ++e) {
-        const int ci = e * 512 + tid;
-        const int row = ci / CPR1, ch = ci % CPR1;
-        xoff[e] = row * (BK1 * 2) + swz<CPR1>(ch, row) * 16;
-        int64_t rr = row0 + row;
-        if (rr >= M) rr = M - 1;                         // tail rows read a valid row, store nothing
-        xsrc[e] = Xin + rr * p + ch * 8;
-    }
-    int poff[NPC];
-    const uint16_t* psrc[NPC];
+            for (int j = 0; j < SPW; ++j) {
+                const int kk = ks * SPW + j;            // k16 step inside the slab
+                const int qc = 2 * kk + lh;             // logical chunk of this lane's 8 values
+                u32x4 xf[2], pf[CB];
 #pragma unroll
-    for (int e = 0; e < NPC; ++e) {
-        const int ci = e * 512 + tid;
-        const int row = ci / CPR1, ch = ci % CPR1;
-        poff[e] = row * (BK1 * 2) + swz<CPR1>(ch, row) * 16;
-        psrc[e] = Pm + (int64_t)(row < R ? row : R - 1) * p + ch * 8;
-    }
-
-    const int ns1 = p / BK1;
-    u32x4 xr[DX][NX], pr[2][NPC];
-    auto load_x = [&](u32x4 (&dst)[NX], int s) {
-#pragma unroll
-        for (int e = 0; e < NX; ++e) dst[e] = *reinterpret_cast<const u32x4*>(xsrc[e] + (int64_t)s * BK1);
-    };
-    auto load_p = [&](u32x4 (&dst)[NPC], int s) {
-#pragma unroll
-        for (int e = 0; e < NPC; ++e) dst[e] = *reinterpret_cast<const u32x4*>(psrc[e] + (int64_t)s * BK1);
-    };
-    auto store_x = [&](const u32x4 (&src)[NX], int slot) {
-#pragma unroll
-        for (int e = 0; e < NX; ++e) *reinterpret_cast<u32x4*>(xs + slot * L::xslab + xoff[e]) = src[e];
-    };
-    auto store_p = [&](const u32x4 (&src)[NPC], int slot) {
-#pragma unroll
-        for (int e = 0; e < NPC; ++e)
-            if (e * 512 + tid < R * CPR1) *reinterpret_cast<u32x4*>(ps + slot * L::pslab + poff[e]) = src[e];
-    };
-
-    // prologue: slab 0 into LDS slot 0; slabs 1..DX of X and 1..2 of P into the register rings
-    if (ns1 > 0) {
-        load_x(xr[0], 0);
-        load_p(pr[0], 0);
-        store_x(xr[0], 0);
-        store_p(pr[0], 0);
-#pragma unroll
-        for (int d = 1; d <= DX; ++d)
-            if (d < ns1) load_x(xr[d % DX], d);
-        if (1 < ns1) load_p(pr[1], 1);
-        if (2 < ns1) load_p(pr[0], 2);
-    }
-    ring_barrier();
-
-    for (int s0 = 0; s0 < ns1; s0 += DX) {
-#pragma unroll
-        for (int d = 0; d < DX; ++d) {
-            const int s = s0 + d;
-            if (s < ns1) {
-                // stage slab s+1 (slot (s+1)&1 was last read in iteration s-1, before its barrier)
-                if (s + 1 < ns1) {
-                    store_x(xr[(d + 1) % DX], (d + 1) & 1);
-                    store_p(pr[(d + 1) & 1], (d + 1) & 1);
+                for (int a = 0; a < 2; ++a) {
+                    const int row = 32 * a + lj;
+                    xf[a] = *reinterpret_cast<const u32x4*>(base + row * (BK1 * 2) + swz<CPR1>(qc, row) * 16);
                 }
-                if (s + 1 + DX < ns1) load_x(xr[(d + 1) % DX], s + 1 + DX);
-                if (s + 3 < ns1) load_p(pr[(d + 1) & 1], s + 3);
-                // consume slab s
-                const unsigned char* xb = xs + (d & 1) * L::xslab;
-                const unsigned char* pb = ps + (d & 1) * L::pslab;
 #pragma unroll
-                for (int j = 0; j < SPW; ++j) {
-                    const int kk = ks * SPW + j;          // k16 step inside the slab
-                    const int qc = 2 * kk + lh;           // logical chunk of this lane's 8 values
-                    u32x4 xf[2], pf[CB];
-#pragma unroll
-                    for (int a = 0; a < 2; ++a) {
-                        const int row = 32 * a + lj;
-                        xf[a] = *reinterpret_cast<const u32x4*>(xb + row * (BK1 * 2) + swz<CPR1>(qc, row) * 16);
-                    }
-#pragma unroll
-                    for (int b = 0; b < CB; ++b) {
-                        const int row = (cs * CB + b) * 32 + lj;
-                        pf[b] = *reinterpret_cast<const u32x4*>(pb + row * (BK1 * 2) + swz<CPR1>(qc, row) * 16);
-                    }
-#pragma unroll
-                    for (int a = 0; a < 2; ++a)
-#pragma unroll
-                        for (int b = 0; b < CB; ++b) acc1[a][b] = mfma16(pf[b], xf[a], acc1[a][b]);
+                for (int b = 0; b < CB; ++b) {
+                    const int row = 64 + (cs * CB + b) * 32 + lj;
+                    pf[b] = *reinterpret_cast<const u32x4*>(base + row * (BK1 * 2) + swz<CPR1>(qc, row) * 16);
                 }
-                ring_barrier();
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+#pragma unroll
+                    for (int b = 0; b < CB; ++b) acc1[a][b] = mfma16(pf[b], xf[a], acc1[a][b]);
             }
         }
+        wg_barrier();
     }
 
+    TMARK(0, 2);
     // ------------------------------------------------------------------ tree reduction over the KS groups
-    {
-        float* red = reinterpret_cast<float*>(lds);
+    if constexpr (KS > 1) {
+        // layout: [wave slot][block (a,b)][quad g][lane][4 floats]: one 16-byte access per quad
+        f32x4* red = reinterpret_cast<f32x4*>(lds);
 #pragma unroll
         for (int half = KS / 2; half >= 1; half >>= 1) {
             if (ks >= half && ks < 2 * half) {
-                float* dst = red + (size_t)(((ks - half) * CS + cs) * (2 * CB)) * 16 * 64;
+                f32x4* dst = red + (size_t)(((ks - half) * CS + cs) * (2 * CB)) * 4 * 64;
 #pragma unroll
                 for (int a = 0; a < 2; ++a)
 #pragma unroll
                     for (int b = 0; b < CB; ++b)
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) dst[((a * CB + b) * 16 + v) * 64 + lane] = acc1[a][b][v];
+                        for (int g = 0; g < 4; ++g)
+                            dst[((a * CB + b) * 4 + g) * 64 + lane] =
+                                f32x4{acc1[a][b][4 * g], acc1[a][b][4 * g + 1], acc1[a][b][4 * g + 2], acc1[a][b][4 * g + 3]};
             }
-            __syncthreads();
+            wg_barrier();
             if (ks < half) {
-                const float* src = red + (size_t)((ks * CS + cs) * (2 * CB)) * 16 * 64;
+                const f32x4* src = red + (size_t)((ks * CS + cs) * (2 * CB)) * 4 * 64;
 #pragma unroll
                 for (int a = 0; a < 2; ++a)
 #pragma unroll
                     for (int b = 0; b < CB; ++b)
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) acc1[a][b][v] += src[((a * CB + b) * 16 + v) * 64 + lane];
+                        for (int g = 0; g < 4; ++g) {
+                            const f32x4 v = src[((a * CB + b) * 4 + g) * 64 + lane];
+                            acc1[a][b][4 * g] += v[0]; acc1[a][b][4 * g + 1] += v[1];
+                            acc1[a][b][4 * g + 2] += v[2]; acc1[a][b][4 * g + 3] += v[3];
+                        }
             }
-            __syncthreads();
+            if (half > 1) wg_barrier();                 // the next round overwrites what was just read
         }
     }
 
-    // ------------------------------------------------------------------ T tile (bf16) to LDS, Tout, operand registers
-    unsigned char* ttile = lds + L::red;
+    TMARK(0, 3);
+    // ------------------------------------------------------------------ T tile (bf16) to LDS, operand registers
     if (ks == 0) {
         // lane holds T[32a + lj][32(cs CB + b) + 8g + 4 lh + (0..3)] in acc1[a][b][4g .. 4g+3]
 #pragma unroll
@@ -256,127 +440,70 @@ __global__ __launch_bounds__(512) void chain2_bf16_kernel(const uint16_t* __rest
                                               (32 * (cs * CB + b) + 8 * g + 4 * lh) * 2) = o;
                 }
     }
-    __syncthreads();
-    if (Tout != nullptr) {
-        constexpr int CPT = R / 8;   // 16-byte chunks per T row
-        for (int i = tid; i < 64 * CPT; i += 512) {
-            const int row = i / CPT, ch = i % CPT;
-            if (row0 + row < M)
-                *reinterpret_cast<u32x4*>(Tout + (row0 + row) * R + ch * 8) =
-                    *reinterpret_cast<const u32x4*>(ttile + row * L::tpitch + ch * 16);
-        }
-    }
+    wg_barrier();                                       // last of the mid barriers: T tile complete
     if (Yout == nullptr) return;
 
+    // Stage 2: wave w owns all 64 rows of T (in registers, as MFMA B operands) and column block w
+    // (32 columns) of every 128-column output tile.
     constexpr int KB = R / 16;
-    u32x4 tf[2][KB];   // B operands of stage 2: T[32a + lj][16kb + 8 lh .. +7]
+    u32x4 tf[2][KB];   // T[32a + lj][16kb + 8 lh .. +7]
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
             tf[a][kb] = *reinterpret_cast<const u32x4*>(ttile + (32 * a + lj) * L::tpitch + (16 * kb + 8 * lh) * 2);
-    __syncthreads();   // T tile consumed; stage 2 takes over the LDS
+    wg_barrier();                                       // T tile consumed; stage 2 takes over the LDS
+    TMARK(0, 4);
+    wg_barrier();                                       // Q slab 0 is in slot 0
+    TMARK(0, 5);
 
     // ------------------------------------------------------------------ stage 2
-    constexpr int BK2 = C::BK2, CPR2 = BK2 / 8;
-    constexpr int KSL = R / BK2;                 // slabs per round
-    constexpr int NQ = 256 * CPR2 / 512;         // chunks per thread per slab
-    unsigned char* const qs = lds;               // [2][256][BK2]
-    unsigned char* const ytile = lds + 2 * L::qslab;
-    const int nround = (q + 255) / 256;
-    const int ns2 = nround * KSL;
-
-    int qrow[NQ], qoff[NQ], qcol[NQ];
-#pragma unroll
-    for (int e = 0; e < NQ; ++e) {
-        const int ci = e * 512 + tid;
-        qrow[e] = ci / CPR2;
-        const int ch = ci % CPR2;
-        qcol[e] = ch * 8;
-        qoff[e] = qrow[e] * (BK2 * 2) + swz<CPR2>(ch, qrow[e]) * 16;
-    }
-    u32x4 qr[2][NQ];
-    auto load_q = [&](u32x4 (&dst)[NQ], int s) {
-        const int round = s / KSL, kslab = s % KSL;
-#pragma unroll
-        for (int e = 0; e < NQ; ++e) {
-            int row = round * 256 + qrow[e];
-            if (row >= q) row = q - 1;
-            dst[e] = *reinterpret_cast<const u32x4*>(Qm + (int64_t)row * R + kslab * BK2 + qcol[e]);
-        }
-    };
-    auto store_q = [&](const u32x4 (&src)[NQ], int slot) {
-#pragma unroll
-        for (int e = 0; e < NQ; ++e) *reinterpret_cast<u32x4*>(qs + slot * L::qslab + qoff[e]) = src[e];
-    };
-
-    if (ns2 > 0) {
-        load_q(qr[0], 0);
-        store_q(qr[0], 0);
-        if (1 < ns2) load_q(qr[1], 1);
-        if (2 < ns2) load_q(qr[0], 2);
-    }
-    ring_barrier();
-
     f32x16 acc2[2];
-    // rounds are processed in pairs so that the slab parity (LDS slot, register set) is a
-    // compile-time constant even when a round has an odd number of slabs
-    for (int rp = 0; rp < nround; rp += 2) {
+    for (int s0 = 0; s0 < n2p; s0 += KSL) {
+        const int t = s0 / KSL;
+        const bool live = s0 < ns2;                     // padded trips only keep the barrier count
 #pragma unroll
-        for (int rip = 0; rip < 2; ++rip) {
-            const int round = rp + rip;
-            if (round < nround) {
+        for (int a = 0; a < 2; ++a)
 #pragma unroll
-                for (int a = 0; a < 2; ++a)
+            for (int v = 0; v < 16; ++v) acc2[a][v] = 0.0f;
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc2[a][v] = 0.0f;
+        for (int kslab = 0; kslab < KSL; ++kslab) {
+            TSTAMP(0, 0, s0 + kslab);
+            if (live) {
+                const unsigned char* base = lds + ((s0 + kslab) & 1) * L::slab2;
+                const int row = 32 * wave + lj;
 #pragma unroll
-                for (int kslab = 0; kslab < KSL; ++kslab) {
-                    const int u = rip * KSL + kslab;          // compile-time; its parity is the slab's
-                    const int s = rp * KSL + u;
-                    if (s + 1 < ns2) store_q(qr[(u + 1) & 1], (u + 1) & 1);
-                    if (s + 3 < ns2) load_q(qr[(u + 1) & 1], s + 3);
-                    const unsigned char* base = qs + (u & 1) * L::qslab;
-#pragma unroll
-                    for (int kk = 0; kk < BK2 / 16; ++kk) {
-                        const int row = 32 * wave + lj;
-                        const u32x4 qf = *reinterpret_cast<const u32x4*>(
-                            base + row * (BK2 * 2) + swz<CPR2>(2 * kk + lh, row) * 16);
-                        const int kb = kslab * (BK2 / 16) + kk;
-                        acc2[0] = mfma16(qf, tf[0][kb], acc2[0]);
-                        acc2[1] = mfma16(qf, tf[1][kb], acc2[1]);
-                    }
-                    ring_barrier();
+                for (int kk = 0; kk < BK2 / 16; ++kk) {
+                    const u32x4 qf = *reinterpret_cast<const u32x4*>(
+                        base + row * (BK2 * 2) + swz<CPR2>(2 * kk + lh, row) * 16);
+                    const int kb = kslab * (BK2 / 16) + kk;
+                    acc2[0] = mfma16(qf, tf[0][kb], acc2[0]);
+                    acc2[1] = mfma16(qf, tf[1][kb], acc2[1]);
                 }
-                // lane holds Y[32a + lj][32 wave + 8g + 4 lh + (0..3)] of this round's 64 x 256 tile
+                if (kslab == KSL - 1) {
+                    // lane holds Y[32a + lj][32 wave + 8g + 4 lh + (0..3)] of this 64 x 128 tile
+                    unsigned char* yt = ytile + (t & 1) * L::ytile;
 #pragma unroll
-                for (int a = 0; a < 2; ++a)
+                    for (int a = 0; a < 2; ++a)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        u32x2 o = {pack2_bf16(acc2[a][4 * g + 0], acc2[a][4 * g + 1]),
-                                   pack2_bf16(acc2[a][4 * g + 2], acc2[a][4 * g + 3])};
-                        *reinterpret_cast<u32x2*>(ytile + (32 * a + lj) * L::ypitch + (32 * wave + 8 * g + 4 * lh) * 2) = o;
-                    }
-                ring_barrier();
-                // 64 rows x 32 chunks of 16 bytes = 2048 chunks, 4 per thread, row-contiguous
-                const int ncol = q - round * 256 < 256 ? q - round * 256 : 256;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int ci = e * 512 + tid;
-                    const int row = ci >> 5, ch = ci & 31;
-                    if (row0 + row < M && ch * 8 < ncol)
-                        *reinterpret_cast<u32x4*>(Yout + (row0 + row) * q + round * 256 + ch * 8) =
-                            *reinterpret_cast<const u32x4*>(ytile + row * L::ypitch + ch * 16);
+                        for (int g = 0; g < 4; ++g) {
+                            u32x2 o = {pack2_bf16(acc2[a][4 * g + 0], acc2[a][4 * g + 1]),
+                                       pack2_bf16(acc2[a][4 * g + 2], acc2[a][4 * g + 3])};
+                            *reinterpret_cast<u32x2*>(yt + (32 * a + lj) * L::ypitch + (32 * wave + 8 * g + 4 * lh) * 2) = o;
+                        }
                 }
             }
+            TSTAMP(0, 1, s0 + kslab);
+            wg_barrier();
         }
     }
+    TMARK(0, 6);
 }
 
 template <int R>
 hipError_t launch_chain2_r(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                            int64_t M, int p, int q, hipStream_t s) {
-    constexpr int lds_bytes = Ch2Lds<R>::bytes;
+    constexpr int lds_bytes = Ch2Cfg<R>::lds_bytes;
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
     static bool attr_set = false;
     if (!attr_set) {
@@ -385,7 +512,7 @@ hipError_t launch_chain2_r(const void* Xin, const void* P, const void* Q, void* 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(chain2_bf16_kernel<R>, dim3((unsigned)ceil_div(M, 64)), dim3(512), lds_bytes, s,
+    hipLaunchKernelGGL(chain2_bf16_kernel<R>, dim3((unsigned)ceil_div(M, 64)), dim3(NT), lds_bytes, s,
                        (const uint16_t*)Xin, (const uint16_t*)P, (const uint16_t*)Q,
                        (uint16_t*)Yout, (uint16_t*)Tout, M, p, q);
     return hipGetLastError();
@@ -393,10 +520,10 @@ hipError_t launch_chain2_r(const void* Xin, const void* P, const void* Q, void* 
 
 }  // namespace
 
-bool chain2_supports(int R, int p) {
+bool chain2_supports(int R, int p, int q) {
+    if (p % 64 != 0 || p > (1 << 20) || q > (1 << 20)) return false;
     switch (R) {
-        case 32: case 96: return p % 128 == 0;
-        case 64: case 128: case 192: case 256: case 384: return p % 64 == 0;
+        case 32: case 64: case 96: case 128: case 160: case 192: case 256: case 320: case 384: return true;
         default: return false;
     }
 }
@@ -408,8 +535,10 @@ hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, voi
         case 64: return launch_chain2_r<64>(Xin, P, Q, Yout, Tout, M, p, q, s);
         case 96: return launch_chain2_r<96>(Xin, P, Q, Yout, Tout, M, p, q, s);
         case 128: return launch_chain2_r<128>(Xin, P, Q, Yout, Tout, M, p, q, s);
+        case 160: return launch_chain2_r<160>(Xin, P, Q, Yout, Tout, M, p, q, s);
         case 192: return launch_chain2_r<192>(Xin, P, Q, Yout, Tout, M, p, q, s);
         case 256: return launch_chain2_r<256>(Xin, P, Q, Yout, Tout, M, p, q, s);
+        case 320: return launch_chain2_r<320>(Xin, P, Q, Yout, Tout, M, p, q, s);
         case 384: return launch_chain2_r<384>(Xin, P, Q, Yout, Tout, M, p, q, s);
         default: return hipErrorInvalidValue;
     }

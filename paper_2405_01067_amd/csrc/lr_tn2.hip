@@ -84,42 +84,40 @@ __global__ __launch_bounds__(256) void tn2_bf16_kernel(Tn2Args args) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
-    // per-thread chunk coordinates
-    int urow[C::NU], uoff[C::NU];
-    const uint16_t* usrc[C::NU];
-    bool uok[C::NU];
+    // per-thread chunk coordinates; global side as 32-bit byte offsets for buffer loads (a chunk in
+    // a column past P gets an offset no descriptor covers and reads as zeros)
+    int uoff[C::NU], usrc[C::NU];
 #pragma unroll
     for (int e = 0; e < C::NU; ++e) {
         const int ci = e * 256 + tid;
-        urow[e] = ci / (TP / 8);
-        const int ch = ci % (TP / 8);
-        uoff[e] = urow[e] * UPITCH + ((((ch >> 2) ^ (urow[e] & 3)) << 2) | (ch & 3)) * 16;
-        uok[e] = p0 + ch * 8 < job.P;
-        usrc[e] = job.U + (int64_t)urow[e] * job.P + (uok[e] ? p0 + ch * 8 : 0);
+        const int row = ci / (TP / 8), ch = ci % (TP / 8);
+        uoff[e] = row * UPITCH + ((((ch >> 2) ^ (row & 3)) << 2) | (ch & 3)) * 16;
+        usrc[e] = p0 + ch * 8 < job.P ? (row * job.P + ch * 8) * 2 : kBufNowhere;
     }
-    int vrow[C::NV], voff[C::NV];
-    const uint16_t* vsrc[C::NV];
+    int voff[C::NV], vsrc[C::NV];
     bool vok[C::NV];
 #pragma unroll
     for (int e = 0; e < C::NV; ++e) {
         const int ci = e * 256 + tid;
-        vrow[e] = ci / (R / 8);
-        const int ch = ci % (R / 8);
+        const int row = ci / (R / 8), ch = ci % (R / 8);
         vok[e] = ci < BKM * (R / 8);
-        voff[e] = vrow[e] * C::VPITCH + ((((ch >> 2) ^ (vrow[e] & 3)) << 2) | (ch & 3)) * 16;
-        vsrc[e] = job.V + (int64_t)vrow[e] * R + ch * 8;
+        voff[e] = row * C::VPITCH + ((((ch >> 2) ^ (row & 3)) << 2) | (ch & 3)) * 16;
+        vsrc[e] = vok[e] ? (row * R + ch * 8) * 2 : kBufNowhere;
     }
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
     u32x4 ur[NRS][C::NU], vr[NRS][C::NV];
-    // rows past the end of the split (ragged last slab) and columns past P load zeros
+    // The descriptors are rebuilt per slab (scalar work) to end exactly at the split's last row:
+    // the row offset is part of the per-lane offset, the only part the hardware range-checks, so
+    // rows past the end of the split (ragged last slab) load zeros.  Buffer loads also keep their
+    // issue rate next to MFMA work, which loads through 64-bit per-lane pointers do not.
     auto load = [&](u32x4 (&du)[C::NU], u32x4 (&dv)[C::NV], int s) {
         const int64_t kr0 = k_begin + (int64_t)s * BKM;
+        const int64_t left = k_end - kr0;                    // >= 1 for every slab that is loaded
+        const rsrc_t ures = make_rsrc(job.U + kr0 * job.P + p0, (left * job.P - p0) * 2);
+        const rsrc_t vres = make_rsrc(job.V + kr0 * R, left * R * 2);
 #pragma unroll
-        for (int e = 0; e < C::NU; ++e)
-            du[e] = (uok[e] && kr0 + urow[e] < k_end) ? *reinterpret_cast<const u32x4*>(usrc[e] + kr0 * job.P) : zero4;
+        for (int e = 0; e < C::NU; ++e) du[e] = buf_load16(ures, usrc[e], 0);
 #pragma unroll
-        for (int e = 0; e < C::NV; ++e)
-            dv[e] = (vok[e] && kr0 + vrow[e] < k_end) ? *reinterpret_cast<const u32x4*>(vsrc[e] + kr0 * R) : zero4;
+        for (int e = 0; e < C::NV; ++e) dv[e] = buf_load16(vres, vsrc[e], 0);
     };
     auto store = [&](const u32x4 (&su)[C::NU], const u32x4 (&sv)[C::NV], int slot) {
         unsigned char* base = lds + slot * C::slab;
