@@ -191,12 +191,9 @@ int lr_linear_bwd(const void* dY, const void* X, const void* T, const void* A, c
     }
     if (dX || dB) {
         // dT = dY A = dY (A^T)^T and dX = dT B = dT (B^T)^T: the forward chain on transposed factors
-        e = launch_transpose_bf16(A, At, (int)m, (int)r, s);
+        const TransposeJob tj[2] = {{A, At, (int)m, (int)r}, {B, Bt, (int)r, (int)n}};
+        e = launch_transpose_bf16(tj, dX ? 2 : 1, s);
         if (e != hipSuccess) return ABT_EHIP;
-        if (dX) {
-            e = launch_transpose_bf16(B, Bt, (int)r, (int)n, s);
-            if (e != hipSuccess) return ABT_EHIP;
-        }
         e = chain(dY, At, dX ? Bt : nullptr, dX, dT, M, (int)m, (int)n, (int)r, s);
         if (e != hipSuccess) return ABT_EHIP;
     }

@@ -62,7 +62,8 @@ bool chain2_supports(int R, int p, int q);
 hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                               int64_t M, int p, int q, int R, hipStream_t s);
 // dst[c, r] = src[r, c] for a bf16 matrix of `rows` x `cols`.
-hipError_t launch_transpose_bf16(const void* src, void* dst, int rows, int cols, hipStream_t s);
+struct TransposeJob { const void* src; void* dst; int rows, cols; };   // dst[cols, rows] = src[rows, cols]^T
+hipError_t launch_transpose_bf16(const TransposeJob* jobs, int njobs, hipStream_t s);
 // part[split][P,Q] = U[rows of split, P]^T . V[rows of split, Q]  (bf16 in, fp32 partials)
 // followed by out[P,Q] (+)= sum over splits, in fixed order.  One of P, Q equals R.
 // job: out[P,R] = U[M,P]^T . V[M,R]; with transposed != 0 the result is stored as out[R,P].

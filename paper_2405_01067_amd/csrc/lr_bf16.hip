@@ -220,17 +220,40 @@ hipError_t launch_chain_r(const void* Xin, const void* P, const void* Q, void* Y
 // bf16 transpose (for A^T and B^T, which turn dT = dY A and dX = dT B into the same
 // "rows times rows" shape the chain kernel consumes).
 // =====================================================================================
-__global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ src,
-                                                             uint16_t* __restrict__ dst,
-                                                             int rows, int cols) {
-    __shared__ uint16_t tile[64][66];
-    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int i = ty; i < 64; i += 4)
-        if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = src[(int64_t)(r0 + i) * cols + c0 + tx];
+// One launch serves up to two matrices (rows and cols multiples of 8).  A work-group moves one
+// 64 x 64 tile: 16-byte loads of row pieces into LDS, 16-byte stores of column pieces out of it.
+struct TrJob { const uint16_t* src; uint16_t* dst; int rows, cols, tiles_x, tile_begin; };
+struct TrArgs { TrJob job[2]; int njobs; };
+
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(TrArgs args) {
+    __shared__ uint16_t tile[64][72];                  // pitch 144 B: 16-byte aligned rows
+    const int jid = (args.njobs > 1 && (int)blockIdx.x >= args.job[1].tile_begin) ? 1 : 0;
+    const TrJob j = args.job[jid];
+    const int t = (int)blockIdx.x - j.tile_begin;
+    const int r0 = (t / j.tiles_x) * 64, c0 = (t % j.tiles_x) * 64;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int ci = e * 256 + threadIdx.x;          // 64 rows x 8 chunks of 8 elements
+        const int row = ci >> 3, ch = ci & 7;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (r0 + row < j.rows && c0 + ch * 8 < j.cols)
+            v = *reinterpret_cast<const u32x4*>(j.src + (int64_t)(r0 + row) * j.cols + c0 + ch * 8);
+        *reinterpret_cast<u32x4*>(&tile[row][ch * 8]) = v;
+    }
     __syncthreads();
-    for (int i = ty; i < 64; i += 4)
-        if (c0 + i < cols && r0 + tx < rows) dst[(int64_t)(c0 + i) * rows + r0 + tx] = tile[tx][i];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int ci = e * 256 + threadIdx.x;          // 64 output rows (source columns) x 8 chunks
+        const int orow = ci >> 3, ch = ci & 7;
+        if (c0 + orow < j.cols && r0 + ch * 8 < j.rows) {
+            uint16_t v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = tile[ch * 8 + i][orow];
+            u32x4 o = {(uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16),
+                       (uint32_t)v[4] | ((uint32_t)v[5] << 16), (uint32_t)v[6] | ((uint32_t)v[7] << 16)};
+            *reinterpret_cast<u32x4*>(j.dst + (int64_t)(c0 + orow) * j.rows + r0 + ch * 8) = o;
+        }
+    }
 }
 
 }  // namespace
@@ -259,10 +282,18 @@ hipError_t launch_chain_bf16(const void* Xin, const void* P, const void* Q, void
 #undef CALL
 }
 
-hipError_t launch_transpose_bf16(const void* src, void* dst, int rows, int cols, hipStream_t s) {
-    dim3 grid((cols + 63) / 64, (rows + 63) / 64);
-    hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, s, (const uint16_t*)src,
-                       (uint16_t*)dst, rows, cols);
+hipError_t launch_transpose_bf16(const TransposeJob* jobs, int njobs, hipStream_t s) {
+    if (njobs < 1 || njobs > 2) return hipErrorInvalidValue;
+    TrArgs args{};
+    args.njobs = njobs;
+    int tiles = 0;
+    for (int i = 0; i < njobs; ++i) {
+        if (jobs[i].rows % 8 || jobs[i].cols % 8) return hipErrorInvalidValue;
+        const int tx = (jobs[i].cols + 63) / 64, ty = (jobs[i].rows + 63) / 64;
+        args.job[i] = TrJob{(const uint16_t*)jobs[i].src, (uint16_t*)jobs[i].dst, jobs[i].rows, jobs[i].cols, tx, tiles};
+        tiles += tx * ty;
+    }
+    hipLaunchKernelGGL(transpose_bf16_kernel, dim3(tiles), dim3(256), 0, s, args);
     return hipGetLastError();
 }
 

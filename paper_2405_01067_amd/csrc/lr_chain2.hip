@@ -15,8 +15,8 @@
 // The waves meet at one s_barrier per slab; LDS holds two slab slots.
 //
 //   stage 1: slabs of 64 contraction columns: 64 rows of Xin and the R rows of P.  The MFMA waves
-//            form CS column groups x KS contraction groups; a wave keeps a 64 x (R/CS) block of
-//            T^T in accumulators and takes every KS-th k16 step.  The KS partial sums are then
+//            form RS row groups x CS column groups x KS contraction groups; a wave keeps its block
+//            of T^T in accumulators and takes every KS-th k16 step.  The KS partial sums are then
 //            added in a fixed tree order through LDS.
 //   T:       rounded to bf16 once, written as a 64 x R tile to LDS (and from there to Tout); every
 //            MFMA wave loads all of it as MFMA operands: T stays in registers for all of stage 2.
@@ -68,19 +68,23 @@ __device__ __forceinline__ int swz(int chunk, int row) {
     else return chunk ^ ((row >> 2) & 3);
 }
 
-// Work split of the four MFMA waves in stage 1: CS column groups x KS contraction groups.
+// Work split of the four MFMA waves in stage 1: RS row groups x CS column groups x KS contraction
+// groups (product 4).  Splitting the rows (RS = 2) would need no partial sums, but every wave then
+// reads more operands from LDS per MFMA, and LDS bandwidth (shared with the loaders' stores) is
+// what limits stage 1: measured slower than contraction groups plus a tree reduction.
 template <int R> struct Ch2;
-template <> struct Ch2<32>  { static constexpr int CS = 1, KS = 4; };
-template <> struct Ch2<64>  { static constexpr int CS = 1, KS = 4; };
-template <> struct Ch2<96>  { static constexpr int CS = 1, KS = 4; };
-template <> struct Ch2<128> { static constexpr int CS = 2, KS = 2; };
-template <> struct Ch2<160> { static constexpr int CS = 1, KS = 4; };
-template <> struct Ch2<192> { static constexpr int CS = 2, KS = 2; };
-template <> struct Ch2<256> { static constexpr int CS = 2, KS = 2; };
-template <> struct Ch2<320> { static constexpr int CS = 2, KS = 2; };
-template <> struct Ch2<384> { static constexpr int CS = 4, KS = 1; };
+template <> struct Ch2<32>  { static constexpr int RS = 1, CS = 1, KS = 4; };
+template <> struct Ch2<64>  { static constexpr int RS = 1, CS = 1, KS = 4; };
+template <> struct Ch2<96>  { static constexpr int RS = 1, CS = 1, KS = 4; };
+template <> struct Ch2<128> { static constexpr int RS = 1, CS = 2, KS = 2; };
+template <> struct Ch2<160> { static constexpr int RS = 1, CS = 1, KS = 4; };
+template <> struct Ch2<192> { static constexpr int RS = 1, CS = 2, KS = 2; };
+template <> struct Ch2<256> { static constexpr int RS = 1, CS = 2, KS = 2; };
+template <> struct Ch2<320> { static constexpr int RS = 1, CS = 2, KS = 2; };
+template <> struct Ch2<384> { static constexpr int RS = 1, CS = 4, KS = 1; };
 
 constexpr int NMW = 4, NLW = 4;                 // MFMA waves, loader waves
+constexpr int NMW_ = NMW;
 constexpr int NMT = 64 * NMW, NLT = 64 * NLW;   // threads per role
 constexpr int NT = NMT + NLT;
 constexpr int BK1 = 64, CPR1 = BK1 / 8;         // stage-1 slab: 64 contraction columns
@@ -91,7 +95,8 @@ constexpr int gcdi(int a, int b) { return b == 0 ? a : gcdi(b, a % b); }
 template <int R>
 struct Ch2Cfg {
     using C = Ch2<R>;
-    static constexpr int CB = R / 32 / C::CS;
+    static constexpr int CB = R / 32 / C::CS;                 // column blocks per wave
+    static constexpr int RA = 2 / C::RS;                      // row blocks per wave
     static constexpr int SPW = BK1 / (16 * C::KS);            // k16 steps per wave per slab
     static constexpr int xpart = 64 * BK1 * 2;                // slot = [64 rows of Xin][R rows of P]
     static constexpr int slab1 = (64 + R) * BK1 * 2;
@@ -107,13 +112,14 @@ struct Ch2Cfg {
     static constexpr int U2 = D2 * KSL / gcdi(D2, KSL);       // stage-2 trip count is padded to a multiple of this
     static constexpr int ypitch = 128 * 2 + 16;
     static constexpr int ytile = 64 * ypitch;
-    static constexpr int red = (C::KS / 2) * C::CS * CB * 8192;   // first (largest) round of the tree
+    static constexpr int red = (C::KS / 2) * C::CS * C::RS * RA * CB * 4096;   // first (largest) round of the tree
     static constexpr int tpitch = R * 2 + 16;
     static constexpr int ttile = 64 * tpitch;
     static constexpr int a = 2 * slab1, b = red + ttile, c = 2 * slab2 + 2 * ytile;
     static constexpr int lds_bytes = a > b ? (a > c ? a : c) : (b > c ? b : c);
     static constexpr int n_mid_barriers = C::KS > 1 ? 2 * ilog2(C::KS) : 1;  // tree + T tile written
     static_assert(SPW >= 1 && NCHX == 2 && R % 32 == 0 && BK2 % 16 == 0, "slab shape");
+    static_assert(C::RS * C::CS * C::KS == NMW_ && CB * C::CS * 32 == R && RA * C::RS == 2, "wave split");
 };
 
 template <int R>
@@ -126,7 +132,7 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
     extern __shared__ __align__(1024) unsigned char lds[];
     using C = Ch2<R>;
     using L = Ch2Cfg<R>;
-    constexpr int CS = C::CS, KS = C::KS, CB = L::CB, SPW = L::SPW;
+    constexpr int RS = C::RS, CS = C::CS, KS = C::KS, CB = L::CB, RA = L::RA, SPW = L::SPW;
     constexpr int BK2 = L::BK2, CPR2 = L::CPR2, KSL = L::KSL;
     constexpr int D1 = L::D1, D2 = L::D2;
 
@@ -347,12 +353,12 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
 
     // ====================================================================== MFMA waves
     const int lj = lane & 31, lh = lane >> 5;
-    const int cs = wave % CS, ks = wave / CS;
+    const int cs = wave % CS, rs = (wave / CS) % RS, ks = wave / (CS * RS);
 
     // ------------------------------------------------------------------ stage 1
-    f32x16 acc1[2][CB];
+    f32x16 acc1[RA][CB];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < RA; ++a)
 #pragma unroll
         for (int b = 0; b < CB; ++b)
 #pragma unroll
@@ -368,10 +374,10 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
             for (int j = 0; j < SPW; ++j) {
                 const int kk = ks * SPW + j;            // k16 step inside the slab
                 const int qc = 2 * kk + lh;             // logical chunk of this lane's 8 values
-                u32x4 xf[2], pf[CB];
+                u32x4 xf[RA], pf[CB];
 #pragma unroll
-                for (int a = 0; a < 2; ++a) {
-                    const int row = 32 * a + lj;
+                for (int a = 0; a < RA; ++a) {
+                    const int row = 32 * (rs * RA + a) + lj;
                     xf[a] = *reinterpret_cast<const u32x4*>(base + row * (BK1 * 2) + swz<CPR1>(qc, row) * 16);
                 }
 #pragma unroll
@@ -380,7 +386,7 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
                     pf[b] = *reinterpret_cast<const u32x4*>(base + row * (BK1 * 2) + swz<CPR1>(qc, row) * 16);
                 }
 #pragma unroll
-                for (int a = 0; a < 2; ++a)
+                for (int a = 0; a < RA; ++a)
 #pragma unroll
                     for (int b = 0; b < CB; ++b) acc1[a][b] = mfma16(pf[b], xf[a], acc1[a][b]);
             }
@@ -393,12 +399,13 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
     if constexpr (KS > 1) {
         // layout: [wave slot][block (a,b)][quad g][lane][4 floats]: one 16-byte access per quad
         f32x4* red = reinterpret_cast<f32x4*>(lds);
+        const int wslot = rs * CS + cs;
 #pragma unroll
         for (int half = KS / 2; half >= 1; half >>= 1) {
             if (ks >= half && ks < 2 * half) {
-                f32x4* dst = red + (size_t)(((ks - half) * CS + cs) * (2 * CB)) * 4 * 64;
+                f32x4* dst = red + (size_t)(((ks - half) * (CS * RS) + wslot) * (RA * CB)) * 4 * 64;
 #pragma unroll
-                for (int a = 0; a < 2; ++a)
+                for (int a = 0; a < RA; ++a)
 #pragma unroll
                     for (int b = 0; b < CB; ++b)
 #pragma unroll
@@ -408,9 +415,9 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
             }
             wg_barrier();
             if (ks < half) {
-                const f32x4* src = red + (size_t)((ks * CS + cs) * (2 * CB)) * 4 * 64;
+                const f32x4* src = red + (size_t)((ks * (CS * RS) + wslot) * (RA * CB)) * 4 * 64;
 #pragma unroll
-                for (int a = 0; a < 2; ++a)
+                for (int a = 0; a < RA; ++a)
 #pragma unroll
                     for (int b = 0; b < CB; ++b)
 #pragma unroll
@@ -427,16 +434,16 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
     TMARK(0, 3);
     // ------------------------------------------------------------------ T tile (bf16) to LDS, operand registers
     if (ks == 0) {
-        // lane holds T[32a + lj][32(cs CB + b) + 8g + 4 lh + (0..3)] in acc1[a][b][4g .. 4g+3]
+        // lane holds T[32(rs RA + a) + lj][32(cs CB + b) + 8g + 4 lh + (0..3)] in acc1[a][b][4g .. 4g+3]
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < RA; ++a)
 #pragma unroll
             for (int b = 0; b < CB; ++b)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     u32x2 o = {pack2_bf16(acc1[a][b][4 * g + 0], acc1[a][b][4 * g + 1]),
                                pack2_bf16(acc1[a][b][4 * g + 2], acc1[a][b][4 * g + 3])};
-                    *reinterpret_cast<u32x2*>(ttile + (32 * a + lj) * L::tpitch +
+                    *reinterpret_cast<u32x2*>(ttile + (32 * (rs * RA + a) + lj) * L::tpitch +
                                               (32 * (cs * CB + b) + 8 * g + 4 * lh) * 2) = o;
                 }
     }
