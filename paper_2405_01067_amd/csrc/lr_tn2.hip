@@ -4,24 +4,27 @@
 // job:  part[split][P,R] = U[rows of split, P]^T . V[rows of split, R]   (dA: U = dY, V = T;
 // dB: U = X, V = dT, result stored transposed), followed by a fixed-order sum over the splits.
 //
-// Work-group: 128 columns of U x all R columns of V over one split of the batch rows; 8 waves in
-// two roles.  Four loader waves move slabs of 64 batch rows (32 for R > 256) global -> register
-// ring (two slabs in flight) -> LDS exactly as they lie in memory (batch row major), two LDS slots,
-// one barrier per slab.  Four MFMA waves (2 x 2, or 4 x 1 when R/32 is odd) each own a block of the
-// output tile.  The MFMA operands, which need 8 consecutive batch rows per lane, are read with the
-// transposing LDS load of gfx950 (ds_read_b64_tr_b16): in every group of 16 lanes, lane s supplies
-// the address of 4 consecutive columns of batch row k0 + s/4 (columns 4 (s%4) ..), and lane l
-// receives column l of the four rows k0 .. k0+3.
-// LDS rows are a multiple of 256 bytes; their 64-byte units are XOR-swizzled with the low two bits
-// of the row, so the four rows one transposing load touches lie in different banks.
+// Work-group: 128 columns of U x all R columns of V over one split of the batch rows.  Four MFMA
+// waves (2 x 2, or 4 x 1 when R/32 is odd) each own a block of the output tile.  Loader waves (two
+// for the U part, R/64 for the V part; half as many with two blocks per thread for wide slabs)
+// move slabs of 64 batch rows global -> register ring (two slabs in flight) -> LDS, two LDS slots,
+// one barrier per slab.  Both operands lie in memory with the contraction index (batch row)
+// slowest, while an MFMA operand needs 8 consecutive batch rows per lane: the loaders transpose
+// 8 x 8 blocks in registers (byte permutes) on the way, so the MFMA waves read their operands
+// with plain 16-byte LDS loads.  (Reading row-major slabs with the transposing LDS load
+// ds_read_b64_tr_b16 instead was limited by the rate of those 8-byte reads.)
 #include "common.h"
+
+#ifdef ABT_TIMING
+__device__ long long abt_tn_tl[2][2][64];
+#define TN_STAMP(role, k, it) do { if (blockIdx.x == 3 && blockIdx.y == 2 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 4 : 0) && (it) < 64) abt_tn_tl[role][k][it] = __builtin_readcyclecounter(); } while (0)
+#else
+#define TN_STAMP(role, k, it) do {} while (0)
+#endif
 
 namespace abt {
 
 namespace {
-
-typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 __device__ __forceinline__ void ring_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -29,15 +32,9 @@ __device__ __forceinline__ void ring_barrier() {
 __device__ __forceinline__ f32x16 mfma16(u32x4 a, u32x4 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
-// transposing LDS read: 4 x b16 for this lane (see the header comment)
-__device__ __forceinline__ u32x2 ds_tr(const unsigned char* p) {
-    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(lds_void*)p);
-    return __builtin_bit_cast(u32x2, v);
-}
-
 constexpr int TP = 128;      // U columns per work-group
-constexpr int UPITCH = TP * 2;
-constexpr int NMT = 256, NLT = 256, NT = NMT + NLT;   // MFMA threads, loader threads
+constexpr int BKM = 64;      // batch rows per slab
+constexpr int NMW = 4;       // MFMA waves
 
 template <int R>
 struct Tn2 {
@@ -45,14 +42,14 @@ struct Tn2 {
     static constexpr bool even = (RB % 2) == 0;
     static constexpr int WGP = even ? 2 : 4, WGQ = even ? 2 : 1;
     static constexpr int PB = even ? 2 : 1, QB = even ? RB / 2 : RB;
-    static constexpr int RP = (R + 127) / 128 * 128;        // padded V columns in LDS
-    static constexpr int VPITCH = RP * 2;
-    static constexpr int BKM = R <= 256 ? 64 : 32;          // batch rows per slab
-    static constexpr int slab = BKM * (UPITCH + VPITCH);
+    static constexpr int NCOL = TP + R;                      // columns of a slab: U part, then V part
+    static constexpr int slab = NCOL * BKM * 2;
     static constexpr int lds_bytes = 2 * slab;
-    static constexpr int NU = BKM * (TP / 8) / NLT;          // 16-byte chunks per loader thread, U part
-    static constexpr int NV = (BKM * (R / 8) + NLT - 1) / NLT;   // V part (the last one may be partial)
-    static constexpr bool v_exact = BKM * (R / 8) % NLT == 0;
+    // loader work unit: an 8 x 8 block (8 batch rows x one 16-byte chunk of columns)
+    static constexpr int BPT = NCOL > 320 ? 2 : 1;           // blocks per loader thread
+    static constexpr int NUW = (TP / BPT + 63) / 64;         // loader waves for the U part
+    static constexpr int NVW = (R / BPT + 63) / 64;          // loader waves for the V part
+    static constexpr int NT = 64 * (NMW + NUW + NVW);
     static constexpr int D = 2;                              // slabs in flight in the loaders' register ring
     static_assert(lds_bytes <= 160 * 1024, "slab shape");
 };
@@ -60,11 +57,102 @@ struct Tn2 {
 struct Tn2Job { const uint16_t* U; const uint16_t* V; float* part; int P; int tile_begin; int transposed; };
 struct Tn2Args { Tn2Job job[2]; int njobs; int64_t M; int64_t rows_per_split; };
 
+// LDS slab: column-major, 64 batch rows = 128 bytes per column, two columns per 256-byte line.  The
+// sixteen 16-byte units of a line are XOR-swizzled with bits of the column-pair index p so that
+// sixteen different bank groups are touched both by a loader store (16 lanes = 16 column chunks
+// 8 columns apart, same unit: p bits 2..5 vary) and by an MFMA operand read (16 lanes = 16
+// consecutive columns, same unit: p bits 0..2 and the column parity vary).
+__device__ __forceinline__ int slab_addr(int col, int unit) {
+    const int p = col >> 1;
+    const int swz = ((p ^ (p >> 3)) & 3) | (p & 4) | (((p >> 5) & 1) << 3);
+    const int u16 = (((col & 1) << 3) | unit) ^ swz;
+    return p * 256 + u16 * 16;
+}
+
+// Loader role: moves NCOLS columns (multiple of 8) of a row-major bf16 matrix, 64 batch rows at a
+// time, into LDS columns [col0, col0 + NCOLS) transposed: a thread loads an 8 x 8 block as eight
+// 16-byte row pieces, transposes it in registers, and stores eight 16-byte column pieces.
+template <int NCOLS, int BPT, int D>
+__device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int cols_valid, int col0, int lt,
+                                          int64_t k_begin, int64_t k_end, int np, int slab_bytes,
+                                          unsigned char* lds) {
+    constexpr int NCC = NCOLS / 8;                       // 16-byte chunks per row
+    constexpr int RGS = 8 / BPT;                         // row groups per block index
+    const int cc = lt % NCC, rg0 = lt / NCC;
+    const bool active = rg0 < RGS;
+    // Offsets of the thread's first block; a second block (BPT = 2) lies 32 batch rows further:
+    // 32 rows of `pitch` elements in memory, unit index + 4 = address ^ 64 in the LDS slab.
+    int goff[8], loff[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        // global: row 8 rg + e, columns 8 cc ..; a chunk past the valid columns, or an idle
+        // thread, gets an offset that no descriptor covers and loads zeros
+        goff[e] = (active && cc * 8 < cols_valid) ? ((8 * rg0 + e) * pitch + cc * 8) * 2 : kBufNowhere;
+        loff[e] = slab_addr(col0 + cc * 8 + e, rg0);         // LDS: column 8 cc + e, rows 8 rg .. 8 rg + 7
+    }
+    const int gstep = (active && cc * 8 < cols_valid) ? 32 * pitch * 2 : 0;
+    u32x4 ring[D][BPT][8];
+    auto descriptor = [&](int s) {
+        const int64_t kr0 = k_begin + (int64_t)s * BKM;
+        const int64_t left = k_end - kr0;                // <= 0 past the split: everything reads zeros
+        // the row offset is part of the per-lane offset, the only part the hardware range-checks;
+        // the descriptor ends at the split's last row
+        return make_rsrc(src + kr0 * pitch, left * pitch * 2);
+    };
+    auto load_block = [&](u32x4 (&dst)[8], rsrc_t res, int b) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dst[e] = buf_load16(res, goff[e] + b * gstep, 0);
+    };
+    auto store_block = [&](const u32x4 (&v)[8], unsigned char* base, int b) {
+        // 8 x 8 transpose of 16-bit elements: word i of output column j packs rows 2i, 2i+1
+        u32x4 out[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                out[j][i] = __builtin_amdgcn_perm(v[2 * i + 1][j >> 1], v[2 * i][j >> 1],
+                                                  (j & 1) ? 0x07060302u : 0x05040100u);
+        if (active) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x4*>(base + (loff[j] ^ (b * 64))) = out[j];
+        }
+    };
+    {
+        const rsrc_t res = descriptor(0);
+#pragma unroll
+        for (int b = 0; b < BPT; ++b) { load_block(ring[0][b], res, b); store_block(ring[0][b], lds, b); }
+    }
+#pragma unroll
+    for (int d = 1; d <= D; ++d) {
+        const rsrc_t res = descriptor(d);
+#pragma unroll
+        for (int b = 0; b < BPT; ++b) load_block(ring[d % D][b], res, b);
+    }
+    ring_barrier();                                      // slab 0 is in slot 0
+    for (int s0 = 0; s0 < np; s0 += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int s = s0 + d;
+            TN_STAMP(1, 0, s);
+            unsigned char* base = lds + ((s + 1) & 1) * slab_bytes;    // slab s+1; slot s&1 is being read
+            const rsrc_t res = descriptor(s + 1 + D);
+#pragma unroll
+            for (int b = 0; b < BPT; ++b) {
+                store_block(ring[(d + 1) % D][b], base, b);
+                load_block(ring[(d + 1) % D][b], res, b);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            TN_STAMP(1, 1, s);
+            ring_barrier();
+        }
+    }
+}
+
 template <int R>
-__global__ __launch_bounds__(NT) void tn2_bf16_kernel(Tn2Args args) {
+__global__ __launch_bounds__(Tn2<R>::NT) void tn2_bf16_kernel(Tn2Args args) {
     extern __shared__ __align__(1024) unsigned char lds[];
     using C = Tn2<R>;
-    constexpr int BKM = C::BKM, D = C::D;
+    constexpr int D = C::D;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
     const int jid = (args.njobs > 1 && (int)blockIdx.x >= args.job[1].tile_begin) ? 1 : 0;
@@ -75,81 +163,14 @@ __global__ __launch_bounds__(NT) void tn2_bf16_kernel(Tn2Args args) {
     if (k_end > args.M) k_end = args.M;
     const int64_t nrows = k_end > k_begin ? k_end - k_begin : 0;
     const int nslab = (int)((nrows + BKM - 1) / BKM);
-    const int np = (nslab + D - 1) / D * D;              // trip count of both roles, padded to the ring
+    const int np = (nslab + D - 1) / D * D;              // trip count of every role, padded to the ring
 
-    if (wave >= NMT / 64) {
-        // ================================================================== loader waves
-        // Slabs go global -> register ring -> LDS exactly as they lie in memory.  Buffer loads: the
-        // row offset is part of the per-lane offset, the only part the hardware range-checks, and
-        // the descriptors (rebuilt per slab, scalar work) end at the split's last row, so rows past
-        // it load zeros; a chunk in a column past P gets an offset that no descriptor covers.
-        const int lt = tid - NMT;
-        int uoff[C::NU], usrc[C::NU];
-#pragma unroll
-        for (int e = 0; e < C::NU; ++e) {
-            const int ci = e * NLT + lt;
-            const int row = ci / (TP / 8), ch = ci % (TP / 8);
-            uoff[e] = row * UPITCH + ((((ch >> 2) ^ (row & 3)) << 2) | (ch & 3)) * 16;
-            usrc[e] = p0 + ch * 8 < job.P ? (row * job.P + ch * 8) * 2 : kBufNowhere;
-        }
-        int voff[C::NV], vsrc[C::NV];
-        bool vok[C::NV];
-#pragma unroll
-        for (int e = 0; e < C::NV; ++e) {
-            const int ci = e * NLT + lt;
-            const int row = ci / (R / 8), ch = ci % (R / 8);
-            vok[e] = C::v_exact || ci < BKM * (R / 8);
-            voff[e] = BKM * UPITCH + row * C::VPITCH + ((((ch >> 2) ^ (row & 3)) << 2) | (ch & 3)) * 16;
-            vsrc[e] = vok[e] ? (row * R + ch * 8) * 2 : kBufNowhere;
-        }
-        u32x4 ring[D][C::NU + C::NV];
-        auto load = [&](u32x4 (&dst)[C::NU + C::NV], int s) {
-            const int64_t kr0 = k_begin + (int64_t)s * BKM;
-            const int64_t left = k_end - kr0;                    // <= 0 past the split: everything reads zeros
-            const rsrc_t ures = make_rsrc(job.U + kr0 * job.P + p0, (left * job.P - p0) * 2);
-            const rsrc_t vres = make_rsrc(job.V + kr0 * R, left * R * 2);
-#pragma unroll
-            for (int e = 0; e < C::NU; ++e) dst[e] = buf_load16(ures, usrc[e], 0);
-#pragma unroll
-            for (int e = 0; e < C::NV; ++e) dst[C::NU + e] = buf_load16(vres, vsrc[e], 0);
-        };
-        // steady state: chunk e of slab s+1 goes to LDS (slot s&1 is being read) and the same chunk
-        // of slab s+1+D is requested, alternating, so LDS port and address path work side by side
-        auto step = [&](u32x4 (&rg)[C::NU + C::NV], int s) {
-            unsigned char* base = lds + ((s + 1) & 1) * C::slab;
-            const int64_t kr0 = k_begin + (int64_t)(s + 1 + D) * BKM;
-            const int64_t left = k_end - kr0;
-            const rsrc_t ures = make_rsrc(job.U + kr0 * job.P + p0, (left * job.P - p0) * 2);
-            const rsrc_t vres = make_rsrc(job.V + kr0 * R, left * R * 2);
-#pragma unroll
-            for (int e = 0; e < C::NU; ++e) {
-                *reinterpret_cast<u32x4*>(base + uoff[e]) = rg[e];
-                rg[e] = buf_load16(ures, usrc[e], 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-#pragma unroll
-            for (int e = 0; e < C::NV; ++e) {
-                if (vok[e]) *reinterpret_cast<u32x4*>(base + voff[e]) = rg[C::NU + e];
-                rg[C::NU + e] = buf_load16(vres, vsrc[e], 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        };
-        load(ring[0], 0);
-#pragma unroll
-        for (int e = 0; e < C::NU; ++e) *reinterpret_cast<u32x4*>(lds + uoff[e]) = ring[0][e];
-#pragma unroll
-        for (int e = 0; e < C::NV; ++e)
-            if (vok[e]) *reinterpret_cast<u32x4*>(lds + voff[e]) = ring[0][C::NU + e];
-#pragma unroll
-        for (int d = 1; d <= D; ++d) load(ring[d % D], d);
-        ring_barrier();                                  // slab 0 is in slot 0
-        for (int s0 = 0; s0 < np; s0 += D) {
-#pragma unroll
-            for (int d = 0; d < D; ++d) {
-                step(ring[(d + 1) % D], s0 + d);
-                ring_barrier();
-            }
-        }
+    if (wave >= NMW + C::NUW) {
+        tn_loader<R, C::BPT, D>(job.V, R, R, TP, tid - 64 * (NMW + C::NUW), k_begin, k_end, np, C::slab, lds);
+        return;
+    }
+    if (wave >= NMW) {
+        tn_loader<TP, C::BPT, D>(job.U + p0, job.P, job.P - p0, 0, tid - 64 * NMW, k_begin, k_end, np, C::slab, lds);
         return;
     }
 
@@ -166,40 +187,34 @@ __global__ __launch_bounds__(NT) void tn2_bf16_kernel(Tn2Args args) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
-    // per lane: group g = lane / 16 selects (column half, row half); s = lane % 16
-    const int ls = lane & 15, lg = lane >> 4;
-    const int tr_row = 8 * (lg >> 1) + (ls >> 2);        // + 16 k16 + 4 rd
-    const int tr_col = 16 * (lg & 1) + 4 * (ls & 3);     // + block column
+    // operand addresses inside a slab for k16 = 0; step k16 moves two units on: address ^ (k16 << 5)
+    int uad[C::PB], vad[C::QB];
+#pragma unroll
+    for (int a = 0; a < C::PB; ++a) uad[a] = slab_addr(wp + a * 32 + lj, lh);
+#pragma unroll
+    for (int b = 0; b < C::QB; ++b) vad[b] = slab_addr(TP + wq + b * 32 + lj, lh);
 
     ring_barrier();                                      // slab 0 is in slot 0
     for (int s = 0; s < np; ++s) {
+        TN_STAMP(0, 0, s);
         if (s < nslab) {
-            const unsigned char* ub = lds + (s & 1) * C::slab;
-            const unsigned char* vb = ub + BKM * UPITCH;
+            const unsigned char* base = lds + (s & 1) * C::slab;
 #pragma unroll
             for (int k16 = 0; k16 < BKM / 16; ++k16) {
-                u32x4 uf[C::PB], vf[C::QB];
-                const int row = 16 * k16 + tr_row, row1 = row + 4;
-#pragma unroll
-                for (int a = 0; a < C::PB; ++a) {
-                    const int col = wp + a * 32 + tr_col;
-                    const u32x2 r0 = ds_tr(ub + row * UPITCH + (((col >> 5) ^ (row & 3)) << 6) + (col & 31) * 2);
-                    const u32x2 r1 = ds_tr(ub + row1 * UPITCH + (((col >> 5) ^ (row1 & 3)) << 6) + (col & 31) * 2);
-                    uf[a] = u32x4{r0[0], r0[1], r1[0], r1[1]};
-                }
-#pragma unroll
-                for (int b = 0; b < C::QB; ++b) {
-                    const int col = wq + b * 32 + tr_col;
-                    const u32x2 r0 = ds_tr(vb + row * C::VPITCH + ((((col >> 5) & ~3) | (((col >> 5) & 3) ^ (row & 3))) << 6) + (col & 31) * 2);
-                    const u32x2 r1 = ds_tr(vb + row1 * C::VPITCH + ((((col >> 5) & ~3) | (((col >> 5) & 3) ^ (row1 & 3))) << 6) + (col & 31) * 2);
-                    vf[b] = u32x4{r0[0], r0[1], r1[0], r1[1]};
-                }
+                // lane (lj, lh) takes rows 16 k16 + 8 lh .. + 7 of column (block column + lj)
+                u32x4 uf[C::PB];
 #pragma unroll
                 for (int a = 0; a < C::PB; ++a)
+                    uf[a] = *reinterpret_cast<const u32x4*>(base + (uad[a] ^ (k16 << 5)));
 #pragma unroll
-                    for (int b = 0; b < C::QB; ++b) acc[a][b] = mfma16(uf[a], vf[b], acc[a][b]);
+                for (int b = 0; b < C::QB; ++b) {
+                    const u32x4 vf = *reinterpret_cast<const u32x4*>(base + (vad[b] ^ (k16 << 5)));
+#pragma unroll
+                    for (int a = 0; a < C::PB; ++a) acc[a][b] = mfma16(uf[a], vf, acc[a][b]);
+                }
             }
         }
+        TN_STAMP(0, 1, s);
         ring_barrier();
     }
 
@@ -272,7 +287,7 @@ hipError_t launch_tn2_r(const Tn2Args& args, int tiles, int splits, hipStream_t 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(tn2_bf16_kernel<R>, dim3(tiles, splits), dim3(NT), lds_bytes, s, args);
+    hipLaunchKernelGGL(tn2_bf16_kernel<R>, dim3(tiles, splits), dim3(Tn2<R>::NT), lds_bytes, s, args);
     return hipGetLastError();
 }
 
