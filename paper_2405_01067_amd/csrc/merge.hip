@@ -39,6 +39,7 @@ struct LayerDev {
     double* LA; double* GB; double* LB; double* Ct; double* Yt;
     double* sigma; double* s3; double* s5;
     double* trace;         // [2]: trace(G_A), trace(G_B); their product bounds ||C||_F^2
+    double* nrm;           // [K]: squared column norms of C, refreshed every sweep, updated by rotations
     int* perm;
     float* PA; float* PB;
     int* rotated;          // [kMaxSweepsCap + 1]
@@ -404,7 +405,7 @@ __device__ __forceinline__ double wave_sum(double v) {
 // A column whose squared norm is below `floor2` (1e-26 ||C||_F^2 bound) is numerically zero: it
 // belongs to a singular value below 1e-13 sigma_max and is left alone (rank-deficient cores).
 __device__ __forceinline__ bool jacobi_rotation(double alpha, double beta, double gamma, double floor2,
-                                                double& c, double& s, bool& significant) {
+                                                double& c, double& s, bool& significant, double* tangent = nullptr) {
     const double lim = alpha * beta;
     const double g2 = gamma * gamma;
     significant = false;
@@ -415,6 +416,7 @@ __device__ __forceinline__ bool jacobi_rotation(double alpha, double beta, doubl
     const double tn = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
     c = 1.0 / sqrt(1.0 + tn * tn);
     s = c * tn;
+    if (tangent) *tangent = tn;
     return true;
 }
 
@@ -485,6 +487,111 @@ __global__ __launch_bounds__(1024) void jacobi_cross_kernel(const LayerDev* __re
     if (any_signif && lane == 0) L.rotated[sweep] = 1;
 }
 
+// Sum over each group of 16 consecutive lanes (a DPP row), result in every lane of the group:
+// two quad permutes, then rotations by 4 and 8 lanes inside the row.  No LDS traffic.
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xf, 0xf, false);
+    hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double row16_sum(double v) {
+    v += dpp_f64<0xB1>(v);    // quad_perm [1,0,3,2]
+    v += dpp_f64<0x4E>(v);    // quad_perm [2,3,0,1]
+    v += dpp_f64<0x124>(v);   // row_ror:4
+    v += dpp_f64<0x128>(v);   // row_ror:8
+    return v;
+}
+
+// Cross round for cores with K <= 32 NE2 <= 512 and blocks of 16 columns.  A work-group of 256
+// threads owns one block pair; a group of 16 lanes owns one left column (in registers, two
+// consecutive rows per lane and 32-row stride) and meets the 16 right columns (in LDS) one per step:
+// four column pairs per wave and step, each needing a single inner product reduced over 16 lanes.
+// The squared norms are not recomputed per pair: they are carried along (nrm, refreshed from the data
+// by the intra-block kernel at the start of every sweep) and updated with the rotation,
+// |x'|^2 = |x|^2 - t gamma, |y'|^2 = |y|^2 + t gamma.
+typedef __attribute__((ext_vector_type(2))) double f64x2;
+template <int NE2>
+__global__ __launch_bounds__(256) void jacobi_cross16_kernel(const LayerDev* __restrict__ layers,
+                                                             const int2* __restrict__ wg_map,
+                                                             int sweep, int round) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int2 wm = wg_map[blockIdx.x];                   // (layer, pair slot)
+    const LayerDev& L = layers[wm.x];
+    if (sweep_finished(L, sweep)) return;
+    const int nb = L.nb, K = L.K;
+    if (round >= nb - 1 || L.jb != 16 || K > 32 * NE2) return;
+    int bI, bJ;
+    if (wm.y == 0) { bI = nb - 1; bJ = round; }
+    else { bI = (round + wm.y) % (nb - 1); bJ = (round - wm.y + (nb - 1)) % (nb - 1); }
+    const int pitch = K + 16;                             // columns 128 bytes apart in the banks
+    double* right = reinterpret_cast<double*>(lds_raw);   // [16][pitch]
+    double* rn = right + 16 * pitch;                      // [16] squared norms of the right columns
+    const int tid = threadIdx.x, g = tid >> 4, l16 = tid & 15;
+
+    double* left_col = L.Ct + (int64_t)(bI * 16 + g) * K;
+    double* right_col = L.Ct + (int64_t)(bJ * 16 + g) * K;
+    f64x2 x[NE2];
+#pragma unroll
+    for (int j = 0; j < NE2; ++j) {
+        const int r = 32 * j + 2 * l16;
+        x[j] = f64x2{0.0, 0.0};
+        if (r < K) {
+            x[j] = *reinterpret_cast<const f64x2*>(left_col + r);
+            *reinterpret_cast<f64x2*>(right + g * pitch + r) = *reinterpret_cast<const f64x2*>(right_col + r);
+        }
+    }
+    if (tid < 16) rn[tid] = L.nrm[bJ * 16 + tid];
+    double alpha = L.nrm[bI * 16 + g];
+    __syncthreads();
+
+    const double floor2 = 1e-26 * L.trace[0] * L.trace[1];
+    bool any_signif = false;
+    for (int step = 0; step < 16; ++step) {
+        const int ci = (g + step) & 15;
+        double* ycol = right + ci * pitch;
+        f64x2 y[NE2];
+        double gamma = 0.0;
+#pragma unroll
+        for (int j = 0; j < NE2; ++j) {
+            const int r = 32 * j + 2 * l16;
+            y[j] = f64x2{0.0, 0.0};
+            if (r < K) y[j] = *reinterpret_cast<const f64x2*>(ycol + r);
+            gamma = fma(x[j][0], y[j][0], gamma);
+            gamma = fma(x[j][1], y[j][1], gamma);
+        }
+        gamma = row16_sum(gamma);
+        const double beta = rn[ci];
+        double c, s, t; bool signif;
+        if (jacobi_rotation(alpha, beta, gamma, floor2, c, s, signif, &t)) {
+#pragma unroll
+            for (int j = 0; j < NE2; ++j) {
+                const int r = 32 * j + 2 * l16;
+                const f64x2 xn = {c * x[j][0] - s * y[j][0], c * x[j][1] - s * y[j][1]};
+                const f64x2 yn = {s * x[j][0] + c * y[j][0], s * x[j][1] + c * y[j][1]};
+                x[j] = xn;
+                if (r < K) *reinterpret_cast<f64x2*>(ycol + r) = yn;
+            }
+            alpha -= t * gamma;
+            if (l16 == 0) rn[ci] = beta + t * gamma;
+        }
+        any_signif |= signif;
+        __syncthreads();
+    }
+#pragma unroll
+    for (int j = 0; j < NE2; ++j) {
+        const int r = 32 * j + 2 * l16;
+        if (r < K) {
+            *reinterpret_cast<f64x2*>(left_col + r) = x[j];
+            *reinterpret_cast<f64x2*>(right_col + r) = *reinterpret_cast<const f64x2*>(right + g * pitch + r);
+        }
+    }
+    if (l16 == 0) L.nrm[bI * 16 + g] = alpha;
+    if (tid < 16) L.nrm[bJ * 16 + tid] = rn[tid];
+    if (any_signif && l16 == 0) L.rotated[sweep] = 1;
+}
+
 // All pairs inside one block of jb columns (jb even): jb - 1 rounds of jb / 2 disjoint pairs.
 template <int NX>
 __global__ __launch_bounds__(512) void jacobi_intra_kernel(const LayerDev* __restrict__ layers,
@@ -532,8 +639,16 @@ __global__ __launch_bounds__(512) void jacobi_intra_kernel(const LayerDev* __res
         any_signif |= signif;
         __syncthreads();
     }
-    for (int cidx = wave; cidx < jb; cidx += jb / 2)
-        for (int r = lane; r < K; r += 64) blk[(int64_t)cidx * K + r] = cols[cidx * K + r];
+    for (int cidx = wave; cidx < jb; cidx += jb / 2) {
+        double ss = 0.0;
+        for (int r = lane; r < K; r += 64) {
+            const double v = cols[cidx * K + r];
+            blk[(int64_t)cidx * K + r] = v;
+            ss = fma(v, v, ss);
+        }
+        ss = wave_sum(ss);
+        if (lane == 0) L.nrm[wm.y * jb + cidx] = ss;       // refreshed from the data once per sweep
+    }
     if (any_signif && lane == 0) L.rotated[sweep] = 1;
 }
 
@@ -623,7 +738,7 @@ struct Plan {
     size_t lds_jacobi = 0;  // largest jb * K * 8 over the layers
     struct PerLayer {
         int K, jb, nb;
-        size_t Abar, Bbar, LA, GB, LB, Ct, Yt, sigma, s3, s5, trace, perm, PA, PB;
+        size_t Abar, Bbar, LA, GB, LB, Ct, Yt, sigma, s3, s5, trace, nrm, perm, PA, PB;
     };
     std::vector<PerLayer> pl;
 };
@@ -678,6 +793,7 @@ Plan make_plan(const abt_merge_desc* layers, int L) {
         q.s3 = take(sizeof(double) * K);
         q.s5 = take(sizeof(double) * K);
         q.trace = take(sizeof(double) * 2);
+        q.nrm = take(sizeof(double) * K);
         q.perm = take(sizeof(int) * K);
         q.PA = take(sizeof(float) * K * kc);
         q.PB = take(sizeof(float) * kc * K);
@@ -702,6 +818,25 @@ hipError_t launch_jacobi_sweep(const Plan& p, const LayerDev* dl, const int2* cr
     }
     hipLaunchKernelGGL(jacobi_intra_kernel<NX>, dim3(p.n_wg_intra), dim3(64 * (p.jb_max / 2)), lds_cross, s,
                        dl, intra, sweep);
+    if (p.K_max <= 512) {
+        // every layer has blocks of 16 columns: the 16-lane-group kernel, sized for the widest core
+        const size_t lds16 = sizeof(double) * (16 * (size_t)(p.K_max + 16) + 16);
+        auto run = [&](auto kern) -> hipError_t {
+            static size_t attr16 = 0;
+            if (lds16 > attr16) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds16);
+                if (e != hipSuccess) return e;
+                attr16 = lds16;
+            }
+            for (int round = 0; round < p.nb_max - 1; ++round)
+                hipLaunchKernelGGL(kern, dim3(p.n_wg_cross), dim3(256), lds16, s, dl, cross, sweep, round);
+            return hipGetLastError();
+        };
+        if (p.K_max <= 256) return run(&jacobi_cross16_kernel<8>);
+        if (p.K_max <= 384) return run(&jacobi_cross16_kernel<12>);
+        return run(&jacobi_cross16_kernel<16>);
+    }
     for (int round = 0; round < p.nb_max - 1; ++round)
         hipLaunchKernelGGL(jacobi_cross_kernel<NX>, dim3(p.n_wg_cross), dim3(64 * p.jb_max), lds_cross, s,
                            dl, cross, sweep, round);
@@ -754,6 +889,7 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
         v.Ct = (double*)(ws + q.Ct); v.Yt = (double*)(ws + q.Yt);
         v.sigma = (double*)(ws + q.sigma); v.s3 = (double*)(ws + q.s3); v.s5 = (double*)(ws + q.s5);
         v.trace = (double*)(ws + q.trace);
+        v.nrm = (double*)(ws + q.nrm);
         v.perm = (int*)(ws + q.perm);
         v.PA = (float*)(ws + q.PA); v.PB = (float*)(ws + q.PB);
         v.rotated = (int*)(ws + p.off_rotated) + (size_t)l * (kMaxSweepsCap + 1);
