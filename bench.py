@@ -33,6 +33,9 @@ def main():
     ap.add_argument("--merge-iters", type=int, default=3)
     ap.add_argument("--no-merge", action="store_true", help="skip the ab_merge timing")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--pmc-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy: the reference dispatch that scales the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time every config-3 / config-4 case (extra key `cases`)")
     args = ap.parse_args()
@@ -126,7 +129,7 @@ def main():
     bwd_avg, bwd_med, bwd_min = event_ms(step.bwd, min(args.steps, 100))
     achieved_gbs = step.bytes_fwd / (fwd_avg * 1e-3) / 1e9
     roofline = {
-        "kernel": "chain_bf16_kernel<192> (lr_linear_fwd: T = X B^T, Y = T A^T fused)",
+        "kernel": "chain2_bf16_kernel<192> (lr_linear_fwd: T = X B^T, Y = T A^T fused, one launch per call)",
         "bound": "hbm", "achieved": round(achieved_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
         "frac": round(achieved_gbs / PEAK_HBM_GBS, 4), "traffic": None,
         "algorithmic_bytes_per_launch": step.bytes_fwd,
@@ -148,6 +151,14 @@ def main():
         "step_hbm_frac": round((step.bytes_fwd + step.bytes_bwd) / sec / 1e9 / PEAK_HBM_GBS, 4),
         "roofline": roofline,
     }
+
+    if args.pmc_copy:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ------------------------------------------------------------------ optional: configs 3 and 4
     if args.all_configs:
@@ -214,14 +225,17 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             cores = os.cpu_count() or 1
+        reps = 0
         t0 = time.perf_counter()
-        orc.lr_linear_fwd(c2["X"], c2["A"], c2["B"])
-        orc.lr_linear_bwd(c2["dY"], c2["X"], c2["A"], c2["B"])
-        cpu_s = time.perf_counter() - t0
+        while reps < 3 or (time.perf_counter() - t0 < 10.0 and reps < 200):
+            orc.lr_linear_fwd(c2["X"], c2["A"], c2["B"])
+            orc.lr_linear_bwd(c2["dY"], c2["X"], c2["A"], c2["B"])
+            reps += 1
+        cpu_s = (time.perf_counter() - t0) / reps
         out["cpu_baseline"] = {"value": round(step.flops / cpu_s / 1e12, 4), "unit": "TFLOP/s", "cores": cores,
                                "kind": "oracle",
-                               "sample": "the full config-2 step once (fwd + bwd, fp64 NumPy/OpenBLAS), "
-                                         f"{cpu_s:.2f} s"}
+                               "sample": f"the full config-2 step (fwd + bwd, fp64 NumPy/OpenBLAS) {reps} times, "
+                                         f"{cpu_s:.3f} s each"}
         if not args.no_merge:
             block = [gen.merge_layer(m, n, seed) for idx, name, m, n, seed in gen.config5_layers()[:4]]
             t0 = time.perf_counter()

@@ -17,7 +17,7 @@
 
 #ifdef ABT_TIMING
 __device__ long long abt_tn_tl[2][2][64];
-#define TN_STAMP(role, k, it) do { if (blockIdx.x == 3 && blockIdx.y == 2 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 4 : 0) && (it) < 64) abt_tn_tl[role][k][it] = __builtin_readcyclecounter(); } while (0)
+#define TN_STAMP(role, k, it) do { if (blockIdx.x == 26 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 4 : 0) && (it) < 64) abt_tn_tl[role][k][it] = __builtin_readcyclecounter(); } while (0)
 #else
 #define TN_STAMP(role, k, it) do {} while (0)
 #endif
@@ -55,7 +55,7 @@ struct Tn2 {
 };
 
 struct Tn2Job { const uint16_t* U; const uint16_t* V; float* part; int P; int tile_begin; int transposed; };
-struct Tn2Args { Tn2Job job[2]; int njobs; int64_t M; int64_t rows_per_split; };
+struct Tn2Args { Tn2Job job[2]; int njobs; int tiles; int splits; int64_t M; int64_t rows_per_split; };
 
 // LDS slab: column-major, 64 batch rows = 128 bytes per column, two columns per 256-byte line.  The
 // sixteen 16-byte units of a line are XOR-swizzled with bits of the column-pair index p so that
@@ -155,10 +155,16 @@ __global__ __launch_bounds__(Tn2<R>::NT) void tn2_bf16_kernel(Tn2Args args) {
     constexpr int D = C::D;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    const int jid = (args.njobs > 1 && (int)blockIdx.x >= args.job[1].tile_begin) ? 1 : 0;
+    // Work-groups are dealt to the eight XCDs round-robin by their linear index, and each XCD has
+    // its own L2: all column tiles of one row split go to the same XCD, so the V rows they share
+    // are fetched from HBM once, not once per XCD.
+    const int xcd = (int)blockIdx.x & 7, slot = (int)blockIdx.x >> 3;
+    const int tile = slot % args.tiles, split = xcd + 8 * (slot / args.tiles);
+    if (split >= args.splits) return;
+    const int jid = (args.njobs > 1 && tile >= args.job[1].tile_begin) ? 1 : 0;
     const Tn2Job job = args.job[jid];
-    const int p0 = ((int)blockIdx.x - job.tile_begin) * TP;
-    const int64_t k_begin = (int64_t)blockIdx.y * args.rows_per_split;
+    const int p0 = (tile - job.tile_begin) * TP;
+    const int64_t k_begin = (int64_t)split * args.rows_per_split;
     int64_t k_end = k_begin + args.rows_per_split;
     if (k_end > args.M) k_end = args.M;
     const int64_t nrows = k_end > k_begin ? k_end - k_begin : 0;
@@ -219,7 +225,7 @@ __global__ __launch_bounds__(Tn2<R>::NT) void tn2_bf16_kernel(Tn2Args args) {
     }
 
     // accumulator v of block (a,b): U column p0 + wp + 32a + 8(v/4) + 4 lh + v%4, V column wq + 32b + lj
-    float* part = job.part + (int64_t)blockIdx.y * job.P * R;
+    float* part = job.part + (int64_t)split * job.P * R;
 #pragma unroll
     for (int a = 0; a < C::PB; ++a)
 #pragma unroll
@@ -287,7 +293,7 @@ hipError_t launch_tn2_r(const Tn2Args& args, int tiles, int splits, hipStream_t 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(tn2_bf16_kernel<R>, dim3(tiles, splits), dim3(Tn2<R>::NT), lds_bytes, s, args);
+    hipLaunchKernelGGL(tn2_bf16_kernel<R>, dim3(8 * tiles * ((splits + 7) / 8)), dim3(Tn2<R>::NT), lds_bytes, s, args);
     return hipGetLastError();
 }
 
@@ -308,6 +314,7 @@ hipError_t launch_tn_bf16(const TnJob* jobs, int njobs, int64_t M, int R, int ac
     Tn2Args args{};
     Red2Args red{};
     args.njobs = red.njobs = njobs;
+    args.tiles = tiles; args.splits = splits;
     args.M = M;
     int64_t rps = ceil_div(M, splits);
     rps = ceil_div(rps, 64) * 64;
