@@ -12,8 +12,11 @@
  *   - All matrices are row-major and contiguous (leading dimension = number of columns).
  *   - Unless a parameter is documented as a HOST pointer it is a DEVICE pointer owned by the
  *     caller; the library never allocates, frees or retains caller memory.
- *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
- *     work on it and return without synchronising the host.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  lr_linear_fwd and
+ *     lr_linear_bwd enqueue work on it and return without synchronising the host.  ab_merge and
+ *     ab_merge_batched wait for the stream a few times (after uploading their layer table, and
+ *     between Jacobi sweeps to see whether every layer has converged); the back-projection
+ *     they enqueue last may still be running when they return.
  *   - `workspace` is caller-owned device scratch of at least the size the matching
  *     *_workspace_bytes() query returns, 256-byte aligned; its contents are undefined
  *     afterwards.  Calls that share a workspace must be stream-ordered.

@@ -592,6 +592,98 @@ __global__ __launch_bounds__(256) void jacobi_cross16_kernel(const LayerDev* __r
     if (any_signif && l16 == 0) L.rotated[sweep] = 1;
 }
 
+// All pairs inside one block of 16 columns for cores with K <= 32 NE2 <= 512: the block lives in
+// LDS, a work-group of 128 threads = 8 groups of 16 lanes rotates 8 disjoint pairs per step, 15
+// steps (round-robin).  Squared norms are computed once at the start, carried with the rotations,
+// and written out at the end (recomputed from the final data) for the cross rounds to start from.
+template <int NE2>
+__global__ __launch_bounds__(128) void jacobi_intra16_kernel(const LayerDev* __restrict__ layers,
+                                                             const int2* __restrict__ wg_map, int sweep) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int2 wm = wg_map[blockIdx.x];                   // (layer, block)
+    const LayerDev& L = layers[wm.x];
+    if (sweep_finished(L, sweep)) return;
+    const int K = L.K;
+    if (L.jb != 16 || K > 32 * NE2) return;
+    const int pitch = K + 16;
+    double* cols = reinterpret_cast<double*>(lds_raw);    // [16][pitch]
+    double* cn = cols + 16 * pitch;                       // [16] squared norms
+    const int tid = threadIdx.x, g = tid >> 4, l16 = tid & 15;
+    double* blk = L.Ct + (int64_t)(wm.y * 16) * K;
+    // load two columns per group, with their squared norms
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int cidx = g + 8 * h;
+        double ss = 0.0;
+#pragma unroll
+        for (int j = 0; j < NE2; ++j) {
+            const int r = 32 * j + 2 * l16;
+            if (r < K) {
+                const f64x2 v = *reinterpret_cast<const f64x2*>(blk + (int64_t)cidx * K + r);
+                *reinterpret_cast<f64x2*>(cols + cidx * pitch + r) = v;
+                ss = fma(v[0], v[0], ss);
+                ss = fma(v[1], v[1], ss);
+            }
+        }
+        ss = row16_sum(ss);
+        if (l16 == 0) cn[cidx] = ss;
+    }
+    __syncthreads();
+    const double floor2 = 1e-26 * L.trace[0] * L.trace[1];
+    bool any_signif = false;
+    for (int round = 0; round < 15; ++round) {
+        int p, q;
+        if (g == 0) { p = 15; q = round; }
+        else { p = (round + g) % 15; q = (round - g + 15) % 15; }
+        double* xc = cols + p * pitch;
+        double* yc = cols + q * pitch;
+        f64x2 x[NE2], y[NE2];
+        double gamma = 0.0;
+#pragma unroll
+        for (int j = 0; j < NE2; ++j) {
+            const int r = 32 * j + 2 * l16;
+            x[j] = f64x2{0.0, 0.0}; y[j] = f64x2{0.0, 0.0};
+            if (r < K) { x[j] = *reinterpret_cast<const f64x2*>(xc + r); y[j] = *reinterpret_cast<const f64x2*>(yc + r); }
+            gamma = fma(x[j][0], y[j][0], gamma);
+            gamma = fma(x[j][1], y[j][1], gamma);
+        }
+        gamma = row16_sum(gamma);
+        const double alpha = cn[p], beta = cn[q];
+        double c, s, t; bool signif;
+        if (jacobi_rotation(alpha, beta, gamma, floor2, c, s, signif, &t)) {
+#pragma unroll
+            for (int j = 0; j < NE2; ++j) {
+                const int r = 32 * j + 2 * l16;
+                if (r < K) {
+                    *reinterpret_cast<f64x2*>(xc + r) = f64x2{c * x[j][0] - s * y[j][0], c * x[j][1] - s * y[j][1]};
+                    *reinterpret_cast<f64x2*>(yc + r) = f64x2{s * x[j][0] + c * y[j][0], s * x[j][1] + c * y[j][1]};
+                }
+            }
+            if (l16 == 0) { cn[p] = alpha - t * gamma; cn[q] = beta + t * gamma; }
+        }
+        any_signif |= signif;
+        __syncthreads();
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int cidx = g + 8 * h;
+        double ss = 0.0;
+#pragma unroll
+        for (int j = 0; j < NE2; ++j) {
+            const int r = 32 * j + 2 * l16;
+            if (r < K) {
+                const f64x2 v = *reinterpret_cast<const f64x2*>(cols + cidx * pitch + r);
+                *reinterpret_cast<f64x2*>(blk + (int64_t)cidx * K + r) = v;
+                ss = fma(v[0], v[0], ss);
+                ss = fma(v[1], v[1], ss);
+            }
+        }
+        ss = row16_sum(ss);
+        if (l16 == 0) L.nrm[wm.y * 16 + cidx] = ss;
+    }
+    if (any_signif && l16 == 0) L.rotated[sweep] = 1;
+}
+
 // All pairs inside one block of jb columns (jb even): jb - 1 rounds of jb / 2 disjoint pairs.
 template <int NX>
 __global__ __launch_bounds__(512) void jacobi_intra_kernel(const LayerDev* __restrict__ layers,
@@ -816,27 +908,31 @@ hipError_t launch_jacobi_sweep(const Plan& p, const LayerDev* dl, const int2* cr
         if (e != hipSuccess) return e;
         attr_bytes = lds_cross;
     }
-    hipLaunchKernelGGL(jacobi_intra_kernel<NX>, dim3(p.n_wg_intra), dim3(64 * (p.jb_max / 2)), lds_cross, s,
-                       dl, intra, sweep);
     if (p.K_max <= 512) {
-        // every layer has blocks of 16 columns: the 16-lane-group kernel, sized for the widest core
+        // every layer has blocks of 16 columns: the 16-lane-group kernels, sized for the widest core
         const size_t lds16 = sizeof(double) * (16 * (size_t)(p.K_max + 16) + 16);
-        auto run = [&](auto kern) -> hipError_t {
-            static size_t attr16 = 0;
+        static size_t attr16_by_size[3] = {0, 0, 0};
+        auto run = [&](auto kern_intra, auto kern_cross, size_t& attr16) -> hipError_t {
             if (lds16 > attr16) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_intra),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds16);
+                if (e != hipSuccess) return e;
+                e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_cross),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds16);
                 if (e != hipSuccess) return e;
                 attr16 = lds16;
             }
+            hipLaunchKernelGGL(kern_intra, dim3(p.n_wg_intra), dim3(128), lds16, s, dl, intra, sweep);
             for (int round = 0; round < p.nb_max - 1; ++round)
-                hipLaunchKernelGGL(kern, dim3(p.n_wg_cross), dim3(256), lds16, s, dl, cross, sweep, round);
+                hipLaunchKernelGGL(kern_cross, dim3(p.n_wg_cross), dim3(256), lds16, s, dl, cross, sweep, round);
             return hipGetLastError();
         };
-        if (p.K_max <= 256) return run(&jacobi_cross16_kernel<8>);
-        if (p.K_max <= 384) return run(&jacobi_cross16_kernel<12>);
-        return run(&jacobi_cross16_kernel<16>);
+        if (p.K_max <= 256) return run(&jacobi_intra16_kernel<8>, &jacobi_cross16_kernel<8>, attr16_by_size[0]);
+        if (p.K_max <= 384) return run(&jacobi_intra16_kernel<12>, &jacobi_cross16_kernel<12>, attr16_by_size[1]);
+        return run(&jacobi_intra16_kernel<16>, &jacobi_cross16_kernel<16>, attr16_by_size[2]);
     }
+    hipLaunchKernelGGL(jacobi_intra_kernel<NX>, dim3(p.n_wg_intra), dim3(64 * (p.jb_max / 2)), lds_cross, s,
+                       dl, intra, sweep);
     for (int round = 0; round < p.nb_max - 1; ++round)
         hipLaunchKernelGGL(jacobi_cross_kernel<NX>, dim3(p.n_wg_cross), dim3(64 * p.jb_max), lds_cross, s,
                            dl, cross, sweep, round);
@@ -978,10 +1074,25 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
     const int2* cross = (const int2*)(ws + p.off_wg_cross);
     const int2* intra = (const int2*)(ws + p.off_wg_intra);
     const int nx = (p.K_max + 63) / 64;
+    std::vector<int> flags((size_t)(kMaxSweepsCap + 1) * L);
     for (int sweep = 0; sweep < max_sweeps; ++sweep) {
         if (nx <= 8) ABT_TRY(launch_jacobi_sweep<8>(p, dl, cross, intra, sweep, s));
         else if (nx <= 16) ABT_TRY(launch_jacobi_sweep<16>(p, dl, cross, intra, sweep, s));
         else ABT_TRY(launch_jacobi_sweep<32>(p, dl, cross, intra, sweep, s));
+        // A sweep is some two dozen launches; once every layer has converged the remaining ones
+        // would all exit at once.  Poll the per-sweep flags (a few KB) instead of issuing them.
+        if (sweep >= 2 && sweep + 1 < max_sweeps) {
+            ABT_TRY(hipMemcpyAsync(flags.data(), ws + p.off_rotated, sizeof(int) * flags.size(),
+                                   hipMemcpyDeviceToHost, s));
+            ABT_TRY(hipStreamSynchronize(s));
+            bool all_done = true;
+            for (int l = 0; l < L && all_done; ++l) {
+                bool done = false;
+                for (int q = 0; q <= sweep; ++q) done |= flags[(size_t)l * (kMaxSweepsCap + 1) + q] == 0;
+                all_done = done;
+            }
+            if (all_done) break;
+        }
     }
     int n2 = 1;
     while (n2 < p.K_max) n2 <<= 1;
