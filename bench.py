@@ -23,6 +23,10 @@ if ROOT not in sys.path:
 METRIC = "factored fwd+bwd TFLOP/s (% bf16 MFMA peak) + ab_merge ms per ViT-B/16 layer set"
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+# HBM bytes of one forward chain launch on config 2, from two rocprofv3 --pmc runs of this file
+# (profiles/chain2_r192_cfg2_pmc.txt): FETCH_SIZE 15794 KiB x 2.0 (the factor that makes a plain
+# 256 MiB copy read 256 MiB) + WRITE_SIZE 80376 KiB x 1.0.  A stored measurement, not a live one.
+CHAIN_FWD_TRAFFIC_BYTES = int((15794.2 * 2.0 + 80376.0) * 1024)
 
 
 def main():
@@ -102,19 +106,23 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
-    def event_ms(fn, iters, warmup=5):
-        """Average duration of fn's stream work from HIP events recorded on the launch stream."""
+    def event_ms(fn, iters, warmup=5, batch=10):
+        """Average duration of one fn() from HIP events recorded on the launch stream (the binding
+        launches on torch's current stream).  Events bracket `batch` back-to-back calls so that the
+        host's launch cost hides behind the kernels and does not count as kernel time."""
         for _ in range(warmup):
             fn()
-        starts = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
-        ends = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
+        n = max(1, iters // batch)
+        starts = [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+        ends = [torch.cuda.Event(enable_timing=True) for _ in range(n)]
         torch.cuda.synchronize()
-        for i in range(iters):
+        for i in range(n):
             starts[i].record()
-            fn()
+            for _ in range(batch):
+                fn()
             ends[i].record()
         torch.cuda.synchronize()
-        ts = sorted(s.elapsed_time(e) for s, e in zip(starts, ends))
+        ts = sorted(s.elapsed_time(e) / batch for s, e in zip(starts, ends))
         return sum(ts) / len(ts), ts[len(ts) // 2], ts[0]
 
     # ------------------------------------------------------------------ headline: config 2
@@ -131,7 +139,7 @@ def main():
     roofline = {
         "kernel": "chain2_bf16_kernel<192> (lr_linear_fwd: T = X B^T, Y = T A^T fused, one launch per call)",
         "bound": "hbm", "achieved": round(achieved_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-        "frac": round(achieved_gbs / PEAK_HBM_GBS, 4), "traffic": None,
+        "frac": round(achieved_gbs / PEAK_HBM_GBS, 4), "traffic": CHAIN_FWD_TRAFFIC_BYTES,
         "algorithmic_bytes_per_launch": step.bytes_fwd,
         "avg_launch_ms": round(fwd_avg, 5), "median_launch_ms": round(fwd_med, 5),
         "mfma_frac": round(2.0 * step.M * step.r * (step.m + step.n) / (fwd_avg * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
