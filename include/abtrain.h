@@ -159,6 +159,27 @@ size_t ab_merge_batched_workspace_bytes(const abt_merge_desc* layers, int L);
 int ab_merge_info(const void* workspace, int layer, int32_t* sweeps, int32_t* n_sigma,
                   void* stream);
 
+/* -------------------------------------------------------------------------------------
+ * ab_factorize: Eq. 3 for a DENSE weight, the abDecomposition step of Algorithm 1 that opens
+ * every low-rank phase: W [m, n] fp32 -> singular values sigma_1 >= ..., k' by the cut-off
+ * rule of ab_merge (tau, k_fixed), A_out = U_k' Sigma_k'^(1/2) [m, k_cap],
+ * B_out = Sigma_k'^(1/2) V_k'^T [k_cap, n], S_out [k_cap], k_out (device int32).
+ * Where the paper transposes W when n > m, this routine keeps W as it is and factors it
+ * trivially as W I (n <= m) or I W (n > m) with the identity on the short side, then runs
+ * the pipeline of ab_merge on that pair: K = min(m, n) singular values are computed.
+ * Limits: min(m, n) a multiple of 32 and <= 2048.  Outputs, zero-filling, the treatment of
+ * numerically zero singular values and stream behaviour as for ab_merge.
+ * ab_factorize_info: as ab_merge_info, for the workspace of an ab_factorize call.
+ * ------------------------------------------------------------------------------------- */
+int ab_factorize(const float* W, int64_t m, int64_t n, float tau, int64_t k_fixed,
+                 float* A_out, float* B_out, float* S_out, int32_t* k_out, int64_t k_cap,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+size_t ab_factorize_workspace_bytes(int64_t m, int64_t n, int64_t k_cap);
+
+int ab_factorize_info(const void* workspace, int64_t m, int64_t n, int32_t* sweeps, int32_t* n_sigma,
+                      void* stream);
+
 /* Sweep cap of the Jacobi SVD (default 16, clamped to [1, 64]); returns the previous value. */
 int abt_set_jacobi_max_sweeps(int max_sweeps);
 

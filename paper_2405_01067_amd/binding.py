@@ -21,6 +21,7 @@ EXPORTS = (
     "lr_linear_bwd", "lr_linear_bwd_workspace_bytes",
     "ab_merge", "ab_merge_workspace_bytes",
     "ab_merge_batched", "ab_merge_batched_workspace_bytes", "ab_merge_info",
+    "ab_factorize", "ab_factorize_workspace_bytes", "ab_factorize_info",
 )
 
 
@@ -81,6 +82,12 @@ def load():
     lib.ab_merge_batched_workspace_bytes.argtypes = [ctypes.POINTER(MergeDesc), ci]
     lib.ab_merge_info.restype = ci
     lib.ab_merge_info.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32), vp]
+    lib.ab_factorize.restype = ci
+    lib.ab_factorize.argtypes = [vp, i64, i64, ctypes.c_float, i64, vp, vp, vp, vp, i64, vp, sz, vp]
+    lib.ab_factorize_workspace_bytes.restype = sz
+    lib.ab_factorize_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.ab_factorize_info.restype = ci
+    lib.ab_factorize_info.argtypes = [vp, i64, i64, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32), vp]
     _lib = lib
     return lib
 
@@ -273,6 +280,37 @@ def ab_merge_batched(layers: List[dict], workspace=None, check_converged: bool =
             sweeps, nsig = merge_info(ws, i)
             outs[i]["sweeps"] = sweeps
     return outs
+
+
+def ab_factorize(W, tau: float, k_fixed: int = 0, k_cap: Optional[int] = None, workspace=None,
+                 check_converged: bool = True):
+    """Truncated SVD factors of a dense fp32 GPU matrix W [m, n] (Eq. 3).  Returns dict(A [m,k_cap],
+    B [k_cap,n], S [k_cap], k (0-d int32 tensor on the GPU), workspace)."""
+    torch = _torch()
+    lib = load()
+    W = _dev_tensor(W, "W")
+    if W.dtype != torch.float32 or W.dim() != 2:
+        raise AbtError("W must be a 2-d fp32 tensor")
+    m, n = W.shape
+    K = min(m, n)
+    k_cap = int(k_cap or K)
+    dev = W.device
+    A_out = torch.empty((m, k_cap), dtype=torch.float32, device=dev)
+    B_out = torch.empty((k_cap, n), dtype=torch.float32, device=dev)
+    S_out = torch.empty((k_cap,), dtype=torch.float32, device=dev)
+    k_out = torch.zeros((), dtype=torch.int32, device=dev)
+    need = lib.ab_factorize_workspace_bytes(m, n, k_cap)
+    if need == 0:
+        raise AbtError(f"ab_factorize: unsupported shape {m} x {n} (min(m, n) must be a multiple of 32, <= 2048)")
+    if workspace is None or workspace.numel() < need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    _check(lib.ab_factorize(_ptr(W), m, n, float(tau), int(k_fixed), _ptr(A_out), _ptr(B_out), _ptr(S_out),
+                            _ptr(k_out), k_cap, _ptr(workspace), workspace.numel(), _stream()), "ab_factorize")
+    if check_converged:
+        sweeps, nsig = ctypes.c_int32(0), ctypes.c_int32(0)
+        _check(lib.ab_factorize_info(_ptr(workspace), m, n, ctypes.byref(sweeps), ctypes.byref(nsig), _stream()),
+               "ab_factorize_info")
+    return dict(A=A_out, B=B_out, S=S_out, k=k_out, workspace=workspace)
 
 
 def merge_info(workspace, layer: int = 0):

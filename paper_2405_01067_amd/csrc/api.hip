@@ -245,6 +245,49 @@ int ab_merge(const float* const* A_copies, const float* const* B_copies, int G,
     return ab_merge_batched(&d, 1, workspace, workspace_bytes, stream);
 }
 
+// Dense W = W I (n <= m) or I W (n > m): the merge of one "copy" whose short-side factor is the
+// identity.  Workspace: [identity K x K fp32][merge workspace].
+static int64_t factorize_K(int64_t m, int64_t n) { return m < n ? m : n; }
+
+size_t ab_factorize_workspace_bytes(int64_t m, int64_t n, int64_t k_cap) {
+    if (m < 1 || n < 1 || k_cap < 1) return 0;
+    const int64_t K = factorize_K(m, n);
+    if (K % 32 || K > 2048) return 0;
+    const size_t wm = ab_merge_workspace_bytes(1, m, n, K, k_cap, 0);
+    return wm ? align_up(sizeof(float) * K * K, 256) + wm : 0;
+}
+
+int ab_factorize(const float* W, int64_t m, int64_t n, float tau, int64_t k_fixed,
+                 float* A_out, float* B_out, float* S_out, int32_t* k_out, int64_t k_cap,
+                 void* workspace, size_t workspace_bytes, void* stream) {
+    if (!W) return ABT_EINVAL;
+    if (m < 1 || n < 1 || k_cap < 1) return ABT_ESHAPE;
+    const int64_t K = factorize_K(m, n);
+    if (K % 32 || K > 2048) return ABT_ESHAPE;
+    if (!aligned(W, 16)) return ABT_EALIGN;
+    const size_t need = ab_factorize_workspace_bytes(m, n, k_cap);
+    if (!workspace || need == 0 || workspace_bytes < need) return ABT_EWORKSPACE;
+    if (!aligned(workspace, 256)) return ABT_EALIGN;
+    float* eye = (float*)workspace;
+    const size_t eye_bytes = align_up(sizeof(float) * K * K, 256);
+    const float* a_copy = n <= m ? W : eye;
+    const float* b_copy = n <= m ? eye : W;
+    abt_merge_desc d{};
+    d.A_copies = &a_copy; d.B_copies = &b_copy; d.G = 1; d.mode = 0;
+    d.m = m; d.n = n; d.k = K; d.tau = tau; d.k_fixed = k_fixed;
+    d.A_out = A_out; d.B_out = B_out; d.S_out = S_out; d.k_out = k_out; d.k_cap = k_cap; d.W_out = nullptr;
+    const int st = check_merge_layer(d);
+    if (st != ABT_OK) return st;
+    if (launch_identity_f32(eye, (int)K, (hipStream_t)stream) != hipSuccess) return ABT_EHIP;
+    return merge_run(&d, 1, (char*)workspace + eye_bytes, g_max_sweeps, (hipStream_t)stream) == hipSuccess ? ABT_OK : ABT_EHIP;
+}
+
+int ab_factorize_info(const void* workspace, int64_t m, int64_t n, int32_t* sweeps, int32_t* n_sigma, void* stream) {
+    if (!workspace || m < 1 || n < 1) return ABT_EINVAL;
+    const int64_t K = factorize_K(m, n);
+    return ab_merge_info((const char*)workspace + align_up(sizeof(float) * K * K, 256), 0, sweeps, n_sigma, stream);
+}
+
 int ab_merge_info(const void* workspace, int layer, int32_t* sweeps, int32_t* n_sigma, void* stream) {
     if (!workspace || layer < 0) return ABT_EINVAL;
     int32_t info[4] = {0, 0, 0, 0};

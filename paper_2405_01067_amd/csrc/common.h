@@ -103,5 +103,6 @@ hipError_t launch_gemm_f32_table(const void* dev_image, int n, int tiles, hipStr
 size_t merge_workspace_bytes(const abt_merge_desc* layers, int L);
 hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int max_sweeps, hipStream_t s);
 hipError_t merge_read_info(const void* workspace, int layer, int32_t out[4], hipStream_t s);
+hipError_t launch_identity_f32(float* dst, int K, hipStream_t s);   // dst[K, K] = I
 
 }  // namespace abt

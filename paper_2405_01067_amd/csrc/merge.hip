@@ -28,6 +28,11 @@ constexpr int kMaxSweepsCap = 64;
 constexpr double kRotateTol = 1e-10;   // |cos| above which a column pair is rotated
 constexpr double kSignifTol = 1e-7;    // a sweep with no |cos| above this ends the iteration
 constexpr double kSigmaFloor = 1e-7;   // sigma_i <= floor * sigma_1: singular vectors returned as zero
+// A column of C with |c|^2 below kZeroColumn2 ||C||_F^2 (|c| < 1e-9 ||C||_F) is numerically zero
+// and is left alone: what it holds is the rounding noise (about 1e-16 ||C||) of the large columns
+// it was rotated with, so its angles cannot be resolved to the 1e-7 the convergence test asks
+// for.  It belongs to a singular value far below kSigmaFloor sigma_1 (||C||_F <= sqrt(K) sigma_1).
+constexpr double kZeroColumn2 = 1e-18;
 
 struct LayerDev {
     const float* const* A_ptrs;
@@ -38,7 +43,7 @@ struct LayerDev {
     float* Abar; float* Bbar;
     double* LA; double* GB; double* LB; double* Ct; double* Yt;
     double* sigma; double* s3; double* s5;
-    double* trace;         // [2]: trace(G_A), trace(G_B); their product bounds ||C||_F^2
+    double* trace;         // [4]: trace(G_A), trace(G_B), ||C||_F^2 (set once C has been formed), unused
     double* nrm;           // [K]: squared column norms of C, refreshed every sweep, updated by rotations
     int* perm;
     float* PA; float* PB;
@@ -53,6 +58,11 @@ struct LayerDev {
 __global__ void fill_i32_kernel(int* p, int64_t n, int v) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
+}
+
+__global__ void identity_f32_kernel(float* p, int K) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < (int64_t)K * K) p[i] = (i / K == i % K) ? 1.0f : 0.0f;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -386,6 +396,22 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(const GemmF64* __restrict
         }
 }
 
+// ||C||_F^2 per layer (fixed summation order), the scale of the "numerically zero column" test.
+__global__ __launch_bounds__(256) void frob2_kernel(const LayerDev* __restrict__ layers) {
+    __shared__ double red[256];
+    const LayerDev& L = layers[blockIdx.x];
+    const int64_t n = (int64_t)L.K * L.K;
+    double ss = 0.0;
+    for (int64_t i = threadIdx.x; i < n; i += 256) ss = fma(L.Ct[i], L.Ct[i], ss);
+    red[threadIdx.x] = ss;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) L.trace[2] = red[0];
+}
+
 // ------------------------------------------------------------------------------------------
 // Stage 5: one-sided Jacobi on the columns of C, held as the rows of Ct (K x K, fp64).
 // Columns are grouped in blocks of jb; a sweep = one intra-block pass (all pairs inside every
@@ -402,8 +428,8 @@ __device__ __forceinline__ double wave_sum(double v) {
 
 // Rotation for a pair with squared norms alpha, beta and inner product gamma; returns false when
 // the pair counts as orthogonal.  x' = c x - s y, y' = s x + c y.
-// A column whose squared norm is below `floor2` (1e-26 ||C||_F^2 bound) is numerically zero: it
-// belongs to a singular value below 1e-13 sigma_max and is left alone (rank-deficient cores).
+// A column whose squared norm is below `floor2` (kZeroColumn2 ||C||_F^2) is numerically zero and
+// is left alone (rank-deficient cores).
 __device__ __forceinline__ bool jacobi_rotation(double alpha, double beta, double gamma, double floor2,
                                                 double& c, double& s, bool& significant, double* tangent = nullptr) {
     const double lim = alpha * beta;
@@ -452,7 +478,7 @@ __global__ __launch_bounds__(1024) void jacobi_cross_kernel(const LayerDev* __re
     for (int r = lane; r < K; r += 64) right[wave * K + r] = right_blk[(int64_t)wave * K + r];
     __syncthreads();
 
-    const double floor2 = 1e-26 * L.trace[0] * L.trace[1];
+    const double floor2 = kZeroColumn2 * L.trace[2];
     bool any_signif = false;
     for (int step = 0; step < jb; ++step) {
         double* ycol = right + ((wave + step) % jb) * K;
@@ -546,7 +572,7 @@ __global__ __launch_bounds__(256) void jacobi_cross16_kernel(const LayerDev* __r
     double alpha = L.nrm[bI * 16 + g];
     __syncthreads();
 
-    const double floor2 = 1e-26 * L.trace[0] * L.trace[1];
+    const double floor2 = kZeroColumn2 * L.trace[2];
     bool any_signif = false;
     for (int step = 0; step < 16; ++step) {
         const int ci = (g + step) & 15;
@@ -629,7 +655,7 @@ __global__ __launch_bounds__(128) void jacobi_intra16_kernel(const LayerDev* __r
         if (l16 == 0) cn[cidx] = ss;
     }
     __syncthreads();
-    const double floor2 = 1e-26 * L.trace[0] * L.trace[1];
+    const double floor2 = kZeroColumn2 * L.trace[2];
     bool any_signif = false;
     for (int round = 0; round < 15; ++round) {
         int p, q;
@@ -700,7 +726,7 @@ __global__ __launch_bounds__(512) void jacobi_intra_kernel(const LayerDev* __res
     for (int cidx = wave; cidx < jb; cidx += jb / 2)
         for (int r = lane; r < K; r += 64) cols[cidx * K + r] = blk[(int64_t)cidx * K + r];
     __syncthreads();
-    const double floor2 = 1e-26 * L.trace[0] * L.trace[1];
+    const double floor2 = kZeroColumn2 * L.trace[2];
     bool any_signif = false;
     for (int round = 0; round < jb - 1; ++round) {
         int p, q;
@@ -884,7 +910,7 @@ Plan make_plan(const abt_merge_desc* layers, int L) {
         q.sigma = take(sizeof(double) * K);
         q.s3 = take(sizeof(double) * K);
         q.s5 = take(sizeof(double) * K);
-        q.trace = take(sizeof(double) * 2);
+        q.trace = take(sizeof(double) * 4);
         q.nrm = take(sizeof(double) * K);
         q.perm = take(sizeof(int) * K);
         q.PA = take(sizeof(float) * K * kc);
@@ -942,6 +968,12 @@ hipError_t launch_jacobi_sweep(const Plan& p, const LayerDev* dl, const int2* cr
 }  // namespace
 
 size_t merge_workspace_bytes(const abt_merge_desc* layers, int L) { return make_plan(layers, L).total; }
+
+hipError_t launch_identity_f32(float* dst, int K, hipStream_t s) {
+    const int64_t n = (int64_t)K * K;
+    hipLaunchKernelGGL(identity_f32_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, dst, K);
+    return hipGetLastError();
+}
 
 hipError_t merge_read_info(const void* workspace, int layer, int32_t out[4], hipStream_t s) {
     hipError_t e = hipStreamSynchronize(s);
@@ -1069,6 +1101,7 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
     hipLaunchKernelGGL(cholesky_kernel, dim3(2 * L), dim3(256), 0, s, dl);
     const GemmF64* d64 = (const GemmF64*)(ws + p.off_gemm64);
     hipLaunchKernelGGL(gemm_f64_kernel, dim3(tb0), dim3(256), 0, s, d64, p.n_gemm64);
+    hipLaunchKernelGGL(frob2_kernel, dim3(L), dim3(256), 0, s, dl);
     ABT_TRY(hipGetLastError());
 
     const int2* cross = (const int2*)(ws + p.off_wg_cross);

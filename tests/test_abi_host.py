@@ -104,6 +104,27 @@ def test_argument_validation_without_device(lib):
     assert call(ws=odd, wsb=1 << 40) == -3
 
 
+def test_factorize_validation_without_device(lib):
+    buf = ctypes.create_string_buffer(4096 + 256)
+    base = (ctypes.addressof(buf) + 255) // 256 * 256          # fake, aligned, never dereferenced
+    p, null, odd = ctypes.c_void_p(base), ctypes.c_void_p(0), ctypes.c_void_p(base + 2)
+    f = lib.ab_factorize
+    big = 1 << 40
+    assert lib.ab_factorize_workspace_bytes(3072, 768, 384) > 4 * 768 * 768
+    assert lib.ab_factorize_workspace_bytes(768, 3072, 384) > 4 * 768 * 768
+    assert lib.ab_factorize_workspace_bytes(100, 70, 32) == 0
+    assert lib.ab_factorize_workspace_bytes(4096, 2080, 32) == 0
+    assert f(null, 256, 256, 0.1, 0, p, p, p, p, 256, p, big, null) == -1        # EINVAL
+    assert f(p, 100, 70, 0.1, 0, p, p, p, p, 64, p, big, null) == -2             # ESHAPE
+    assert f(p, 4096, 2080, 0.1, 0, p, p, p, p, 64, p, big, null) == -2
+    assert f(p, 256, 256, 0.1, 0, p, p, p, p, 0, p, big, null) == -2
+    assert f(odd, 256, 256, 0.1, 0, p, p, p, p, 256, p, big, null) == -3         # EALIGN
+    assert f(p, 256, 256, 0.1, 0, p, p, p, p, 256, null, 0, null) == -4          # EWORKSPACE
+    assert f(p, 256, 256, 0.1, 0, p, p, p, p, 256, p, 1024, null) == -4
+    assert f(p, 256, 256, 1.5, 0, p, p, p, p, 256, p, big, null) == -1           # tau out of range
+    assert f(p, 256, 256, 0.1, 0, null, p, p, p, 256, p, big, null) == -1
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     x = torch.zeros(4, 64, dtype=torch.bfloat16)
