@@ -225,6 +225,27 @@ def main():
         ws_holder.clear()
         torch.cuda.empty_cache()
 
+    # ------------------------------------------------------------------ ab_factorize: dense ViT-B/16 weights (extra key)
+    if not args.no_merge:
+        rng = np.random.default_rng(7)
+        fz = []
+        for name, m, n in (("qkv", 2304, 768), ("proj", 768, 768), ("fc1", 3072, 768), ("fc2", 768, 3072)):
+            sigma = gen.power_law_spectrum(min(m, n), gap_at=gen.CFG5_GAP_AT)
+            Lf, Rf, _, _ = gen.planted_factor_pair(rng, m, n, sigma)
+            W = up((Lf @ Rf).astype(np.float32), torch.float32)
+            o = abt.ab_factorize(W, tau=gen.CFG5_TAU_GAP, k_cap=gen.CFG5_K_IN)        # warm-up, also checks convergence
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            o = abt.ab_factorize(W, tau=gen.CFG5_TAU_GAP, k_cap=gen.CFG5_K_IN, workspace=o["workspace"],
+                                 check_converged=False)
+            torch.cuda.synchronize()
+            fz.append({"layer": name, "m": m, "n": n, "ms": round((time.perf_counter() - t0) * 1e3, 3),
+                       "k": int(o["k"].item())})
+            del W, o
+        out["ab_factorize"] = {"per_layer": fz, "ms_per_layer_set": round(12 * sum(f["ms"] for f in fz), 1),
+                               "note": "dense W with the config-5 spectrum; one layer per call, K = 768"}
+        torch.cuda.empty_cache()
+
     # ------------------------------------------------------------------ CPU oracle beside it (reported, not a target)
     if not args.no_cpu:
         from oracle import ab_oracle as orc
