@@ -169,7 +169,9 @@ int ab_merge_info(const void* workspace, int layer, int32_t* sweeps, int32_t* n_
  * the pipeline of ab_merge on that pair: K = min(m, n) singular values are computed.
  * Limits: min(m, n) a multiple of 32 and <= 2048.  Outputs, zero-filling, the treatment of
  * numerically zero singular values and stream behaviour as for ab_merge.
- * ab_factorize_info: as ab_merge_info, for the workspace of an ab_factorize call.
+ * ab_merge_info applies to the workspace of an ab_factorize / ab_factorize_batched call too.
+ * ab_factorize_batched: L dense weights in one call (every stage one grouped launch);
+ * `layers` is a HOST array read before the call returns.
  * ------------------------------------------------------------------------------------- */
 int ab_factorize(const float* W, int64_t m, int64_t n, float tau, int64_t k_fixed,
                  float* A_out, float* B_out, float* S_out, int32_t* k_out, int64_t k_cap,
@@ -177,8 +179,22 @@ int ab_factorize(const float* W, int64_t m, int64_t n, float tau, int64_t k_fixe
 
 size_t ab_factorize_workspace_bytes(int64_t m, int64_t n, int64_t k_cap);
 
-int ab_factorize_info(const void* workspace, int64_t m, int64_t n, int32_t* sweeps, int32_t* n_sigma,
-                      void* stream);
+typedef struct {
+    const float* W;               /* [m, n] fp32 */
+    int64_t m, n;
+    float tau;
+    int64_t k_fixed;
+    float* A_out;                 /* [m, k_cap] */
+    float* B_out;                 /* [k_cap, n] */
+    float* S_out;                 /* [k_cap] */
+    int32_t* k_out;
+    int64_t k_cap;
+} abt_factorize_desc;
+
+int ab_factorize_batched(const abt_factorize_desc* layers, int L,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+size_t ab_factorize_batched_workspace_bytes(const abt_factorize_desc* layers, int L);
 
 /* Sweep cap of the Jacobi SVD (default 16, clamped to [1, 64]); returns the previous value. */
 int abt_set_jacobi_max_sweeps(int max_sweeps);

@@ -21,12 +21,20 @@ EXPORTS = (
     "lr_linear_bwd", "lr_linear_bwd_workspace_bytes",
     "ab_merge", "ab_merge_workspace_bytes",
     "ab_merge_batched", "ab_merge_batched_workspace_bytes", "ab_merge_info",
-    "ab_factorize", "ab_factorize_workspace_bytes", "ab_factorize_info",
+    "ab_factorize", "ab_factorize_workspace_bytes",
+    "ab_factorize_batched", "ab_factorize_batched_workspace_bytes",
 )
 
 
 class AbtError(RuntimeError):
     pass
+
+
+class FactorizeDesc(ctypes.Structure):
+    _fields_ = [("W", ctypes.c_void_p), ("m", ctypes.c_int64), ("n", ctypes.c_int64),
+                ("tau", ctypes.c_float), ("k_fixed", ctypes.c_int64),
+                ("A_out", ctypes.c_void_p), ("B_out", ctypes.c_void_p), ("S_out", ctypes.c_void_p),
+                ("k_out", ctypes.c_void_p), ("k_cap", ctypes.c_int64)]
 
 
 class MergeDesc(ctypes.Structure):
@@ -86,8 +94,10 @@ def load():
     lib.ab_factorize.argtypes = [vp, i64, i64, ctypes.c_float, i64, vp, vp, vp, vp, i64, vp, sz, vp]
     lib.ab_factorize_workspace_bytes.restype = sz
     lib.ab_factorize_workspace_bytes.argtypes = [i64, i64, i64]
-    lib.ab_factorize_info.restype = ci
-    lib.ab_factorize_info.argtypes = [vp, i64, i64, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32), vp]
+    lib.ab_factorize_batched.restype = ci
+    lib.ab_factorize_batched.argtypes = [ctypes.POINTER(FactorizeDesc), ci, vp, sz, vp]
+    lib.ab_factorize_batched_workspace_bytes.restype = sz
+    lib.ab_factorize_batched_workspace_bytes.argtypes = [ctypes.POINTER(FactorizeDesc), ci]
     _lib = lib
     return lib
 
@@ -286,31 +296,47 @@ def ab_factorize(W, tau: float, k_fixed: int = 0, k_cap: Optional[int] = None, w
                  check_converged: bool = True):
     """Truncated SVD factors of a dense fp32 GPU matrix W [m, n] (Eq. 3).  Returns dict(A [m,k_cap],
     B [k_cap,n], S [k_cap], k (0-d int32 tensor on the GPU), workspace)."""
+    return ab_factorize_batched([dict(W=W, tau=tau, k_fixed=k_fixed, k_cap=k_cap)], workspace=workspace,
+                                check_converged=check_converged)[0]
+
+
+def ab_factorize_batched(layers: List[dict], workspace=None, check_converged: bool = True):
+    """Factorise L dense weights in one call.  Each layer dict: W (fp32 GPU tensor [m, n]), tau, and
+    optionally k_fixed, k_cap.  Returns a list of dicts as ab_factorize."""
     torch = _torch()
     lib = load()
-    W = _dev_tensor(W, "W")
-    if W.dtype != torch.float32 or W.dim() != 2:
-        raise AbtError("W must be a 2-d fp32 tensor")
-    m, n = W.shape
-    K = min(m, n)
-    k_cap = int(k_cap or K)
-    dev = W.device
-    A_out = torch.empty((m, k_cap), dtype=torch.float32, device=dev)
-    B_out = torch.empty((k_cap, n), dtype=torch.float32, device=dev)
-    S_out = torch.empty((k_cap,), dtype=torch.float32, device=dev)
-    k_out = torch.zeros((), dtype=torch.int32, device=dev)
-    need = lib.ab_factorize_workspace_bytes(m, n, k_cap)
+    L = len(layers)
+    descs = (FactorizeDesc * L)()
+    outs = []
+    dev = None
+    for i, lay in enumerate(layers):
+        W = _dev_tensor(lay["W"], "W")
+        if W.dtype != torch.float32 or W.dim() != 2:
+            raise AbtError("W must be a 2-d fp32 tensor")
+        m, n = W.shape
+        k_cap = int(lay.get("k_cap") or min(m, n))
+        dev = W.device
+        o = dict(A=torch.empty((m, k_cap), dtype=torch.float32, device=dev),
+                 B=torch.empty((k_cap, n), dtype=torch.float32, device=dev),
+                 S=torch.empty((k_cap,), dtype=torch.float32, device=dev),
+                 k=torch.zeros((), dtype=torch.int32, device=dev), _W=W)
+        d = descs[i]
+        d.W = _ptr(W); d.m = m; d.n = n; d.tau = float(lay["tau"]); d.k_fixed = int(lay.get("k_fixed", 0))
+        d.A_out = _ptr(o["A"]); d.B_out = _ptr(o["B"]); d.S_out = _ptr(o["S"]); d.k_out = _ptr(o["k"])
+        d.k_cap = k_cap
+        outs.append(o)
+    need = lib.ab_factorize_batched_workspace_bytes(descs, L)
     if need == 0:
-        raise AbtError(f"ab_factorize: unsupported shape {m} x {n} (min(m, n) must be a multiple of 32, <= 2048)")
+        raise AbtError("ab_factorize: unsupported shape (min(m, n) must be a multiple of 32, <= 2048)")
     if workspace is None or workspace.numel() < need:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
-    _check(lib.ab_factorize(_ptr(W), m, n, float(tau), int(k_fixed), _ptr(A_out), _ptr(B_out), _ptr(S_out),
-                            _ptr(k_out), k_cap, _ptr(workspace), workspace.numel(), _stream()), "ab_factorize")
-    if check_converged:
-        sweeps, nsig = ctypes.c_int32(0), ctypes.c_int32(0)
-        _check(lib.ab_factorize_info(_ptr(workspace), m, n, ctypes.byref(sweeps), ctypes.byref(nsig), _stream()),
-               "ab_factorize_info")
-    return dict(A=A_out, B=B_out, S=S_out, k=k_out, workspace=workspace)
+    _check(lib.ab_factorize_batched(descs, L, _ptr(workspace), workspace.numel(), _stream()), "ab_factorize_batched")
+    for i, o in enumerate(outs):
+        o["workspace"] = workspace
+        o.pop("_W")
+        if check_converged:
+            merge_info(workspace, i)
+    return outs
 
 
 def merge_info(workspace, layer: int = 0):

@@ -246,46 +246,96 @@ int ab_merge(const float* const* A_copies, const float* const* B_copies, int G,
 }
 
 // Dense W = W I (n <= m) or I W (n > m): the merge of one "copy" whose short-side factor is the
-// identity.  Workspace: [identity K x K fp32][merge workspace].
-static int64_t factorize_K(int64_t m, int64_t n) { return m < n ? m : n; }
+// identity.  Workspace: [merge workspace of the L layers][one K x K fp32 identity per distinct K].
+}  // extern "C"
+
+namespace {
+int64_t factorize_K(int64_t m, int64_t n) { return m < n ? m : n; }
+
+struct FactorizePlan {
+    std::vector<abt_merge_desc> merge;      // A_copies / B_copies are filled in by the caller
+    std::vector<int64_t> Ks;                // distinct K, in order of first use
+    std::vector<size_t> eye_off;            // byte offset of each identity behind the merge workspace
+    std::vector<int> eye_of_layer;
+    size_t merge_bytes = 0, total = 0;
+    int status = ABT_OK;
+};
+
+FactorizePlan plan_factorize(const abt_factorize_desc* layers, int L) {
+    FactorizePlan p;
+    if (!layers || L < 1) { p.status = ABT_EINVAL; return p; }
+    p.merge.resize(L);
+    p.eye_of_layer.resize(L);
+    for (int l = 0; l < L; ++l) {
+        const abt_factorize_desc& f = layers[l];
+        if (f.m < 1 || f.n < 1 || f.k_cap < 1) { p.status = ABT_ESHAPE; return p; }
+        const int64_t K = factorize_K(f.m, f.n);
+        if (K % 32 || K > 2048) { p.status = ABT_ESHAPE; return p; }
+        abt_merge_desc& d = p.merge[l];
+        d = abt_merge_desc{};
+        d.G = 1; d.mode = 0; d.m = f.m; d.n = f.n; d.k = K; d.tau = f.tau; d.k_fixed = f.k_fixed;
+        d.A_out = f.A_out; d.B_out = f.B_out; d.S_out = f.S_out; d.k_out = f.k_out; d.k_cap = f.k_cap;
+        int e = -1;
+        for (size_t i = 0; i < p.Ks.size(); ++i) if (p.Ks[i] == K) e = (int)i;
+        if (e < 0) { e = (int)p.Ks.size(); p.Ks.push_back(K); }
+        p.eye_of_layer[l] = e;
+    }
+    p.merge_bytes = align_up(merge_workspace_bytes(p.merge.data(), L), 256);
+    size_t off = p.merge_bytes;
+    for (int64_t K : p.Ks) { p.eye_off.push_back(off); off += align_up(sizeof(float) * K * K, 256); }
+    p.total = off;
+    return p;
+}
+}  // namespace
+
+extern "C" {
+
+size_t ab_factorize_batched_workspace_bytes(const abt_factorize_desc* layers, int L) {
+    const FactorizePlan p = plan_factorize(layers, L);
+    return p.status == ABT_OK ? p.total : 0;
+}
+
+int ab_factorize_batched(const abt_factorize_desc* layers, int L, void* workspace, size_t workspace_bytes,
+                         void* stream) {
+    FactorizePlan p = plan_factorize(layers, L);
+    if (p.status != ABT_OK) return p.status;
+    for (int l = 0; l < L; ++l) {
+        if (!layers[l].W) return ABT_EINVAL;
+        if (!aligned(layers[l].W, 16)) return ABT_EALIGN;
+    }
+    if (!workspace || workspace_bytes < p.total) return ABT_EWORKSPACE;
+    if (!aligned(workspace, 256)) return ABT_EALIGN;
+    // one pointer pair per layer: (W, I) or (I, W); the arrays are read before merge_run returns
+    std::vector<const float*> a_ptr(L), b_ptr(L);
+    for (int l = 0; l < L; ++l) {
+        const float* eye = (const float*)((const char*)workspace + p.eye_off[p.eye_of_layer[l]]);
+        const bool tall = layers[l].n <= layers[l].m;
+        a_ptr[l] = tall ? layers[l].W : eye;
+        b_ptr[l] = tall ? eye : layers[l].W;
+        p.merge[l].A_copies = &a_ptr[l];
+        p.merge[l].B_copies = &b_ptr[l];
+        const int st = check_merge_layer(p.merge[l]);
+        if (st != ABT_OK) return st;
+    }
+    for (size_t i = 0; i < p.Ks.size(); ++i)
+        if (launch_identity_f32((float*)((char*)workspace + p.eye_off[i]), (int)p.Ks[i], (hipStream_t)stream) != hipSuccess)
+            return ABT_EHIP;
+    return merge_run(p.merge.data(), L, workspace, g_max_sweeps, (hipStream_t)stream) == hipSuccess ? ABT_OK : ABT_EHIP;
+}
 
 size_t ab_factorize_workspace_bytes(int64_t m, int64_t n, int64_t k_cap) {
-    if (m < 1 || n < 1 || k_cap < 1) return 0;
-    const int64_t K = factorize_K(m, n);
-    if (K % 32 || K > 2048) return 0;
-    const size_t wm = ab_merge_workspace_bytes(1, m, n, K, k_cap, 0);
-    return wm ? align_up(sizeof(float) * K * K, 256) + wm : 0;
+    abt_factorize_desc f{};
+    f.m = m; f.n = n; f.k_cap = k_cap;
+    return ab_factorize_batched_workspace_bytes(&f, 1);
 }
 
 int ab_factorize(const float* W, int64_t m, int64_t n, float tau, int64_t k_fixed,
                  float* A_out, float* B_out, float* S_out, int32_t* k_out, int64_t k_cap,
                  void* workspace, size_t workspace_bytes, void* stream) {
-    if (!W) return ABT_EINVAL;
-    if (m < 1 || n < 1 || k_cap < 1) return ABT_ESHAPE;
-    const int64_t K = factorize_K(m, n);
-    if (K % 32 || K > 2048) return ABT_ESHAPE;
-    if (!aligned(W, 16)) return ABT_EALIGN;
-    const size_t need = ab_factorize_workspace_bytes(m, n, k_cap);
-    if (!workspace || need == 0 || workspace_bytes < need) return ABT_EWORKSPACE;
-    if (!aligned(workspace, 256)) return ABT_EALIGN;
-    float* eye = (float*)workspace;
-    const size_t eye_bytes = align_up(sizeof(float) * K * K, 256);
-    const float* a_copy = n <= m ? W : eye;
-    const float* b_copy = n <= m ? eye : W;
-    abt_merge_desc d{};
-    d.A_copies = &a_copy; d.B_copies = &b_copy; d.G = 1; d.mode = 0;
-    d.m = m; d.n = n; d.k = K; d.tau = tau; d.k_fixed = k_fixed;
-    d.A_out = A_out; d.B_out = B_out; d.S_out = S_out; d.k_out = k_out; d.k_cap = k_cap; d.W_out = nullptr;
-    const int st = check_merge_layer(d);
-    if (st != ABT_OK) return st;
-    if (launch_identity_f32(eye, (int)K, (hipStream_t)stream) != hipSuccess) return ABT_EHIP;
-    return merge_run(&d, 1, (char*)workspace + eye_bytes, g_max_sweeps, (hipStream_t)stream) == hipSuccess ? ABT_OK : ABT_EHIP;
-}
-
-int ab_factorize_info(const void* workspace, int64_t m, int64_t n, int32_t* sweeps, int32_t* n_sigma, void* stream) {
-    if (!workspace || m < 1 || n < 1) return ABT_EINVAL;
-    const int64_t K = factorize_K(m, n);
-    return ab_merge_info((const char*)workspace + align_up(sizeof(float) * K * K, 256), 0, sweeps, n_sigma, stream);
+    abt_factorize_desc f{};
+    f.W = W; f.m = m; f.n = n; f.tau = tau; f.k_fixed = k_fixed;
+    f.A_out = A_out; f.B_out = B_out; f.S_out = S_out; f.k_out = k_out; f.k_cap = k_cap;
+    return ab_factorize_batched(&f, 1, workspace, workspace_bytes, stream);
 }
 
 int ab_merge_info(const void* workspace, int layer, int32_t* sweeps, int32_t* n_sigma, void* stream) {

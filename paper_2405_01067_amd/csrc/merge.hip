@@ -530,7 +530,7 @@ __device__ __forceinline__ double row16_sum(double v) {
     return v;
 }
 
-// Cross round for cores with K <= 32 NE2 <= 512 and blocks of 16 columns.  A work-group of 256
+// Cross round for cores with K <= 32 NE2 <= 768 and blocks of 16 columns.  A work-group of 256
 // threads owns one block pair; a group of 16 lanes owns one left column (in registers, two
 // consecutive rows per lane and 32-row stride) and meets the 16 right columns (in LDS) one per step:
 // four column pairs per wave and step, each needing a single inner product reduced over 16 lanes.
@@ -618,7 +618,7 @@ __global__ __launch_bounds__(256) void jacobi_cross16_kernel(const LayerDev* __r
     if (any_signif && l16 == 0) L.rotated[sweep] = 1;
 }
 
-// All pairs inside one block of 16 columns for cores with K <= 32 NE2 <= 512: the block lives in
+// All pairs inside one block of 16 columns for cores with K <= 32 NE2 <= 768: the block lives in
 // LDS, a work-group of 128 threads = 8 groups of 16 lanes rotates 8 disjoint pairs per step, 15
 // steps (round-robin).  Squared norms are computed once at the start, carried with the rotations,
 // and written out at the end (recomputed from the final data) for the cross rounds to start from.
@@ -861,7 +861,7 @@ struct Plan {
     std::vector<PerLayer> pl;
 };
 
-int jacobi_block(int K) { return K <= 512 ? 16 : (K <= 1024 ? 8 : 4); }
+int jacobi_block(int K) { return K <= 768 ? 16 : (K <= 1024 ? 8 : 4); }
 
 Plan make_plan(const abt_merge_desc* layers, int L) {
     Plan p;
@@ -934,10 +934,10 @@ hipError_t launch_jacobi_sweep(const Plan& p, const LayerDev* dl, const int2* cr
         if (e != hipSuccess) return e;
         attr_bytes = lds_cross;
     }
-    if (p.K_max <= 512) {
+    if (p.K_max <= 768) {
         // every layer has blocks of 16 columns: the 16-lane-group kernels, sized for the widest core
         const size_t lds16 = sizeof(double) * (16 * (size_t)(p.K_max + 16) + 16);
-        static size_t attr16_by_size[3] = {0, 0, 0};
+        static size_t attr16_by_size[4] = {0, 0, 0, 0};
         auto run = [&](auto kern_intra, auto kern_cross, size_t& attr16) -> hipError_t {
             if (lds16 > attr16) {
                 hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_intra),
@@ -955,7 +955,8 @@ hipError_t launch_jacobi_sweep(const Plan& p, const LayerDev* dl, const int2* cr
         };
         if (p.K_max <= 256) return run(&jacobi_intra16_kernel<8>, &jacobi_cross16_kernel<8>, attr16_by_size[0]);
         if (p.K_max <= 384) return run(&jacobi_intra16_kernel<12>, &jacobi_cross16_kernel<12>, attr16_by_size[1]);
-        return run(&jacobi_intra16_kernel<16>, &jacobi_cross16_kernel<16>, attr16_by_size[2]);
+        if (p.K_max <= 512) return run(&jacobi_intra16_kernel<16>, &jacobi_cross16_kernel<16>, attr16_by_size[2]);
+        return run(&jacobi_intra16_kernel<24>, &jacobi_cross16_kernel<24>, attr16_by_size[3]);
     }
     hipLaunchKernelGGL(jacobi_intra_kernel<NX>, dim3(p.n_wg_intra), dim3(64 * (p.jb_max / 2)), lds_cross, s,
                        dl, intra, sweep);

@@ -104,6 +104,20 @@ def test_rank_deficient_weight_and_k_cap():
     assert rel(A @ B, A_o @ B_o) < TOL
 
 
+def test_batched_matches_single_calls():
+    specs = [(320, 192, 40), (192, 320, 40), (256, 256, 100), (768, 96, 17)]
+    mats, taus = [], []
+    for m, n, gap in specs:
+        W32, sigma = planted(m, n, gap, seed=3 * m + n)
+        mats.append(W32)
+        taus.append(float(math.sqrt(sigma[gap - 1] * sigma[gap]) / sigma[0]))
+    outs = abt.ab_factorize_batched([dict(W=dev(W), tau=t) for W, t in zip(mats, taus)])
+    for (m, n, gap), W32, tau, o in zip(specs, mats, taus, outs):
+        check(W32, o, tau=tau, expect_k=gap)
+        single = abt.ab_factorize(dev(W32), tau=tau)
+        assert torch.equal(single["S"], o["S"]) and torch.equal(single["A"], o["A"]) and torch.equal(single["B"], o["B"])
+
+
 def test_unsupported_shapes_are_refused():
     with pytest.raises(abt.AbtError):
         abt.ab_factorize(torch.zeros((100, 70), device="cuda:0"), tau=0.1)      # min(m, n) % 32

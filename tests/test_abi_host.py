@@ -111,6 +111,13 @@ def test_factorize_validation_without_device(lib):
     f = lib.ab_factorize
     big = 1 << 40
     assert lib.ab_factorize_workspace_bytes(3072, 768, 384) > 4 * 768 * 768
+    descs = (abt.FactorizeDesc * 2)()
+    for d, (m, n) in zip(descs, ((3072, 768), (768, 768))):
+        d.m, d.n, d.k_cap = m, n, 384
+    both = lib.ab_factorize_batched_workspace_bytes(descs, 2)
+    # the two layers share one 768 x 768 identity
+    assert both < lib.ab_factorize_workspace_bytes(3072, 768, 384) + lib.ab_factorize_workspace_bytes(768, 768, 384)
+    assert both > lib.ab_factorize_workspace_bytes(3072, 768, 384)
     assert lib.ab_factorize_workspace_bytes(768, 3072, 384) > 4 * 768 * 768
     assert lib.ab_factorize_workspace_bytes(100, 70, 32) == 0
     assert lib.ab_factorize_workspace_bytes(4096, 2080, 32) == 0
