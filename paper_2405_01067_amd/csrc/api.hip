@@ -1,6 +1,5 @@
 // C ABI of the library: argument validation, workspace carving and the launch sequences.
 // Every operation is documented in include/abtrain.h.
-#include <cstdlib>
 #include <vector>
 
 #include "common.h"
@@ -11,12 +10,11 @@ namespace {
 
 int g_max_sweeps = 16;
 
-// Chain kernel choice: the 64-row / 8-wave kernel wherever it supports the rank, else the
-// 128-row kernel.  ABT_CHAIN=1 in the environment forces the 128-row kernel (for comparisons).
+// Chain kernel choice: the 64-row kernel with loader and MFMA waves wherever it supports the rank
+// (32, 64, 96, 128, 160, 192, 256, 320, 384), else the older 128-row kernel (224, 288, 352).
 hipError_t chain(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                  int64_t M, int p, int q, int R, hipStream_t s) {
-    static const int forced = [] { const char* e = getenv("ABT_CHAIN"); return e ? atoi(e) : 0; }();
-    if (forced != 1 && chain2_supports(R, p, q)) return launch_chain2_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
+    if (chain2_supports(R, p, q)) return launch_chain2_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
     return launch_chain_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
 }
 

@@ -43,7 +43,7 @@ struct LayerDev {
     float* Abar; float* Bbar;
     double* LA; double* GB; double* LB; double* Ct; double* Yt;
     double* sigma; double* s3; double* s5;
-    double* trace;         // [4]: trace(G_A), trace(G_B), ||C||_F^2 (set once C has been formed), unused
+    double* trace;         // [10]: trace(G_A), trace(G_B), then eight partial sums of ||C||_F^2
     double* nrm;           // [K]: squared column norms of C, refreshed every sweep, updated by rotations
     int* perm;
     float* PA; float* PB;
@@ -396,20 +396,27 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(const GemmF64* __restrict
         }
 }
 
-// ||C||_F^2 per layer (fixed summation order), the scale of the "numerically zero column" test.
+// ||C||_F^2 per layer, the scale of the "numerically zero column" test: eight work-groups per
+// layer leave eight partial sums, which the readers add in a fixed order.
 __global__ __launch_bounds__(256) void frob2_kernel(const LayerDev* __restrict__ layers) {
     __shared__ double red[256];
-    const LayerDev& L = layers[blockIdx.x];
+    const LayerDev& L = layers[blockIdx.y];
     const int64_t n = (int64_t)L.K * L.K;
     double ss = 0.0;
-    for (int64_t i = threadIdx.x; i < n; i += 256) ss = fma(L.Ct[i], L.Ct[i], ss);
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += 8 * 256) ss = fma(L.Ct[i], L.Ct[i], ss);
     red[threadIdx.x] = ss;
     __syncthreads();
     for (int s = 128; s > 0; s >>= 1) {
         if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
         __syncthreads();
     }
-    if (threadIdx.x == 0) L.trace[2] = red[0];
+    if (threadIdx.x == 0) L.trace[2 + blockIdx.x] = red[0];
+}
+__device__ __forceinline__ double frob2(const LayerDev& L) {
+    double s = 0.0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s += L.trace[2 + j];
+    return s;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -478,7 +485,7 @@ __global__ __launch_bounds__(1024) void jacobi_cross_kernel(const LayerDev* __re
     for (int r = lane; r < K; r += 64) right[wave * K + r] = right_blk[(int64_t)wave * K + r];
     __syncthreads();
 
-    const double floor2 = kZeroColumn2 * L.trace[2];
+    const double floor2 = kZeroColumn2 * frob2(L);
     bool any_signif = false;
     for (int step = 0; step < jb; ++step) {
         double* ycol = right + ((wave + step) % jb) * K;
@@ -572,7 +579,7 @@ __global__ __launch_bounds__(256) void jacobi_cross16_kernel(const LayerDev* __r
     double alpha = L.nrm[bI * 16 + g];
     __syncthreads();
 
-    const double floor2 = kZeroColumn2 * L.trace[2];
+    const double floor2 = kZeroColumn2 * frob2(L);
     bool any_signif = false;
     for (int step = 0; step < 16; ++step) {
         const int ci = (g + step) & 15;
@@ -655,7 +662,7 @@ __global__ __launch_bounds__(128) void jacobi_intra16_kernel(const LayerDev* __r
         if (l16 == 0) cn[cidx] = ss;
     }
     __syncthreads();
-    const double floor2 = kZeroColumn2 * L.trace[2];
+    const double floor2 = kZeroColumn2 * frob2(L);
     bool any_signif = false;
     for (int round = 0; round < 15; ++round) {
         int p, q;
@@ -726,7 +733,7 @@ __global__ __launch_bounds__(512) void jacobi_intra_kernel(const LayerDev* __res
     for (int cidx = wave; cidx < jb; cidx += jb / 2)
         for (int r = lane; r < K; r += 64) cols[cidx * K + r] = blk[(int64_t)cidx * K + r];
     __syncthreads();
-    const double floor2 = kZeroColumn2 * L.trace[2];
+    const double floor2 = kZeroColumn2 * frob2(L);
     bool any_signif = false;
     for (int round = 0; round < jb - 1; ++round) {
         int p, q;
@@ -910,7 +917,7 @@ Plan make_plan(const abt_merge_desc* layers, int L) {
         q.sigma = take(sizeof(double) * K);
         q.s3 = take(sizeof(double) * K);
         q.s5 = take(sizeof(double) * K);
-        q.trace = take(sizeof(double) * 4);
+        q.trace = take(sizeof(double) * 10);
         q.nrm = take(sizeof(double) * K);
         q.perm = take(sizeof(int) * K);
         q.PA = take(sizeof(float) * K * kc);
@@ -1102,7 +1109,7 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
     hipLaunchKernelGGL(cholesky_kernel, dim3(2 * L), dim3(256), 0, s, dl);
     const GemmF64* d64 = (const GemmF64*)(ws + p.off_gemm64);
     hipLaunchKernelGGL(gemm_f64_kernel, dim3(tb0), dim3(256), 0, s, d64, p.n_gemm64);
-    hipLaunchKernelGGL(frob2_kernel, dim3(L), dim3(256), 0, s, dl);
+    hipLaunchKernelGGL(frob2_kernel, dim3(8, L), dim3(256), 0, s, dl);
     ABT_TRY(hipGetLastError());
 
     const int2* cross = (const int2*)(ws + p.off_wg_cross);
