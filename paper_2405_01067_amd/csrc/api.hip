@@ -14,7 +14,7 @@ int g_max_sweeps = 16;
 // (32, 64, 96, 128, 160, 192, 256, 320, 384), else the older 128-row kernel (224, 288, 352).
 hipError_t chain(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                  int64_t M, int p, int q, int R, hipStream_t s) {
-    if (chain2_supports(R, p, q)) return launch_chain2_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, 0, s);
+    if (chain2_supports(R, p, q)) return launch_chain2_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
     return launch_chain_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
 }
 
@@ -188,17 +188,11 @@ int lr_linear_bwd(const void* dY, const void* X, const void* T, const void* A, c
         Tp = ws + w.T;
     }
     if (dX || dB) {
-        // dT = dY A = dY (A^T)^T and dX = dT B = dT (B^T)^T: the forward chain on transposed factors.
-        // The 64-row kernel takes A and B as they are (its loaders transpose on the way to LDS);
-        // the older kernel needs A^T and B^T written out first.
-        if (chain2_supports((int)r, (int)m, (int)n)) {
-            e = launch_chain2_bf16(dY, A, dX ? B : nullptr, dX, dT, M, (int)m, (int)n, (int)r, 1, s);
-        } else {
-            const TransposeJob tj[2] = {{A, At, (int)m, (int)r}, {B, Bt, (int)r, (int)n}};
-            e = launch_transpose_bf16(tj, dX ? 2 : 1, s);
-            if (e != hipSuccess) return ABT_EHIP;
-            e = chain(dY, At, dX ? Bt : nullptr, dX, dT, M, (int)m, (int)n, (int)r, s);
-        }
+        // dT = dY A = dY (A^T)^T and dX = dT B = dT (B^T)^T: the forward chain on transposed factors
+        const TransposeJob tj[2] = {{A, At, (int)m, (int)r}, {B, Bt, (int)r, (int)n}};
+        e = launch_transpose_bf16(tj, dX ? 2 : 1, s);
+        if (e != hipSuccess) return ABT_EHIP;
+        e = chain(dY, At, dX ? Bt : nullptr, dX, dT, M, (int)m, (int)n, (int)r, s);
         if (e != hipSuccess) return ABT_EHIP;
     }
     TnJob jobs[2];

@@ -47,17 +47,6 @@ __device__ __forceinline__ void buf_store16(u32x4 v, rsrc_t r, int lane_off, int
     __builtin_amdgcn_raw_buffer_store_b128(v, r, lane_off, wave_off, 0);
 }
 
-// 8 x 8 transpose of 16-bit elements held as eight rows of 8 (one u32x4 each): word i of output
-// column j packs rows 2i (low half) and 2i+1 (high half) of column j.
-__device__ __forceinline__ void transpose8x8_b16(const u32x4 (&v)[8], u32x4 (&out)[8]) {
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            out[j][i] = __builtin_amdgcn_perm(v[2 * i + 1][j >> 1], v[2 * i][j >> 1],
-                                              (j & 1) ? 0x07060302u : 0x05040100u);
-}
-
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -70,10 +59,8 @@ hipError_t launch_chain_bf16(const void* Xin, const void* P, const void* Q, void
 // R in {32, 64, 96, 128, 160, 192, 256, 320, 384} with p a multiple of 64 and p, q <= 2^20
 // (32-bit byte offsets inside a work-group's rows and inside the factors) (chain2_supports).
 bool chain2_supports(int R, int p, int q);
-// transposed != 0: P is handed over as [p, R] and Q as [R, q] (row-major), i.e. the backward pass
-// passes A and B as they are; the loaders transpose on the way to LDS.
 hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
-                              int64_t M, int p, int q, int R, int transposed, hipStream_t s);
+                              int64_t M, int p, int q, int R, hipStream_t s);
 // dst[c, r] = src[r, c] for a bf16 matrix of `rows` x `cols`.
 struct TransposeJob { const void* src; void* dst; int rows, cols; };   // dst[cols, rows] = src[rows, cols]^T
 hipError_t launch_transpose_bf16(const TransposeJob* jobs, int njobs, hipStream_t s);

@@ -103,9 +103,6 @@ struct Ch2Cfg {
     static constexpr int NCHX = 64 * CPR1 / NLT;              // 16-byte chunks per loader thread (Xin part) = 2
     static constexpr int NCHP = R * CPR1 / NLT;               // chunks per loader thread (P part) = R / 32
     static constexpr int D1 = clampi(32 / (NCHX + NCHP), 2, 6);   // stage-1 slabs in flight (register ring depth)
-    // transposed factors: 8 x 8 blocks, BPT per loader thread, ACT loader threads take part
-    static constexpr int BPT1 = R > 256 ? 2 : 1, ACT1 = R / BPT1;
-    static constexpr int D1T = clampi(32 / (NCHX + 8 * BPT1), 2, 6);
     // stage 2: a slab is 128 rows of Q times BK2 = R / KSL columns
     static constexpr int KSL = R <= 224 ? 1 : 2;
     static constexpr int BK2 = R / KSL, CPR2 = BK2 / 8;
@@ -113,10 +110,6 @@ struct Ch2Cfg {
     static constexpr int NCHQ = 128 * CPR2 / NLT;             // chunks per loader thread = BK2 / 16
     static constexpr int D2 = clampi(36 / NCHQ, 2, 6);        // stage-2 slabs in flight
     static constexpr int U2 = D2 * KSL / gcdi(D2, KSL);       // stage-2 trip count is padded to a multiple of this
-    static constexpr int BPT2 = 2 * BK2 > 256 ? 2 : 1, ACT2 = 2 * BK2 / BPT2;
-    static constexpr int D2T = clampi(36 / (8 * BPT2), 2, 6);
-    static constexpr int U2T = D2T * KSL / gcdi(D2T, KSL);
-    static_assert(ACT1 <= NLT && ACT2 <= NLT && ACT1 * BPT1 == R && ACT2 * BPT2 == 2 * BK2, "block split");
     static constexpr int ypitch = 128 * 2 + 16;
     static constexpr int ytile = 64 * ypitch;
     static constexpr int red = (C::KS / 2) * C::CS * C::RS * RA * CB * 4096;   // first (largest) round of the tree
@@ -129,7 +122,7 @@ struct Ch2Cfg {
     static_assert(C::RS * C::CS * C::KS == NMW_ && CB * C::CS * 32 == R && RA * C::RS == 2, "wave split");
 };
 
-template <int R, bool TR>
+template <int R>
 __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restrict__ Xin,
                                                          const uint16_t* __restrict__ Pm,
                                                          const uint16_t* __restrict__ Qm,
@@ -141,7 +134,7 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
     using L = Ch2Cfg<R>;
     constexpr int RS = C::RS, CS = C::CS, KS = C::KS, CB = L::CB, RA = L::RA, SPW = L::SPW;
     constexpr int BK2 = L::BK2, CPR2 = L::CPR2, KSL = L::KSL;
-    constexpr int D1 = TR ? L::D1T : L::D1, D2 = TR ? L::D2T : L::D2, U2 = TR ? L::U2T : L::U2;
+    constexpr int D1 = L::D1, D2 = L::D2;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t row0 = (int64_t)blockIdx.x * 64;
@@ -149,7 +142,7 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
     const int n1p = (ns1 + D1 - 1) / D1 * D1;           // stage-1 trip count, padded to the loaders' ring
     const int ntile = (q + 127) / 128;                  // stage-2 output tiles of 128 columns
     const int ns2 = ntile * KSL;
-    const int n2p = (ns2 + U2 - 1) / U2 * U2;           // stage-2 trip count, padded likewise
+    const int n2p = (ns2 + L::U2 - 1) / L::U2 * L::U2;  // stage-2 trip count, padded likewise
     unsigned char* const ttile = lds + L::red;
     unsigned char* const ytile = lds + 2 * L::slab2;
     // Work-groups walk the contraction slabs (stage 1) and the output tiles (stage 2) from
@@ -159,10 +152,6 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
     const int rot2 = (int)(blockIdx.x % (unsigned)ntile);
     auto slab1_of = [&](int s) { if (s > ns1 - 1) s = ns1 - 1; s += rot1; return s >= ns1 ? s - ns1 : s; };
     auto tile_of = [&](int t) { if (t > ntile - 1) t = ntile - 1; t += rot2; return t >= ntile ? t - ntile : t; };
-    // P row r of a stage-1 slab sits in LDS row r ^ (r / 8 % 2): neighbouring rows change places in
-    // every other group of eight, so that the column pieces a transposing loader stores (rows 8 apart
-    // in neighbouring lanes) alternate between the two halves of the banks.
-    auto prow = [](int r) { return r ^ ((r >> 3) & 1); };
 
     if (wave >= NMW) {
         // ================================================================== loader waves
@@ -172,110 +161,23 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
         // loads do not slow down.  The descriptors cover exactly this work-group's valid rows and the
         // row offset is part of the per-lane offset (the only part the hardware range-checks), so
         // rows past M read as zeros and stores to them are dropped.
-        //
-        // TR: the factors are given transposed, P as [p, R] and Q as [R, q] (the backward pass hands
-        // over A and B as they are).  Their slabs then lie in memory with the contraction index
-        // slowest; a loader thread takes 8 x 8 blocks (eight 16-byte row pieces), transposes them in
-        // registers and stores eight 16-byte column pieces, so LDS holds the same layout either way.
         const int lt = tid - NMT;
         const int64_t rows_valid = M - row0 < 64 ? M - row0 : 64;
         const rsrc_t xres = make_rsrc(Xin + row0 * p, rows_valid * p * 2);
         const rsrc_t pres = make_rsrc(Pm, (int64_t)R * p * 2);
-        // ---------------- stage-2 assignment (computed first: the first Q slabs are requested before
-        // stage 1's epilogue so that their latency hides behind the reduction and the T tile)
-        constexpr int NQ = TR ? 8 * L::BPT2 : L::NCHQ;   // 16-byte items per thread and slab
-        int qoff[NQ];                                    // LDS offsets of the items as stored
-        int qsrc[TR ? L::BPT2 : L::NCHQ];                // global per-lane offsets
-        int qsrc_half[TR ? L::BPT2 : 1];                 // TR: the same for a ragged last tile (64 columns)
-        if constexpr (!TR) {
+        // stage-2 chunk assignment (computed first: the first Q slabs are requested before stage 1's
+        // epilogue so that their latency hides behind the reduction and the T tile)
+        int qoff[L::NCHQ], qsrc[L::NCHQ];
 #pragma unroll
-            for (int e = 0; e < L::NCHQ; ++e) {
-                const int ci = e * NLT + lt;
-                const int row = ci / CPR2, ch = ci % CPR2;
-                qsrc[e] = (row * R + ch * 8) * 2;
-                qoff[e] = row * (BK2 * 2) + swz<CPR2>(ch, row) * 16;
-            }
-            qsrc_half[0] = 0;
-        } else {
-#pragma unroll
-            for (int b = 0; b < L::BPT2; ++b) {
-                // block = rows k 8 rg .. 8 rg + 7 of the slab, columns (Q rows) 8 cc .. 8 cc + 7 of the tile
-                const int idx = lt + b * L::ACT2;
-                const int rg = idx % CPR2, cc = idx / CPR2;
-                const bool act = lt < L::ACT2;
-                qsrc[b] = act ? (8 * rg * q + 8 * cc) * 2 : kBufNowhere;
-                qsrc_half[b] = (act && cc < 8) ? qsrc[b] : kBufNowhere;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int qrow = 8 * cc + j;
-                    qoff[8 * b + j] = act ? qrow * (BK2 * 2) + swz<CPR2>(rg, qrow) * 16 : -1;
-                }
-            }
+        for (int e = 0; e < L::NCHQ; ++e) {
+            const int ci = e * NLT + lt;
+            const int row = ci / CPR2, ch = ci % CPR2;
+            qsrc[e] = (row * R + ch * 8) * 2;
+            qoff[e] = row * (BK2 * 2) + swz<CPR2>(ch, row) * 16;
         }
-        auto q_issue = [&](u32x4 (&dst)[NQ], int s) {
-            if (s > ns2 - 1) s = ns2 - 1;
-            const int t = tile_of(s / KSL);
-            const int rows = q - t * 128 < 128 ? q - t * 128 : 128;
-            if constexpr (!TR) {
-                // the descriptor is rebuilt per slab (scalar work) to cover exactly the tile's rows:
-                // rows of a ragged last tile past the end of Q read as zeros (never stored)
-                const rsrc_t qres = make_rsrc(Qm + (int64_t)t * 128 * R, (int64_t)rows * R * 2);
-                const int so = (s % KSL) * BK2 * 2;
-#pragma unroll
-                for (int e = 0; e < L::NCHQ; ++e) dst[e] = buf_load16(qres, qsrc[e], so);
-            } else {
-                const rsrc_t qres = make_rsrc(Qm, (int64_t)R * q * 2);
-                const int so = ((s % KSL) * BK2 * q + t * 128) * 2;      // in bounds by construction
-#pragma unroll
-                for (int b = 0; b < L::BPT2; ++b) {
-                    const int vo = rows < 128 ? qsrc_half[b] : qsrc[b];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) dst[8 * b + e] = buf_load16(qres, vo, so + e * q * 2);
-                }
-            }
-        };
-        // LDS stores of one slab's items, each followed by the request for the same item of a later
-        // slab: the LDS port and the vector-memory address path then work side by side
-        auto q_commit_issue = [&](u32x4 (&rg)[NQ], unsigned char* base, int s_next, bool reload, auto&& between) {
-            int sn = s_next > ns2 - 1 ? ns2 - 1 : s_next;
-            const int t = tile_of(sn / KSL);
-            const int rows = q - t * 128 < 128 ? q - t * 128 : 128;
-            if constexpr (!TR) {
-                const rsrc_t qres = make_rsrc(Qm + (int64_t)t * 128 * R, (int64_t)rows * R * 2);
-                const int so = (sn % KSL) * BK2 * 2;
-#pragma unroll
-                for (int e = 0; e < L::NCHQ; ++e) {
-                    *reinterpret_cast<u32x4*>(base + qoff[e]) = rg[e];
-                    if (reload) rg[e] = buf_load16(qres, qsrc[e], so);
-                    __builtin_amdgcn_sched_barrier(0);
-                    between(e);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            } else {
-                const rsrc_t qres = make_rsrc(Qm, (int64_t)R * q * 2);
-                const int so = ((sn % KSL) * BK2 * q + t * 128) * 2;
-#pragma unroll
-                for (int b = 0; b < L::BPT2; ++b) {
-                    u32x4 in[8], out[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) in[e] = rg[8 * b + e];
-                    transpose8x8_b16(in, out);
-                    const int vo = rows < 128 ? qsrc_half[b] : qsrc[b];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        if (qoff[8 * b + j] >= 0) *reinterpret_cast<u32x4*>(base + qoff[8 * b + j]) = out[j];
-                        if (reload) rg[8 * b + j] = buf_load16(qres, vo, so + j * q * 2);
-                        __builtin_amdgcn_sched_barrier(0);
-                        if (j < 4) between(4 * b + j);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                }
-            }
-        };
         {
-            // ---------------- stage 1: one ring entry = this thread's items of one slab (64 rows of
-            // Xin, then the R rows of P), D1 slabs ahead
-            constexpr int NP = TR ? 8 * L::BPT1 : L::NCHP;
+            // stage 1: one ring entry = this thread's chunks of one slab (64 rows of Xin, then the R
+            // rows of P), D1 slabs ahead
             int xsrc[L::NCHX], off[L::NCHX];
 #pragma unroll
             for (int e = 0; e < L::NCHX; ++e) {
@@ -284,86 +186,52 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
                 off[e] = row * (BK1 * 2) + swz<CPR1>(ch, row) * 16;
                 xsrc[e] = (row * p + ch * 8) * 2;
             }
-            int poff[NP];
-            int psrc[TR ? L::BPT1 : 1];
-            int pstep;                                   // scalar stride between the items of one group
-            if constexpr (!TR) {
-                // P chunk e of this thread: row 32 e + lt / 8, chunk lt % 8
-                const int prow0 = lt / CPR1, pch = lt % CPR1;
-                psrc[0] = (prow0 * p + pch * 8) * 2;
-                pstep = (NLT / CPR1) * p * 2;            // 32 rows of P, in bytes
+            // P chunk e of this thread: row 32 e + lt / 8, chunk lt % 8
+            const int prow0 = lt / CPR1, pch = lt % CPR1;
+            const int psrc = (prow0 * p + pch * 8) * 2;
+            const int pstep = (NLT / CPR1) * p * 2;      // 32 rows of P, in bytes
+            int poff[L::NCHP];
 #pragma unroll
-                for (int e = 0; e < L::NCHP; ++e) {
-                    const int row = prow(e * (NLT / CPR1) + prow0);
-                    poff[e] = L::xpart + row * (BK1 * 2) + swz<CPR1>(pch, row) * 16;
-                }
-            } else {
-                pstep = R * 2;                           // one contraction row of the [p, R] matrix
-#pragma unroll
-                for (int b = 0; b < L::BPT1; ++b) {
-                    // block = contraction rows 8 rg .. + 7 of the slab, columns (P rows) 8 cc .. + 7
-                    const int idx = lt + b * L::ACT1;
-                    const int rg = idx & 7, cc = idx >> 3;
-                    const bool act = lt < L::ACT1;
-                    psrc[b] = act ? (8 * rg * R + 8 * cc) * 2 : kBufNowhere;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const int row = prow(8 * cc + j);
-                        poff[8 * b + j] = act ? L::xpart + row * (BK1 * 2) + swz<CPR1>(rg, row) * 16 : -1;
-                    }
-                }
+            for (int e = 0; e < L::NCHP; ++e) {
+                const int row = e * (NLT / CPR1) + prow0;
+                poff[e] = L::xpart + row * (BK1 * 2) + swz<CPR1>(pch, row) * 16;
             }
-            u32x4 ring[D1][L::NCHX + NP];
-            auto p_offset = [&](int slab) { return TR ? slab * (BK1 * R * 2) : slab * (BK1 * 2); };
-            auto load = [&](u32x4 (&dst)[L::NCHX + NP], int s) {
-                const int sa = slab1_of(s);
-                const int so = sa * (BK1 * 2), sp = p_offset(sa);
+            u32x4 ring[D1][L::NCHX + L::NCHP];
+            auto load = [&](u32x4 (&dst)[L::NCHX + L::NCHP], int s) {
+                const int so = slab1_of(s) * (BK1 * 2);
 #pragma unroll
                 for (int e = 0; e < L::NCHX; ++e) dst[e] = buf_load16(xres, xsrc[e], so);
-                if constexpr (!TR) {
 #pragma unroll
-                    for (int e = 0; e < NP; ++e) dst[L::NCHX + e] = buf_load16(pres, psrc[0], sp + e * pstep);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < NP; ++e) dst[L::NCHX + e] = buf_load16(pres, psrc[e >> 3], sp + (e & 7) * pstep);
-                }
+                for (int e = 0; e < L::NCHP; ++e) dst[L::NCHX + e] = buf_load16(pres, psrc, so + e * pstep);
             };
-            // steady state (reload) and first slab (no reload): LDS store of every item, each
-            // followed by the request for the same item of slab s_next
-            auto commit_issue = [&](u32x4 (&rg)[L::NCHX + NP], unsigned char* base, int s_next, bool reload) {
-                const int sa = slab1_of(s_next);
-                const int so = sa * (BK1 * 2), sp = p_offset(sa);
+            auto store = [&](const u32x4 (&srcv)[L::NCHX + L::NCHP], int slot) {
+#pragma unroll
+                for (int e = 0; e < L::NCHX; ++e) *reinterpret_cast<u32x4*>(lds + slot * L::slab1 + off[e]) = srcv[e];
+#pragma unroll
+                for (int e = 0; e < L::NCHP; ++e)
+                    *reinterpret_cast<u32x4*>(lds + slot * L::slab1 + poff[e]) = srcv[L::NCHX + e];
+            };
+            // steady state: chunk e of slab s+1 goes to LDS (slot s&1 is being read) and the same
+            // chunk of slab s+1+D1 is requested, alternating: the LDS port and the vector-memory
+            // address path then both stay busy instead of taking turns
+            auto step1 = [&](u32x4 (&rg)[L::NCHX + L::NCHP], int s) {
+                const int slot = (s + 1) & 1;
+                const int so = slab1_of(s + 1 + D1) * (BK1 * 2);
 #pragma unroll
                 for (int e = 0; e < L::NCHX; ++e) {
-                    *reinterpret_cast<u32x4*>(base + off[e]) = rg[e];
-                    if (reload) rg[e] = buf_load16(xres, xsrc[e], so);
+                    *reinterpret_cast<u32x4*>(lds + slot * L::slab1 + off[e]) = rg[e];
+                    rg[e] = buf_load16(xres, xsrc[e], so);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                if constexpr (!TR) {
 #pragma unroll
-                    for (int e = 0; e < NP; ++e) {
-                        *reinterpret_cast<u32x4*>(base + poff[e]) = rg[L::NCHX + e];
-                        if (reload) rg[L::NCHX + e] = buf_load16(pres, psrc[0], sp + e * pstep);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                } else {
-#pragma unroll
-                    for (int b = 0; b < L::BPT1; ++b) {
-                        u32x4 in[8], out[8];
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) in[e] = rg[L::NCHX + 8 * b + e];
-                        transpose8x8_b16(in, out);
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) {
-                            if (poff[8 * b + j] >= 0) *reinterpret_cast<u32x4*>(base + poff[8 * b + j]) = out[j];
-                            if (reload) rg[L::NCHX + 8 * b + j] = buf_load16(pres, psrc[b], sp + j * pstep);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                    }
+                for (int e = 0; e < L::NCHP; ++e) {
+                    *reinterpret_cast<u32x4*>(lds + slot * L::slab1 + poff[e]) = rg[L::NCHX + e];
+                    rg[L::NCHX + e] = buf_load16(pres, psrc, so + e * pstep);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             };
             load(ring[0], 0);
-            commit_issue(ring[0], lds, 0, false);
+            store(ring[0], 0);
 #pragma unroll
             for (int d = 1; d <= D1; ++d) load(ring[d % D1], d);
             TMARK(1, 0);
@@ -371,18 +239,29 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
             for (int s0 = 0; s0 < n1p; s0 += D1) {
 #pragma unroll
                 for (int d = 0; d < D1; ++d) {
-                    const int s = s0 + d;                   // slab s+1 goes to the slot not being read
-                    commit_issue(ring[(d + 1) % D1], lds + ((s + 1) & 1) * L::slab1, s + 1 + D1, true);
+                    step1(ring[(d + 1) % D1], s0 + d);
                     wg_barrier();
                 }
             }
             TMARK(1, 1);
         }
-        // ---------------- stage-2 ring: D2 slabs of Q in flight
-        u32x4 ring2[D2][NQ];
+        // stage-2 ring: D2 slabs of Q in flight.  The descriptor is rebuilt per slab (scalar work) to
+        // cover exactly the tile's rows: the wave-uniform offset of a buffer access is not range
+        // checked, only the per-lane part is.  Rows of a ragged last tile that lie past the end of Q
+        // then read as zeros; their output columns are never stored.
+        u32x4 ring2[D2][L::NCHQ];
+        auto load_q = [&](u32x4 (&dst)[L::NCHQ], int s) {
+            if (s > ns2 - 1) s = ns2 - 1;
+            const int t = tile_of(s / KSL);
+            const int rows = q - t * 128 < 128 ? q - t * 128 : 128;
+            const rsrc_t qres = make_rsrc(Qm + (int64_t)t * 128 * R, (int64_t)rows * R * 2);
+            const int so = (s % KSL) * BK2 * 2;
+#pragma unroll
+            for (int e = 0; e < L::NCHQ; ++e) dst[e] = buf_load16(qres, qsrc[e], so);
+        };
         if (Yout != nullptr) {
 #pragma unroll
-            for (int d = 0; d < D2; ++d) q_issue(ring2[d], d);
+            for (int d = 0; d < D2; ++d) load_q(ring2[d], d);
         }
 #pragma unroll
         for (int i = 0; i < L::n_mid_barriers; ++i) wg_barrier();
@@ -398,7 +277,9 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
         if (Yout == nullptr) return;
         const rsrc_t yres = make_rsrc(Yout + row0 * q, rows_valid * q * 2);
         wg_barrier();                                    // T tile consumed: LDS belongs to stage 2
-        q_commit_issue(ring2[0], lds, D2, true, [](int) {});
+#pragma unroll
+        for (int e = 0; e < L::NCHQ; ++e) *reinterpret_cast<u32x4*>(lds + qoff[e]) = ring2[0][e];
+        load_q(ring2[0], D2);
         wg_barrier();                                    // Q slab 0 is in slot 0
         // stage 2: the Q slabs, and the finished output tiles: tile t was staged in LDS by the MFMA
         // waves during the last slab of t and leaves here, one slab later, as full 256-byte rows, in
@@ -426,6 +307,28 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
             const bool whole = q - t * 128 >= 128;
             if (whole || yleft[e]) buf_store16(ypiece[e], yres, ydst[e], t * 256);
         };
+        auto step2 = [&](u32x4 (&rg)[L::NCHQ], int s, bool flush, int seq) {
+            const int slot = (s + 1) & 1;
+            int sn = s + 1 + D2;
+            if (sn > ns2 - 1) sn = ns2 - 1;
+            const int tn = tile_of(sn / KSL);
+            const int rows = q - tn * 128 < 128 ? q - tn * 128 : 128;
+            const rsrc_t qres = make_rsrc(Qm + (int64_t)tn * 128 * R, (int64_t)rows * R * 2);
+            const int so = (sn % KSL) * BK2 * 2;
+            if (flush) flush_read(seq);
+#pragma unroll
+            for (int e = 0; e < L::NCHQ; ++e) {
+                *reinterpret_cast<u32x4*>(lds + slot * L::slab2 + qoff[e]) = rg[e];
+                rg[e] = buf_load16(qres, qsrc[e], so);
+                __builtin_amdgcn_sched_barrier(0);
+                if (e < 4 && flush) flush_store(seq, e);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (flush) {
+#pragma unroll
+                for (int e = L::NCHQ; e < 4; ++e) flush_store(seq, e);
+            }
+        };
         int flushed = 0;
         for (int s0 = 0; s0 < n2p; s0 += D2) {
 #pragma unroll
@@ -433,16 +336,8 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
                 const int s = s0 + d;
                 const bool flush = s > 0 && s % KSL == 0 && flushed < ntile;
                 TSTAMP(1, 0, s);
-                if (flush) flush_read(flushed);
-                int stored = 0;
-                q_commit_issue(ring2[(d + 1) % D2], lds + ((s + 1) & 1) * L::slab2, s + 1 + D2, true,
-                               [&](int e) { if (flush && e < 4) { flush_store(flushed, e); stored |= 1 << e; } });
-                if (flush) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (!(stored & (1 << e))) flush_store(flushed, e);
-                    ++flushed;
-                }
+                step2(ring2[(d + 1) % D2], s, flush, flushed);
+                if (flush) ++flushed;
                 TSTAMP(1, 3, s);
                 wg_barrier();
             }
@@ -487,7 +382,7 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
                 }
 #pragma unroll
                 for (int b = 0; b < CB; ++b) {
-                    const int row = 64 + prow((cs * CB + b) * 32 + lj);
+                    const int row = 64 + (cs * CB + b) * 32 + lj;
                     pf[b] = *reinterpret_cast<const u32x4*>(base + row * (BK1 * 2) + swz<CPR1>(qc, row) * 16);
                 }
 #pragma unroll
@@ -612,19 +507,19 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
     TMARK(0, 6);
 }
 
-template <int R, bool TR>
+template <int R>
 hipError_t launch_chain2_r(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                            int64_t M, int p, int q, hipStream_t s) {
     constexpr int lds_bytes = Ch2Cfg<R>::lds_bytes;
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chain2_bf16_kernel<R, TR>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chain2_bf16_kernel<R>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((chain2_bf16_kernel<R, TR>), dim3((unsigned)ceil_div(M, 64)), dim3(NT), lds_bytes, s,
+    hipLaunchKernelGGL(chain2_bf16_kernel<R>, dim3((unsigned)ceil_div(M, 64)), dim3(NT), lds_bytes, s,
                        (const uint16_t*)Xin, (const uint16_t*)P, (const uint16_t*)Q,
                        (uint16_t*)Yout, (uint16_t*)Tout, M, p, q);
     return hipGetLastError();
@@ -641,17 +536,17 @@ bool chain2_supports(int R, int p, int q) {
 }
 
 hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
-                              int64_t M, int p, int q, int R, int transposed, hipStream_t s) {
+                              int64_t M, int p, int q, int R, hipStream_t s) {
     switch (R) {
-        case 32: return transposed ? launch_chain2_r<32, true>(Xin, P, Q, Yout, Tout, M, p, q, s) : launch_chain2_r<32, false>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 64: return transposed ? launch_chain2_r<64, true>(Xin, P, Q, Yout, Tout, M, p, q, s) : launch_chain2_r<64, false>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 96: return transposed ? launch_chain2_r<96, true>(Xin, P, Q, Yout, Tout, M, p, q, s) : launch_chain2_r<96, false>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 128: return transposed ? launch_chain2_r<128, true>(Xin, P, Q, Yout, Tout, M, p, q, s) : launch_chain2_r<128, false>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 160: return transposed ? launch_chain2_r<160, true>(Xin, P, Q, Yout, Tout, M, p, q, s) : launch_chain2_r<160, false>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 192: return transposed ? launch_chain2_r<192, true>(Xin, P, Q, Yout, Tout, M, p, q, s) : launch_chain2_r<192, false>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 256: return transposed ? launch_chain2_r<256, true>(Xin, P, Q, Yout, Tout, M, p, q, s) : launch_chain2_r<256, false>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 320: return transposed ? launch_chain2_r<320, true>(Xin, P, Q, Yout, Tout, M, p, q, s) : launch_chain2_r<320, false>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 384: return transposed ? launch_chain2_r<384, true>(Xin, P, Q, Yout, Tout, M, p, q, s) : launch_chain2_r<384, false>(Xin, P, Q, Yout, Tout, M, p, q, s);
+        case 32: return launch_chain2_r<32>(Xin, P, Q, Yout, Tout, M, p, q, s);
+        case 64: return launch_chain2_r<64>(Xin, P, Q, Yout, Tout, M, p, q, s);
+        case 96: return launch_chain2_r<96>(Xin, P, Q, Yout, Tout, M, p, q, s);
+        case 128: return launch_chain2_r<128>(Xin, P, Q, Yout, Tout, M, p, q, s);
+        case 160: return launch_chain2_r<160>(Xin, P, Q, Yout, Tout, M, p, q, s);
+        case 192: return launch_chain2_r<192>(Xin, P, Q, Yout, Tout, M, p, q, s);
+        case 256: return launch_chain2_r<256>(Xin, P, Q, Yout, Tout, M, p, q, s);
+        case 320: return launch_chain2_r<320>(Xin, P, Q, Yout, Tout, M, p, q, s);
+        case 384: return launch_chain2_r<384>(Xin, P, Q, Yout, Tout, M, p, q, s);
         default: return hipErrorInvalidValue;
     }
 }

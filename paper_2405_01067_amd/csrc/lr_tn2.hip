@@ -104,8 +104,14 @@ __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int co
         for (int e = 0; e < 8; ++e) dst[e] = buf_load16(res, goff[e] + b * gstep, 0);
     };
     auto store_block = [&](const u32x4 (&v)[8], unsigned char* base, int b) {
+        // 8 x 8 transpose of 16-bit elements: word i of output column j packs rows 2i, 2i+1
         u32x4 out[8];
-        transpose8x8_b16(v, out);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                out[j][i] = __builtin_amdgcn_perm(v[2 * i + 1][j >> 1], v[2 * i][j >> 1],
+                                                  (j & 1) ? 0x07060302u : 0x05040100u);
         if (active) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x4*>(base + (loff[j] ^ (b * 64))) = out[j];
