@@ -53,7 +53,7 @@ struct LayerDev {
 };
 
 // ------------------------------------------------------------------------------------------
-// zero-fill (also used instead of memset so the call sequence stays graph-capturable)
+// zero-fill by a kernel (fill kernels, not memset nodes, are what stays correct under graph replay)
 // ------------------------------------------------------------------------------------------
 __global__ void fill_i32_kernel(int* p, int64_t n, int v) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
