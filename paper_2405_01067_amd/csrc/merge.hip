@@ -26,12 +26,17 @@ namespace {
 constexpr int kInfoInts = 4;      // per layer: sweeps, n_sigma, converged, k'
 constexpr int kMaxSweepsCap = 64;
 constexpr double kRotateTol = 1e-10;   // |cos| above which a column pair is rotated
-constexpr double kSignifTol = 1e-7;    // a sweep with no |cos| above this ends the iteration
+// A sweep in which no visited pair had |cos| above kSignifTol ends the iteration.  Every such pair
+// was still rotated to orthogonality when visited and the later rotations of that sweep disturb it
+// only by O(cos^2), so the cosines left behind are of order 1e-10 (1e-7 gave the same results to
+// the last bit on the config-5 layers at one more sweep).
+constexpr double kSignifTol = 1e-5;
 constexpr double kSigmaFloor = 1e-7;   // sigma_i <= floor * sigma_1: singular vectors returned as zero
 // A column of C with |c|^2 below kZeroColumn2 ||C||_F^2 (|c| < 1e-9 ||C||_F) is numerically zero
 // and is left alone: what it holds is the rounding noise (about 1e-16 ||C||) of the large columns
-// it was rotated with, so its angles cannot be resolved to the 1e-7 the convergence test asks
-// for.  It belongs to a singular value far below kSigmaFloor sigma_1 (||C||_F <= sqrt(K) sigma_1).
+// it was rotated with, so its angles are noise at the level the convergence test looks at and
+// would keep the iteration from ending.  It belongs to a singular value far below
+// kSigmaFloor sigma_1 (||C||_F <= sqrt(K) sigma_1).
 constexpr double kZeroColumn2 = 1e-18;
 
 struct LayerDev {
