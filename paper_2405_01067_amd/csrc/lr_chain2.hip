@@ -259,12 +259,18 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
 #pragma unroll
             for (int e = 0; e < L::NCHQ; ++e) dst[e] = buf_load16(qres, qsrc[e], so);
         };
-        if (Yout != nullptr) {
+        // The first D2 slabs of Q are requested around the barriers of the T phase, one slab per
+        // barrier and the rest after the last: requesting them all first would hold the MFMA waves
+        // at the first of those barriers for as long as the requests take to issue.
 #pragma unroll
-            for (int d = 0; d < D2; ++d) load_q(ring2[d], d);
+        for (int i = 0; i <= L::n_mid_barriers; ++i) {
+            if (Yout != nullptr) {
+#pragma unroll
+                for (int d = 0; d < D2; ++d)
+                    if ((d < L::n_mid_barriers ? d : L::n_mid_barriers) == i) load_q(ring2[d], d);
+            }
+            if (i < L::n_mid_barriers) wg_barrier();
         }
-#pragma unroll
-        for (int i = 0; i < L::n_mid_barriers; ++i) wg_barrier();
         // T tile is in LDS: store it (the MFMA waves load their operands from it meanwhile)
         if (Tout != nullptr) {
             const rsrc_t tres = make_rsrc(Tout + row0 * R, rows_valid * R * 2);
@@ -395,57 +401,86 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
     }
 
     TMARK(0, 2);
-    // ------------------------------------------------------------------ tree reduction over the KS groups
-    if constexpr (KS > 1) {
-        // layout: [wave slot][block (a,b)][quad g][lane][4 floats]: one 16-byte access per quad
+    // ------------------------------------------------------------------ sum over the KS groups, T tile (bf16) to LDS
+    // lane holds T[32(rs RA + a) + lj][32(cs CB + b) + 8g + 4 lh + (0..3)] in acc1[a][b][4g .. 4g+3]
+    auto emit_T = [&](const f32x16 (&blk)[CB], int a) {
+#pragma unroll
+        for (int b = 0; b < CB; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                u32x2 o = {pack2_bf16(blk[b][4 * g + 0], blk[b][4 * g + 1]),
+                           pack2_bf16(blk[b][4 * g + 2], blk[b][4 * g + 3])};
+                *reinterpret_cast<u32x2*>(ttile + (32 * (rs * RA + a) + lj) * L::tpitch +
+                                          (32 * (cs * CB + b) + 8 * g + 4 * lh) * 2) = o;
+            }
+    };
+    if constexpr (KS == 2 && RA == 2) {
+        // Two contraction groups: the partners swap halves instead of one sending everything.  Wave ks
+        // sends its row block 1 - ks, adds what it receives to its row block ks and converts that
+        // half of T itself: every wave stores and loads half as much, and all four convert.
         f32x4* red = reinterpret_cast<f32x4*>(lds);
-        const int wslot = rs * CS + cs;
+        auto swap_and_emit = [&](const f32x16 (&send)[CB], f32x16 (&keep)[CB], int a_keep) {
+            f32x4* dst = red + (size_t)((ks * CS + cs) * CB) * 4 * 64;
 #pragma unroll
-        for (int half = KS / 2; half >= 1; half >>= 1) {
-            if (ks >= half && ks < 2 * half) {
-                f32x4* dst = red + (size_t)(((ks - half) * (CS * RS) + wslot) * (RA * CB)) * 4 * 64;
+            for (int b = 0; b < CB; ++b)
 #pragma unroll
-                for (int a = 0; a < RA; ++a)
-#pragma unroll
-                    for (int b = 0; b < CB; ++b)
-#pragma unroll
-                        for (int g = 0; g < 4; ++g)
-                            dst[((a * CB + b) * 4 + g) * 64 + lane] =
-                                f32x4{acc1[a][b][4 * g], acc1[a][b][4 * g + 1], acc1[a][b][4 * g + 2], acc1[a][b][4 * g + 3]};
-            }
+                for (int g = 0; g < 4; ++g)
+                    dst[(b * 4 + g) * 64 + lane] = f32x4{send[b][4 * g], send[b][4 * g + 1], send[b][4 * g + 2], send[b][4 * g + 3]};
             wg_barrier();
-            if (ks < half) {
-                const f32x4* src = red + (size_t)((ks * (CS * RS) + wslot) * (RA * CB)) * 4 * 64;
-#pragma unroll
-                for (int a = 0; a < RA; ++a)
-#pragma unroll
-                    for (int b = 0; b < CB; ++b)
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            const f32x4 v = src[((a * CB + b) * 4 + g) * 64 + lane];
-                            acc1[a][b][4 * g] += v[0]; acc1[a][b][4 * g + 1] += v[1];
-                            acc1[a][b][4 * g + 2] += v[2]; acc1[a][b][4 * g + 3] += v[3];
-                        }
-            }
-            if (half > 1) wg_barrier();                 // the next round overwrites what was just read
-        }
-    }
-
-    TMARK(0, 3);
-    // ------------------------------------------------------------------ T tile (bf16) to LDS, operand registers
-    if (ks == 0) {
-        // lane holds T[32(rs RA + a) + lj][32(cs CB + b) + 8g + 4 lh + (0..3)] in acc1[a][b][4g .. 4g+3]
-#pragma unroll
-        for (int a = 0; a < RA; ++a)
+            const f32x4* src = red + (size_t)(((1 - ks) * CS + cs) * CB) * 4 * 64;
 #pragma unroll
             for (int b = 0; b < CB; ++b)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    u32x2 o = {pack2_bf16(acc1[a][b][4 * g + 0], acc1[a][b][4 * g + 1]),
-                               pack2_bf16(acc1[a][b][4 * g + 2], acc1[a][b][4 * g + 3])};
-                    *reinterpret_cast<u32x2*>(ttile + (32 * (rs * RA + a) + lj) * L::tpitch +
-                                              (32 * (cs * CB + b) + 8 * g + 4 * lh) * 2) = o;
+                    const f32x4 v = src[(b * 4 + g) * 64 + lane];
+                    keep[b][4 * g] += v[0]; keep[b][4 * g + 1] += v[1];
+                    keep[b][4 * g + 2] += v[2]; keep[b][4 * g + 3] += v[3];
                 }
+            TMARK(0, 3);
+            emit_T(keep, a_keep);
+        };
+        if (ks == 0) swap_and_emit(acc1[1], acc1[0], 0);
+        else swap_and_emit(acc1[0], acc1[1], 1);
+    } else {
+        if constexpr (KS > 1) {
+            // tree; layout: [wave slot][block (a,b)][quad g][lane][4 floats]: one 16-byte access per quad
+            f32x4* red = reinterpret_cast<f32x4*>(lds);
+            const int wslot = rs * CS + cs;
+#pragma unroll
+            for (int half = KS / 2; half >= 1; half >>= 1) {
+                if (ks >= half && ks < 2 * half) {
+                    f32x4* dst = red + (size_t)(((ks - half) * (CS * RS) + wslot) * (RA * CB)) * 4 * 64;
+#pragma unroll
+                    for (int a = 0; a < RA; ++a)
+#pragma unroll
+                        for (int b = 0; b < CB; ++b)
+#pragma unroll
+                            for (int g = 0; g < 4; ++g)
+                                dst[((a * CB + b) * 4 + g) * 64 + lane] =
+                                    f32x4{acc1[a][b][4 * g], acc1[a][b][4 * g + 1], acc1[a][b][4 * g + 2], acc1[a][b][4 * g + 3]};
+                }
+                wg_barrier();
+                if (ks < half) {
+                    const f32x4* src = red + (size_t)((ks * (CS * RS) + wslot) * (RA * CB)) * 4 * 64;
+#pragma unroll
+                    for (int a = 0; a < RA; ++a)
+#pragma unroll
+                        for (int b = 0; b < CB; ++b)
+#pragma unroll
+                            for (int g = 0; g < 4; ++g) {
+                                const f32x4 v = src[((a * CB + b) * 4 + g) * 64 + lane];
+                                acc1[a][b][4 * g] += v[0]; acc1[a][b][4 * g + 1] += v[1];
+                                acc1[a][b][4 * g + 2] += v[2]; acc1[a][b][4 * g + 3] += v[3];
+                            }
+                }
+                if (half > 1) wg_barrier();             // the next round overwrites what was just read
+            }
+        }
+        TMARK(0, 3);
+        if (ks == 0) {
+#pragma unroll
+            for (int a = 0; a < RA; ++a) emit_T(acc1[a], a);
+        }
     }
     wg_barrier();                                       // last of the mid barriers: T tile complete
     if (Yout == nullptr) return;
