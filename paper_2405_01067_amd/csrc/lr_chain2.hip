@@ -230,10 +230,11 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
                     __builtin_amdgcn_sched_barrier(0);
                 }
             };
-            load(ring[0], 0);
-            store(ring[0], 0);
+            // all D1 slabs are requested before the first one is waited for
 #pragma unroll
-            for (int d = 1; d <= D1; ++d) load(ring[d % D1], d);
+            for (int d = 0; d < D1; ++d) load(ring[d], d);
+            store(ring[0], 0);
+            load(ring[0], D1);
             TMARK(1, 0);
             wg_barrier();                                   // slab 0 is in slot 0
             for (int s0 = 0; s0 < n1p; s0 += D1) {

@@ -117,16 +117,17 @@ __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int co
             for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x4*>(base + (loff[j] ^ (b * 64))) = out[j];
         }
     };
-    {
-        const rsrc_t res = descriptor(0);
+    // all D slabs are requested before the first one is waited for
 #pragma unroll
-        for (int b = 0; b < BPT; ++b) { load_block(ring[0][b], res, b); store_block(ring[0][b], lds, b); }
-    }
-#pragma unroll
-    for (int d = 1; d <= D; ++d) {
+    for (int d = 0; d < D; ++d) {
         const rsrc_t res = descriptor(d);
 #pragma unroll
-        for (int b = 0; b < BPT; ++b) load_block(ring[d % D][b], res, b);
+        for (int b = 0; b < BPT; ++b) load_block(ring[d][b], res, b);
+    }
+    {
+        const rsrc_t res = descriptor(D);
+#pragma unroll
+        for (int b = 0; b < BPT; ++b) { store_block(ring[0][b], lds, b); load_block(ring[0][b], res, b); }
     }
     ring_barrier();                                      // slab 0 is in slot 0
     for (int s0 = 0; s0 < np; s0 += D) {
