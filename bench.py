@@ -24,9 +24,9 @@ METRIC = "factored fwd+bwd TFLOP/s (% bf16 MFMA peak) + ab_merge ms per ViT-B/16
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes of one forward chain launch on config 2, from two rocprofv3 --pmc runs of this file
-# (profiles/chain2_r192_cfg2_pmc.txt): FETCH_SIZE 15794 KiB x 2.0 (the factor that makes a plain
+# (profiles/chain2_r192_cfg2_pmc.txt): FETCH_SIZE 15623 KiB x 2.0 (the factor that makes a plain
 # 256 MiB copy read 256 MiB) + WRITE_SIZE 80376 KiB x 1.0.  A stored measurement, not a live one.
-CHAIN_FWD_TRAFFIC_BYTES = int((15794.2 * 2.0 + 80376.0) * 1024)
+CHAIN_FWD_TRAFFIC_BYTES = int((15623.2 * 2.0 + 80376.0) * 1024)
 
 
 def main():
