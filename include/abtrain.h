@@ -196,7 +196,9 @@ int ab_factorize_batched(const abt_factorize_desc* layers, int L,
 
 size_t ab_factorize_batched_workspace_bytes(const abt_factorize_desc* layers, int L);
 
-/* Sweep cap of the Jacobi SVD (default 16, clamped to [1, 64]); returns the previous value. */
+/* Sweep cap of the Jacobi SVD (default 30, clamped to [1, 64]; sweeps stop as soon as every layer
+ * has converged: 8-9 for the 384-wide cores of config 5, about 15 for dense 768-wide weights);
+ * returns the previous value. */
 int abt_set_jacobi_max_sweeps(int max_sweeps);
 
 #ifdef __cplusplus

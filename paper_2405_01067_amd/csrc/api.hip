@@ -8,7 +8,7 @@ using namespace abt;
 
 namespace {
 
-int g_max_sweeps = 16;
+int g_max_sweeps = 30;
 
 // Chain kernel choice: the 64-row kernel with loader and MFMA waves wherever it supports the rank
 // (32, 64, 96, 128, 160, 192, 256, 320, 384), else the older 128-row kernel (224, 288, 352).
