@@ -94,6 +94,18 @@ def test_planted_gap(m, n, k_in, G, gap, mode):
     compare(out, ref, expect_k=gap, check_W=True)
 
 
+def test_wide_core_by_concatenation():
+    # mode 1 with G k = 1024 columns: wider than what the 16-lane-group Jacobi kernels take (768),
+    # so the general one-pair-per-wave kernels run; the concatenated core has rank <= 256 + noise
+    m, n, k_in, G, gap = 1152, 1088, 256, 4, 100
+    lay = gen.merge_layer(m, n, seed=77, k_in=k_in, g=G, gap_at=gap)
+    tau = gap_tau(lay["sigma_planted"], gap)
+    out = abt.ab_merge([dev(a) for a in lay["A_copies"]], [dev(b) for b in lay["B_copies"]],
+                       tau=tau, mode=1, k_cap=256)
+    ref = orc.ab_merge(lay["A_copies"], lay["B_copies"], tau=tau, mode=1)
+    compare(out, ref, expect_k=gap)
+
+
 def test_identical_copies_are_a_fixed_point():
     rng = np.random.default_rng(3)
     sigma = np.linspace(4.0, 1.0, 32)
