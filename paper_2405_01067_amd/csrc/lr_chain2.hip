@@ -33,6 +33,10 @@
 // = B[8h..8h+7][l%32], accumulator v = C[8(v/4) + 4h + v%4][l%32].
 #include "common.h"
 
+// Phase timing for tuning, compiled out of the library: with -DABT_TIMING, wave 0 (role 0, an MFMA
+// wave) and wave 4 (role 1, a loader wave) of work-group 5 record the cycle counter at the marked
+// points into abt_tbuf (once per launch) and abt_tl (per slab of stage 2); a test program that
+// includes this file reads them back with hipMemcpyFromSymbol.
 #ifdef ABT_TIMING
 __device__ long long abt_tbuf[2][64];
 #define TMARK(role, i) do { if (blockIdx.x == 5 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 4 : 0)) abt_tbuf[role][i] = __builtin_readcyclecounter(); } while (0)

@@ -15,6 +15,7 @@
 // ds_read_b64_tr_b16 instead was limited by the rate of those 8-byte reads.)
 #include "common.h"
 
+// Per-slab timing for tuning, compiled out of the library (see the same switch in lr_chain2.hip).
 #ifdef ABT_TIMING
 __device__ long long abt_tn_tl[2][2][64];
 #define TN_STAMP(role, k, it) do { if (blockIdx.x == 26 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 4 : 0) && (it) < 64) abt_tn_tl[role][k][it] = __builtin_readcyclecounter(); } while (0)
