@@ -450,9 +450,19 @@ __device__ __forceinline__ bool jacobi_rotation(double alpha, double beta, doubl
     if (!(alpha > floor2) || !(beta > floor2)) return false;
     significant = g2 > (kSignifTol * kSignifTol) * lim;
     if (!(g2 > (kRotateTol * kRotateTol) * lim)) return false;
-    const double zeta = (beta - alpha) / (2.0 * gamma);
-    const double tn = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-    c = 1.0 / sqrt(1.0 + tn * tn);
+    // tangent of the rotation angle, the smaller root of t^2 + 2 zeta t - 1 = 0 with
+    // zeta = (beta - alpha) / (2 gamma), written so that it costs one square root and one division:
+    // t = 2 gamma sign(d) / (|d| + sqrt(d^2 + 4 gamma^2)), d = beta - alpha
+    const double d = beta - alpha;
+    const double g2x = 2.0 * gamma;
+    const double tn = (d >= 0.0 ? g2x : -g2x) / (fabs(d) + sqrt(fma(d, d, g2x * g2x)));
+    // c = (1 + t^2)^(-1/2): hardware reciprocal square root refined by two Newton steps (the
+    // rotation stays orthogonal to rounding: c^2 + s^2 = c^2 (1 + t^2))
+    const double w = fma(tn, tn, 1.0);
+    double y = __builtin_amdgcn_rsq(w);
+    y = y * fma(-0.5 * w, y * y, 1.5);
+    y = y * fma(-0.5 * w, y * y, 1.5);
+    c = y;
     s = c * tn;
     if (tangent) *tangent = tn;
     return true;
