@@ -600,16 +600,16 @@ __global__ __launch_bounds__(256) void jacobi_cross16_kernel(const LayerDev* __r
         const int ci = (g + step) & 15;
         double* ycol = right + ci * pitch;
         f64x2 y[NE2];
-        double gamma = 0.0;
+        double gsum[4] = {0.0, 0.0, 0.0, 0.0};           // four independent chains, fixed order
 #pragma unroll
         for (int j = 0; j < NE2; ++j) {
             const int r = 32 * j + 2 * l16;
             y[j] = f64x2{0.0, 0.0};
             if (r < K) y[j] = *reinterpret_cast<const f64x2*>(ycol + r);
-            gamma = fma(x[j][0], y[j][0], gamma);
-            gamma = fma(x[j][1], y[j][1], gamma);
+            gsum[2 * (j & 1)] = fma(x[j][0], y[j][0], gsum[2 * (j & 1)]);
+            gsum[2 * (j & 1) + 1] = fma(x[j][1], y[j][1], gsum[2 * (j & 1) + 1]);
         }
-        gamma = row16_sum(gamma);
+        double gamma = row16_sum((gsum[0] + gsum[1]) + (gsum[2] + gsum[3]));
         const double beta = rn[ci];
         double c, s, t; bool signif;
         if (jacobi_rotation(alpha, beta, gamma, floor2, c, s, signif, &t)) {
@@ -686,16 +686,16 @@ __global__ __launch_bounds__(128) void jacobi_intra16_kernel(const LayerDev* __r
         double* xc = cols + p * pitch;
         double* yc = cols + q * pitch;
         f64x2 x[NE2], y[NE2];
-        double gamma = 0.0;
+        double gsum[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
         for (int j = 0; j < NE2; ++j) {
             const int r = 32 * j + 2 * l16;
             x[j] = f64x2{0.0, 0.0}; y[j] = f64x2{0.0, 0.0};
             if (r < K) { x[j] = *reinterpret_cast<const f64x2*>(xc + r); y[j] = *reinterpret_cast<const f64x2*>(yc + r); }
-            gamma = fma(x[j][0], y[j][0], gamma);
-            gamma = fma(x[j][1], y[j][1], gamma);
+            gsum[2 * (j & 1)] = fma(x[j][0], y[j][0], gsum[2 * (j & 1)]);
+            gsum[2 * (j & 1) + 1] = fma(x[j][1], y[j][1], gsum[2 * (j & 1) + 1]);
         }
-        gamma = row16_sum(gamma);
+        double gamma = row16_sum((gsum[0] + gsum[1]) + (gsum[2] + gsum[3]));
         const double alpha = cn[p], beta = cn[q];
         double c, s, t; bool signif;
         if (jacobi_rotation(alpha, beta, gamma, floor2, c, s, signif, &t)) {
