@@ -10,8 +10,8 @@ W = A B with A = U_k Sigma_k^(1/2) (m x k) and B = Sigma_k^(1/2) V_k^T (k x n).
 The layer acts as y = x W^T, so for a batch X (M x n):  T = X B^T (M x k),  Y = T A^T (M x m).
 
 Pins (tests/test_oracle_pins.py): every function below is checked against closed forms,
-finite differences, planted spectra, brute-force Jacobi on tiny matrices and invariants.
-Nothing here is "parity unpinned".
+finite differences, planted spectra, brute-force Jacobi on tiny matrices, invariants and, for
+the optimiser step, a library optimiser run in fp64.  Nothing here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -142,3 +142,62 @@ def merged_spectrum(A_copies, B_copies, mode=0):
     if W.shape[1] > W.shape[0]:
         W = W.T
     return np.linalg.svd(W, compute_uv=False)
+
+
+# --------------------------------------------------------------------------------------
+# group training step (Sec. "Methodology", group-training phase of Algorithm 1; Sec. "Learning
+# rate rebound"; the experiments train with AdamW, Sec. "Experiments")
+# --------------------------------------------------------------------------------------
+
+def lr_rebound_scale(i, rebound_steps):
+    """Factor applied to the scheduled learning rate i steps (0-based) after a change of the
+    parameters' shape.  The paper says the rate drops to near zero and climbs back to its
+    scheduled value over `rebound_steps` steps; the shape of the climb is not given.  Reading:
+    linear, (i + 1) / rebound_steps, capped at 1; rebound_steps <= 0 means no rebound."""
+    if rebound_steps <= 0:
+        return 1.0
+    return min(1.0, (int(i) + 1) / float(rebound_steps))
+
+
+def adamw_step(theta, g, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01,
+               lr_scale=1.0):
+    """One step of Adam with decoupled weight decay (the optimiser the paper's experiments
+    name), step counter t >= 1, on fp64 copies of the arguments:
+
+        m' = b1 m + (1 - b1) g                 v' = b2 v + (1 - b2) g^2
+        mh = m' / (1 - b1^t)                   vh = v' / (1 - b2^t)
+        theta' = theta - eta (mh / (sqrt(vh) + eps) + lambda theta),   eta = lr * lr_scale.
+
+    The rebound factor multiplies the whole step (gradient part and decay part alike), as a
+    change of the learning rate does.  Returns (theta', m', v')."""
+    theta, g, m, v = _f64(theta), _f64(g), _f64(m), _f64(v)
+    assert t >= 1
+    m1 = beta1 * m + (1.0 - beta1) * g
+    v1 = beta2 * v + (1.0 - beta2) * g * g
+    mh = m1 / (1.0 - beta1 ** t)
+    vh = v1 / (1.0 - beta2 ** t)
+    eta = lr * lr_scale
+    return theta - eta * (mh / (np.sqrt(vh) + eps) + weight_decay * theta), m1, v1
+
+
+def group_train_step(X, dY, A, B, target, state, t, lr, lr_scale=1.0, **hyper):
+    """One step of the group-training phase for one layer and a given upstream gradient dY:
+    forward and backward of the factored layer, then an AdamW step on the factor this group
+    trains (target 'A' or 'B'); the other factor is frozen and keeps its value.  `state` is the
+    pair (m, v) of the trained factor.  Returns a dict with Y, dX, the gradient used, the new
+    factors and the new state."""
+    Y, _ = lr_linear_fwd(X, A, B)
+    dX, dA, dB, _ = lr_linear_bwd(dY, X, A, B)
+    m, v = state
+    if target == "A":
+        A1, m1, v1 = adamw_step(A, dA, m, v, t, lr, lr_scale=lr_scale, **hyper)
+        return {"Y": Y, "dX": dX, "grad": dA, "A": A1, "B": _f64(B), "state": (m1, v1)}
+    if target == "B":
+        B1, m1, v1 = adamw_step(B, dB, m, v, t, lr, lr_scale=lr_scale, **hyper)
+        return {"Y": Y, "dX": dX, "grad": dB, "A": _f64(A), "B": B1, "state": (m1, v1)}
+    raise ValueError("target must be 'A' or 'B'")
+
+
+def reconstruct(A, B):
+    """W <- A B, the hand-off from the factors back to the full-rank weight (Algorithm 1)."""
+    return _f64(A) @ _f64(B)

@@ -347,3 +347,100 @@ def test_bf16_rounding_helper_is_rne():
     assert r[3] == -2.5 and r[6] == np.inf
     assert abs(r[4] - 3.140625) < 1e-7
     assert np.all(np.abs(r[:5] - x[:5]) <= np.abs(x[:5]) * 2.0 ** -8)
+
+
+# ---------------------------------------------------------------------------------------------
+# group-training step: AdamW, learning-rate rebound, frozen factor, reconstruction
+# ---------------------------------------------------------------------------------------------
+
+def test_adamw_first_step_closed_form():
+    # from a zero state the bias-corrected moments are g and g^2: theta moves by lr g/(|g|+eps),
+    # whatever the betas are; the decay term is lr * lambda * theta.
+    rng = np.random.default_rng(5)
+    th = rng.standard_normal(50)
+    g = rng.standard_normal(50) * 10.0 ** rng.integers(-6, 3, 50)
+    for b1, b2 in ((0.9, 0.999), (0.5, 0.7)):
+        th1, m1, v1 = orc.adamw_step(th, g, 0 * th, 0 * th, 1, 1e-2, b1, b2, 1e-8, 0.0)
+        np.testing.assert_allclose(th1, th - 1e-2 * g / (np.abs(g) + 1e-8), rtol=1e-13, atol=0)
+        np.testing.assert_allclose(m1, (1 - b1) * g, rtol=1e-14)
+        np.testing.assert_allclose(v1, (1 - b2) * g * g, rtol=1e-14)
+    th2, _, _ = orc.adamw_step(th, g, 0 * th, 0 * th, 1, 1e-2, 0.9, 0.999, 1e-8, 0.3)
+    np.testing.assert_allclose(th2 - th1, -1e-2 * 0.3 * th, rtol=1e-10, atol=1e-16)
+
+
+def test_adamw_constant_gradient_and_pure_decay():
+    # a constant gradient keeps mh = g, vh = g^2 at every step: t equal moves of lr*sign(g)
+    g = np.array([3.0, -0.25, 1e-3])
+    th, m, v = np.zeros(3), np.zeros(3), np.zeros(3)
+    for t in range(1, 8):
+        th, m, v = orc.adamw_step(th, g, m, v, t, 1e-3, 0.9, 0.999, 0.0, 0.0)
+        np.testing.assert_allclose(th, -t * 1e-3 * np.sign(g), rtol=1e-12)
+    # zero gradient: only the decoupled decay acts, theta_t = theta_0 (1 - lr lambda)^t
+    th0 = np.array([2.0, -5.0])
+    th, m, v = th0.copy(), np.zeros(2), np.zeros(2)
+    for t in range(1, 6):
+        th, m, v = orc.adamw_step(th, np.zeros(2), m, v, t, 0.1, weight_decay=0.5)
+        np.testing.assert_allclose(th, th0 * (1 - 0.05) ** t, rtol=1e-13)
+        assert np.all(m == 0) and np.all(v == 0)
+
+
+def test_adamw_against_library_optimizer():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(11)
+    th0 = rng.standard_normal((7, 5))
+    p = torch.nn.Parameter(torch.tensor(th0, dtype=torch.float64))
+    opt = torch.optim.AdamW([p], lr=3e-3, betas=(0.8, 0.95), eps=1e-6, weight_decay=0.1)
+    th, m, v = th0.copy(), np.zeros_like(th0), np.zeros_like(th0)
+    for t in range(1, 13):
+        g = rng.standard_normal((7, 5)) * (0.1 if t % 3 else 10.0)
+        scale = orc.lr_rebound_scale(t - 1, 6)
+        for group in opt.param_groups:
+            group["lr"] = 3e-3 * scale
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        th, m, v = orc.adamw_step(th, g, m, v, t, 3e-3, 0.8, 0.95, 1e-6, 0.1, lr_scale=scale)
+        np.testing.assert_allclose(th, p.detach().numpy(), rtol=1e-12, atol=1e-14)
+    st = opt.state[p]
+    np.testing.assert_allclose(m, st["exp_avg"].numpy(), rtol=1e-13)
+    np.testing.assert_allclose(v, st["exp_avg_sq"].numpy(), rtol=1e-13)
+
+
+def test_lr_rebound_scale_ramp():
+    n = 8
+    s = [orc.lr_rebound_scale(i, n) for i in range(12)]
+    assert s[0] == pytest.approx(1.0 / n) and s[0] < 0.2          # starts near zero
+    assert all(b > a for a, b in zip(s[:n - 1], s[1:n]))           # climbs
+    assert np.allclose(np.diff(s[:n]), 1.0 / n)                    # linearly
+    assert s[n - 1] == 1.0 and all(x == 1.0 for x in s[n:])        # back at the scheduled rate
+    assert orc.lr_rebound_scale(0, 0) == 1.0
+
+
+def test_group_step_freezes_the_other_factor_and_descends():
+    rng = np.random.default_rng(2)
+    M, m, n, k = 40, 12, 9, 4
+    X = rng.standard_normal((M, n)); A = rng.standard_normal((m, k)); B = rng.standard_normal((k, n))
+    Yt = rng.standard_normal((M, m))
+    loss = lambda A_, B_: 0.5 * np.sum((orc.lr_linear_fwd(X, A_, B_)[0] - Yt) ** 2)
+    for target in ("A", "B"):
+        Y, _ = orc.lr_linear_fwd(X, A, B)
+        dY = Y - Yt
+        tr = A if target == "A" else B
+        out = orc.group_train_step(X, dY, A, B, target, (0 * tr, 0 * tr), 1, 1e-3, weight_decay=0.0)
+        frozen_new, frozen_old = (out["B"], B) if target == "A" else (out["A"], A)
+        assert np.array_equal(frozen_new, frozen_old)
+        moved = out["A"] - A if target == "A" else out["B"] - B
+        # first Adam step: every entry moves by lr against the sign of its gradient
+        np.testing.assert_allclose(moved, -1e-3 * np.sign(out["grad"]), rtol=1e-6)
+        assert loss(out["A"], out["B"]) < loss(A, B)
+        # the gradient is the one of the full backward
+        ref = orc.lr_linear_bwd(dY, X, A, B)
+        assert np.array_equal(out["grad"], ref[1] if target == "A" else ref[2])
+        assert np.array_equal(out["dX"], ref[0])
+
+
+def test_reconstruct_is_the_dense_weight_of_the_layer():
+    rng = np.random.default_rng(3)
+    A = rng.standard_normal((6, 3)); B = rng.standard_normal((3, 5)); X = rng.standard_normal((4, 5))
+    W = orc.reconstruct(A, B)
+    np.testing.assert_allclose(X @ W.T, orc.lr_linear_fwd(X, A, B)[0], rtol=1e-13, atol=1e-13)
+    assert np.linalg.matrix_rank(W) == 3
