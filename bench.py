@@ -40,6 +40,7 @@ def main():
     ap.add_argument("--pmc-copy", action="store_true",
                     help="also run one plain 256 MiB device copy: the reference dispatch that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command")
+    ap.add_argument("--no-group", action="store_true", help="skip the group-training step timings")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time every config-3 / config-4 case (extra key `cases`)")
     args = ap.parse_args()
@@ -245,6 +246,57 @@ def main():
                                "ranks_min_max": [min(int(x["k"].item()) for x in o), max(int(x["k"].item()) for x in o)],
                                "note": "48 dense ViT-B/16 weights with the config-5 spectrum in one batched call"}
         del dense, fl, o
+        torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------------ group-training step (extra key)
+    # A-groups skip dB, B-groups skip dA (5/6 of the full step's flops); then one AdamW launch over
+    # the trained factors of all 48 ViT-B/16 layers at rank 192 (fp32 state, bf16 copy written).
+    if not args.no_group:
+        def step_A():
+            step.fwd()
+            abt.lr_linear_bwd(step.dY, step.X, step.T, step.A, step.B, dX=step.dX, dA=step.dA, need_dB=False,
+                              workspace=step.ws)
+
+        def step_B():
+            step.fwd()
+            abt.lr_linear_bwd(step.dY, step.X, step.T, step.A, step.B, dX=step.dX, dB=step.dB, need_dA=False,
+                              workspace=step.ws)
+
+        ga_ms = event_ms(step_A, min(args.steps, 100))[0]
+        gb_ms = event_ms(step_B, min(args.steps, 100))[0]
+        tensors, elems = [], 0
+        for blk in range(gen.VIT_B16_BLOCKS):
+            for li, (name, m, n) in enumerate(gen.VIT_B16_LINEARS):
+                cnt = m * 192 if (blk + li) % 2 == 0 else 192 * n
+                elems += cnt
+                tensors.append(dict(param=torch.zeros(cnt, device=dev), grad=torch.full((cnt,), 1e-3, device=dev),
+                                    exp_avg=torch.zeros(cnt, device=dev), exp_avg_sq=torch.zeros(cnt, device=dev),
+                                    param_bf16=torch.empty(cnt, dtype=bf16, device=dev)))
+        counter = {"t": 0}
+        plan = abt.AdamwPlan(tensors)            # the table is marshalled once, as a training loop would
+
+        def adamw_once():
+            counter["t"] += 1
+            abt.ab_adamw_step(plan, step=counter["t"], lr=1e-3, lr_scale=1.0)
+
+        ad_ms = event_ms(adamw_once, min(args.steps, 100))[0]
+        ad_bytes = 30.0 * elems
+        # the same volume through a plain device copy (half read, half written): what this box
+        # sustains for a mixed read/write stream
+        src = torch.empty(int(ad_bytes) // 2, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        cp_ms = event_ms(lambda: dst.copy_(src), min(args.steps, 100))[0]
+        del src, dst
+        flops56 = step.flops * 5.0 / 6.0
+        out["group_step"] = {"workload": "config 2 layer, one factor frozen; AdamW over the trained factors of 48 layers",
+                             "A_group_ms": round(ga_ms, 4), "B_group_ms": round(gb_ms, 4),
+                             "A_group_tflops": round(flops56 / (ga_ms * 1e-3) / 1e12, 1),
+                             "B_group_tflops": round(flops56 / (gb_ms * 1e-3) / 1e12, 1),
+                             "adamw_ms": round(ad_ms, 4), "adamw_elements": elems,
+                             "adamw_GBps": round(ad_bytes / (ad_ms * 1e-3) / 1e9, 1),
+                             "adamw_hbm_frac": round(ad_bytes / (ad_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                             "device_copy_same_bytes_GBps": round(ad_bytes / (cp_ms * 1e-3) / 1e9, 1)}
+        del tensors, plan
         torch.cuda.empty_cache()
 
     # ------------------------------------------------------------------ CPU oracle beside it (reported, not a target)

@@ -196,6 +196,54 @@ int ab_factorize_batched(const abt_factorize_desc* layers, int L,
 
 size_t ab_factorize_batched_workspace_bytes(const abt_factorize_desc* layers, int L);
 
+/* -------------------------------------------------------------------------------------
+ * Group-training step (group-training phase of Algorithm 1; Sec. "Learning rate rebound").
+ * A group trains one factor of every layer and keeps the other frozen: call lr_linear_bwd
+ * with the frozen factor's gradient pointer NULL (its product is skipped), then ab_adamw_step
+ * on the trained factors of all layers at once.
+ *
+ * ab_adamw_step: one step of Adam with decoupled weight decay (the optimiser of the paper's
+ * experiments) on n tensors in one launch per 48 tensors.  For every element, in fp32:
+ *     m' = beta1 m + (1 - beta1) g            v' = beta2 v + (1 - beta2) g^2
+ *     u  = (m' / (1 - beta1^step)) / (sqrt(v' / (1 - beta2^step)) + eps)
+ *     theta' = theta - lr * lr_scale * (u + weight_decay * theta)
+ * lr_scale is the rebound factor of the step (ab_lr_rebound_scale, or 1).  step >= 1 is the
+ * 1-based count of optimiser steps the state has seen including this one.  The
+ * hyper-parameters are doubles: 1 - beta, the two bias corrections and lr * lr_scale are
+ * evaluated on the host in double precision and each rounded once to fp32 for the kernel.
+ * `tensors` is a HOST array read before the call returns.  Per tensor: param, exp_avg,
+ * exp_avg_sq (fp32, DEVICE, updated in place), grad (fp32, DEVICE, read only), param_bf16
+ * (DEVICE, may be NULL: if given, receives theta' rounded to bf16, the copy the bf16 layer
+ * kernels read), count elements (>= 0; 0 skips the tensor).  All pointers 16-byte aligned;
+ * tensors must not overlap.  The result is deterministic.  No workspace, no allocation.
+ * Errors: ABT_EINVAL (n < 0, NULL table or pointer, step < 1, betas outside [0, 1),
+ * eps < 0 or any hyper-parameter not finite), ABT_ESHAPE (count < 0), ABT_EALIGN.
+ * ------------------------------------------------------------------------------------- */
+typedef struct {
+    float* param;
+    const float* grad;
+    float* exp_avg;
+    float* exp_avg_sq;
+    void* param_bf16;             /* may be NULL */
+    int64_t count;
+} abt_adamw_tensor;
+
+int ab_adamw_step(const abt_adamw_tensor* tensors, int n, int64_t step,
+                  double lr, double lr_scale, double beta1, double beta2, double eps,
+                  double weight_decay, void* stream);
+
+/* Factor applied to the scheduled learning rate i steps (0-based) after the parameters changed
+ * shape (Sec. "Learning rate rebound": the rate drops to near zero and climbs back over
+ * rebound_steps steps; the climb is taken as linear): min(1, (i + 1) / rebound_steps);
+ * 1 when rebound_steps <= 0 or i < 0 is not meaningful (i < 0 is treated as 0).  Host only. */
+double ab_lr_rebound_scale(int64_t i, int64_t rebound_steps);
+
+/* W [m, n] = A [m, k] . B [k, n] (fp32, DEVICE, row-major): the hand-off from the averaged
+ * factors back to the full-rank weight at the end of a low-rank phase (Algorithm 1).
+ * m, n, k >= 1.  Errors: ABT_EINVAL, ABT_ESHAPE, ABT_EALIGN, ABT_EHIP. */
+int ab_reconstruct(const float* A, const float* B, float* W,
+                   int64_t m, int64_t n, int64_t k, void* stream);
+
 /* Sweep cap of the Jacobi SVD (default 30, clamped to [1, 64]; sweeps stop as soon as every layer
  * has converged: 8-9 for the 384-wide cores of config 5, about 15 for dense 768-wide weights);
  * returns the previous value. */

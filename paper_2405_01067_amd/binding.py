@@ -23,6 +23,7 @@ EXPORTS = (
     "ab_merge_batched", "ab_merge_batched_workspace_bytes", "ab_merge_info",
     "ab_factorize", "ab_factorize_workspace_bytes",
     "ab_factorize_batched", "ab_factorize_batched_workspace_bytes",
+    "ab_adamw_step", "ab_lr_rebound_scale", "ab_reconstruct",
 )
 
 
@@ -35,6 +36,11 @@ class FactorizeDesc(ctypes.Structure):
                 ("tau", ctypes.c_float), ("k_fixed", ctypes.c_int64),
                 ("A_out", ctypes.c_void_p), ("B_out", ctypes.c_void_p), ("S_out", ctypes.c_void_p),
                 ("k_out", ctypes.c_void_p), ("k_cap", ctypes.c_int64)]
+
+
+class AdamwTensor(ctypes.Structure):
+    _fields_ = [("param", ctypes.c_void_p), ("grad", ctypes.c_void_p), ("exp_avg", ctypes.c_void_p),
+                ("exp_avg_sq", ctypes.c_void_p), ("param_bf16", ctypes.c_void_p), ("count", ctypes.c_int64)]
 
 
 class MergeDesc(ctypes.Structure):
@@ -98,6 +104,13 @@ def load():
     lib.ab_factorize_batched.argtypes = [ctypes.POINTER(FactorizeDesc), ci, vp, sz, vp]
     lib.ab_factorize_batched_workspace_bytes.restype = sz
     lib.ab_factorize_batched_workspace_bytes.argtypes = [ctypes.POINTER(FactorizeDesc), ci]
+    lib.ab_adamw_step.restype = ci
+    cd = ctypes.c_double
+    lib.ab_adamw_step.argtypes = [ctypes.POINTER(AdamwTensor), ci, i64, cd, cd, cd, cd, cd, cd, vp]
+    lib.ab_lr_rebound_scale.restype = ctypes.c_double
+    lib.ab_lr_rebound_scale.argtypes = [i64, i64]
+    lib.ab_reconstruct.restype = ci
+    lib.ab_reconstruct.argtypes = [vp, vp, vp, i64, i64, i64, vp]
     _lib = lib
     return lib
 
@@ -337,6 +350,66 @@ def ab_factorize_batched(layers: List[dict], workspace=None, check_converged: bo
         if check_converged:
             merge_info(workspace, i)
     return outs
+
+
+def lr_rebound_scale(i: int, rebound_steps: int) -> float:
+    """Learning-rate factor i steps (0-based) after a change of the parameters' shape."""
+    return float(load().ab_lr_rebound_scale(int(i), int(rebound_steps)))
+
+
+class AdamwPlan:
+    """The tensor table of ab_adamw_step, marshalled once: a training loop updates the same
+    tensors every step, and building the table costs more host time than the kernel runs.
+    Holds references to the tensors so that their memory stays alive."""
+
+    def __init__(self, tensors: Sequence[dict]):
+        torch = _torch()
+        self.n = len(tensors)
+        self.table = (AdamwTensor * max(self.n, 1))()
+        self.tensors = list(tensors)
+        for i, t in enumerate(tensors):
+            p = _dev_tensor(t["param"], "param")
+            cnt = p.numel()
+            for key in ("param", "grad", "exp_avg", "exp_avg_sq"):
+                x = _dev_tensor(t[key], key)
+                if x.dtype != torch.float32 or x.numel() != cnt:
+                    raise AbtError(f"{key} must be fp32 with as many elements as param")
+            pb = t.get("param_bf16")
+            if pb is not None:
+                _dev_tensor(pb, "param_bf16")
+                if pb.dtype != torch.bfloat16 or pb.numel() != cnt:
+                    raise AbtError("param_bf16 must be bf16 with as many elements as param")
+            e = self.table[i]
+            e.param = _ptr(t["param"]); e.grad = _ptr(t["grad"]); e.exp_avg = _ptr(t["exp_avg"])
+            e.exp_avg_sq = _ptr(t["exp_avg_sq"]); e.param_bf16 = _ptr(pb); e.count = cnt
+
+
+def ab_adamw_step(tensors, step: int, lr: float, lr_scale: float = 1.0, beta1: float = 0.9,
+                  beta2: float = 0.999, eps: float = 1e-8, weight_decay: float = 0.01):
+    """One AdamW step, in place.  `tensors` is an AdamwPlan, or a list of dicts with fp32 GPU
+    tensors param, grad, exp_avg, exp_avg_sq of equal element count and optionally param_bf16
+    (bf16, same count) that receives the rounded new parameter."""
+    plan = tensors if isinstance(tensors, AdamwPlan) else AdamwPlan(tensors)
+    _check(load().ab_adamw_step(plan.table, plan.n, int(step), float(lr), float(lr_scale), float(beta1),
+                                float(beta2), float(eps), float(weight_decay), _stream()), "ab_adamw_step")
+
+
+def ab_reconstruct(A, B, W=None):
+    """W [m, n] = A [m, k] . B [k, n] for fp32 GPU tensors."""
+    torch = _torch()
+    _dev_tensor(A, "A"); _dev_tensor(B, "B")
+    if A.dtype != torch.float32 or B.dtype != torch.float32 or A.dim() != 2 or B.dim() != 2 or A.shape[1] != B.shape[0]:
+        raise AbtError("ab_reconstruct: A [m, k] and B [k, n] must be fp32 matrices")
+    m, k = A.shape
+    n = B.shape[1]
+    if W is None:
+        W = torch.empty((m, n), dtype=torch.float32, device=A.device)
+    else:
+        _dev_tensor(W, "W")
+        if W.dtype != torch.float32 or tuple(W.shape) != (m, n):
+            raise AbtError("ab_reconstruct: W must be fp32 [m, n]")
+    _check(load().ab_reconstruct(_ptr(A), _ptr(B), _ptr(W), m, n, k, _stream()), "ab_reconstruct")
+    return W
 
 
 def merge_info(workspace, layer: int = 0):

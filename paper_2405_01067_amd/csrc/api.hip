@@ -1,5 +1,6 @@
 // C ABI of the library: argument validation, workspace carving and the launch sequences.
 // Every operation is documented in include/abtrain.h.
+#include <cmath>
 #include <vector>
 
 #include "common.h"
@@ -98,6 +99,55 @@ const char* abt_status_string(int status) {
         case ABT_EHIP: return "ABT_EHIP: HIP runtime error";
         default: return "unknown abt_status";
     }
+}
+
+int ab_adamw_step(const abt_adamw_tensor* tensors, int n, int64_t step,
+                  double lr, double lr_scale, double beta1, double beta2, double eps,
+                  double weight_decay, void* stream) {
+    if (n < 0 || (n > 0 && !tensors) || step < 1) return ABT_EINVAL;
+    if (!std::isfinite(lr) || !std::isfinite(lr_scale) || !std::isfinite(eps) || !std::isfinite(weight_decay) ||
+        !(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0) || eps < 0.0)
+        return ABT_EINVAL;
+    std::vector<AdamwTensor> v;
+    v.reserve((size_t)n);
+    for (int i = 0; i < n; ++i) {
+        const abt_adamw_tensor& t = tensors[i];
+        if (t.count < 0) return ABT_ESHAPE;
+        if (t.count == 0) continue;
+        if (!t.param || !t.grad || !t.exp_avg || !t.exp_avg_sq) return ABT_EINVAL;
+        if (!aligned(t.param, 16) || !aligned(t.grad, 16) || !aligned(t.exp_avg, 16) ||
+            !aligned(t.exp_avg_sq, 16) || !aligned(t.param_bf16, 16))
+            return ABT_EALIGN;
+        v.push_back(AdamwTensor{t.param, t.grad, t.exp_avg, t.exp_avg_sq, (uint16_t*)t.param_bf16, t.count});
+    }
+    if (v.empty()) return ABT_OK;
+    AdamwHyper h;
+    const double b1 = beta1, b2 = beta2;
+    h.beta1 = (float)beta1; h.beta2 = (float)beta2;
+    h.one_minus_beta1 = (float)(1.0 - b1); h.one_minus_beta2 = (float)(1.0 - b2);
+    // 1 - beta^step, without cancellation when beta^step is close to 1
+    const double bc1 = b1 > 0.0 ? -std::expm1((double)step * std::log(b1)) : 1.0;
+    const double bc2 = b2 > 0.0 ? -std::expm1((double)step * std::log(b2)) : 1.0;
+    h.inv_bc1 = (float)(1.0 / bc1);
+    h.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
+    h.eps = (float)eps; h.eta = (float)(lr * lr_scale); h.weight_decay = (float)weight_decay;
+    return launch_adamw(v.data(), (int)v.size(), h, (hipStream_t)stream) == hipSuccess ? ABT_OK : ABT_EHIP;
+}
+
+double ab_lr_rebound_scale(int64_t i, int64_t rebound_steps) {
+    if (rebound_steps <= 0) return 1.0;
+    if (i < 0) i = 0;
+    if (i + 1 >= rebound_steps) return 1.0;
+    return (double)(i + 1) / (double)rebound_steps;
+}
+
+int ab_reconstruct(const float* A, const float* B, float* W,
+                   int64_t m, int64_t n, int64_t k, void* stream) {
+    if (!A || !B || !W) return ABT_EINVAL;
+    if (m < 1 || n < 1 || k < 1 || m > INT32_MAX || n > INT32_MAX || k > INT32_MAX) return ABT_ESHAPE;
+    if (!aligned(A, 16) || !aligned(B, 16) || !aligned(W, 16)) return ABT_EALIGN;
+    return launch_gemm_f32_one(gemm(A, B, W, m, n, k, k, n, n, 0, 0, 0), (hipStream_t)stream) == hipSuccess
+               ? ABT_OK : ABT_EHIP;
 }
 
 int abt_set_jacobi_max_sweeps(int max_sweeps) {

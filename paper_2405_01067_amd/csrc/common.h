@@ -105,4 +105,18 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
 hipError_t merge_read_info(const void* workspace, int layer, int32_t out[4], hipStream_t s);
 hipError_t launch_identity_f32(float* dst, int K, hipStream_t s);   // dst[K, K] = I
 
+// ------------------------------------------------------------------ optimiser step
+// Adam with decoupled weight decay on up to any number of tensors (kAdamwMaxTensors per launch).
+constexpr int kAdamwMaxTensors = 48;
+struct AdamwTensor {
+    float* param; const float* grad; float* exp_avg; float* exp_avg_sq; uint16_t* param_bf16; int64_t count;
+};
+struct AdamwHyper {   // everything the kernel needs, prepared on the host in double precision
+    float beta1, beta2, one_minus_beta1, one_minus_beta2;
+    float inv_bc1;        // 1 / (1 - beta1^step)
+    float inv_sqrt_bc2;   // 1 / sqrt(1 - beta2^step)
+    float eps, eta, weight_decay;   // eta = lr * lr_scale
+};
+hipError_t launch_adamw(const AdamwTensor* tensors, int n, const AdamwHyper& h, hipStream_t s);
+
 }  // namespace abt

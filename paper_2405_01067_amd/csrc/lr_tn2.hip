@@ -279,9 +279,13 @@ int tn2_choose_splits(int64_t M, int total_tiles) {
     int64_t want = 256 / total_tiles;
     int64_t max_by_rows = M / (8 * 64);
     if (max_by_rows < 1) max_by_rows = 1;
-    if (want > max_by_rows) want = max_by_rows;
-    if (want < 1) want = 1;
     if (want > 64) want = 64;
+    // split s runs on XCD s % 8: a multiple of eight splits gives every XCD the same number of
+    // work-groups (ten splits would give two XCDs twice the work of the others)
+    if (want >= 8) want = want / 8 * 8;
+    else want = 8;
+    if (want > max_by_rows) want = max_by_rows >= 8 ? max_by_rows / 8 * 8 : max_by_rows;
+    if (want < 1) want = 1;
     return (int)want;
 }
 

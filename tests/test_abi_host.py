@@ -23,7 +23,7 @@ def lib():
 def declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"^\s*(?:const\s+char\s*\*|int|size_t)\s+(\w+)\s*\(", text, flags=re.M)
+    names = re.findall(r"^\s*(?:const\s+char\s*\*|int|size_t|double)\s+(\w+)\s*\(", text, flags=re.M)
     return sorted(set(names))
 
 
@@ -130,6 +130,49 @@ def test_factorize_validation_without_device(lib):
     assert f(p, 256, 256, 0.1, 0, p, p, p, p, 256, p, 1024, null) == -4
     assert f(p, 256, 256, 1.5, 0, p, p, p, p, 256, p, big, null) == -1           # tau out of range
     assert f(p, 256, 256, 0.1, 0, null, p, p, p, 256, p, big, null) == -1
+
+
+def test_group_step_validation_and_rebound_factor_without_device(lib):
+    from oracle import ab_oracle as orc
+    buf = ctypes.create_string_buffer(4096 + 256)
+    base = (ctypes.addressof(buf) + 255) // 256 * 256          # fake, aligned, never dereferenced
+    p, null = ctypes.c_void_p(base), ctypes.c_void_p(0)
+    step = lib.ab_adamw_step
+    t = (abt.AdamwTensor * 2)()
+    for e in t:
+        e.param = e.grad = e.exp_avg = e.exp_avg_sq = base
+        e.count = 100
+    ok = (1e-3, 1.0, 0.9, 0.999, 1e-8, 0.01)
+    assert step(t, 0, 1, *ok, null) == 0                        # nothing to do
+    t[0].count = t[1].count = 0
+    assert step(t, 2, 1, *ok, null) == 0                        # empty tensors are skipped
+    t[0].count = 100
+    assert step(t, 2, 0, *ok, null) == -1                       # step counts from 1
+    assert step(None, 2, 1, *ok, null) == -1
+    assert step(t, -1, 1, *ok, null) == -1
+    assert step(t, 2, 1, 1e-3, 1.0, 1.0, 0.999, 1e-8, 0.01, null) == -1      # beta1 = 1
+    assert step(t, 2, 1, 1e-3, 1.0, 0.9, -0.1, 1e-8, 0.01, null) == -1
+    assert step(t, 2, 1, 1e-3, 1.0, 0.9, 0.999, -1.0, 0.01, null) == -1
+    assert step(t, 2, 1, float("nan"), 1.0, 0.9, 0.999, 1e-8, 0.01, null) == -1
+    t[0].count = -5
+    assert step(t, 2, 1, *ok, null) == -2
+    t[0].count = 100
+    t[0].grad = 0
+    assert step(t, 2, 1, *ok, null) == -1
+    t[0].grad = base + 4
+    assert step(t, 2, 1, *ok, null) == -3
+    t[0].grad = base
+    t[0].param_bf16 = base + 2
+    assert step(t, 2, 1, *ok, null) == -3
+    # the learning-rate factor is host arithmetic: the library's and the oracle's must agree
+    for n in (0, 1, 3, 8, 1000):
+        for i in range(0, 12):
+            assert lib.ab_lr_rebound_scale(i, n) == pytest.approx(orc.lr_rebound_scale(i, n), rel=1e-15)
+    assert lib.ab_lr_rebound_scale(-3, 8) == pytest.approx(1 / 8)
+    r = lib.ab_reconstruct
+    assert r(null, p, p, 8, 8, 4, null) == -1
+    assert r(p, p, p, 0, 8, 4, null) == -2
+    assert r(p, p, ctypes.c_void_p(base + 4), 8, 8, 4, null) == -3
 
 
 def test_binding_refuses_cpu_tensors(lib):
