@@ -91,6 +91,52 @@ def test_bf16_relu_inputs_half_zero():
     check_full(c, torch.bfloat16, TOL_BF16)
 
 
+# ------------------------------------------------------------------ largest sizes
+
+@pytest.mark.parametrize("m,n", [(1 << 20, 64), (64, 1 << 20)], ids=["m=2^20", "n=2^20"])
+def test_bf16_widest_factor_dimension(m, n):
+    # the documented limit of m and n: row pitches of 2 MiB, 16384 contraction slabs or output tiles
+    c = gen.lr_case(M=70, m=m, n=n, r=32, seed=4242)
+    check_full(c, torch.bfloat16, TOL_BF16)
+
+
+def test_bf16_row_offsets_beyond_4_GiB():
+    # dY and Y of 5.2 GB each: byte offsets of rows pass 2^32.  The inputs are a seeded block of
+    # 40000 rows repeated 32 times plus 37 more rows (the period is not a power of two, so a row
+    # offset that wrapped at 2^32 bytes = 2^20 rows would land on different data); every output
+    # row must then repeat with the same period, the first period is compared with the oracle
+    # in full, and dA, dB are 32 times the block's plus those of the 37 extra rows.
+    blk, reps, extra, m, n, r = 40000, 32, 37, 2048, 64, 64
+    c = gen.lr_case(M=blk, m=m, n=n, r=r, seed=808)
+    M = blk * reps + extra
+    Xb, dYb = dev(c["X"], torch.bfloat16), dev(c["dY"], torch.bfloat16)
+    X = torch.cat([Xb.repeat(reps, 1), Xb[:extra]])
+    dY = torch.cat([dYb.repeat(reps, 1), dYb[:extra]])
+    assert dY.numel() * 2 > (1 << 32) and tuple(dY.shape) == (M, m)
+    A, B = dev(c["A"], torch.bfloat16), dev(c["B"], torch.bfloat16)
+    Y, T = abt.lr_linear_fwd(X, A, B, save_T=True)
+    dX, dA, dB = abt.lr_linear_bwd(dY, X, T, A, B)
+    torch.cuda.synchronize()
+    for out in (Y, T):
+        first = out[:blk]
+        for k in range(1, reps):
+            assert torch.equal(out[k * blk:(k + 1) * blk], first), k
+        assert torch.equal(out[reps * blk:], first[:extra])
+    # dX: work-groups start the 32 contraction slabs of dT = dY A at different slabs, so the fp32
+    # sums of two periods are taken in different orders and a few bf16 roundings fall the other way
+    first = dX[:blk].float()
+    for k in range(1, reps):
+        d = (dX[k * blk:(k + 1) * blk].float() - first).norm() / first.norm()
+        assert float(d) < 1e-3, (k, float(d))
+    assert float((dX[reps * blk:].float() - first[:extra]).norm() / first[:extra].norm()) < 1e-3
+    Yo, To = orc.lr_linear_fwd(c["X"], c["A"], c["B"])
+    dXo, dAo, dBo, _ = orc.lr_linear_bwd(c["dY"], c["X"], c["A"], c["B"])
+    _, dAe, dBe, _ = orc.lr_linear_bwd(c["dY"][:extra], c["X"][:extra], c["A"], c["B"])
+    errs = {"Y": rel(host(Y[:blk]), Yo), "T": rel(host(T[:blk]), To), "dX": rel(host(dX[:blk]), dXo),
+            "dA": rel(host(dA), reps * dAo + dAe), "dB": rel(host(dB), reps * dBo + dBe)}
+    assert all(e < TOL_BF16 for e in errs.values()), errs
+
+
 # ------------------------------------------------------------------ options
 
 def test_bwd_skips_accumulate_recompute_and_determinism():
