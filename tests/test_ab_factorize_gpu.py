@@ -89,6 +89,15 @@ def test_vit_attention_projection_shape():
     check(W32, out, tau=tau, expect_k=192)
 
 
+def test_widest_core_the_boundary_admits():
+    # min(m, n) = 2048, the documented limit, with n > m (the I W route): blocks of 4 columns,
+    # 511 cross rounds per sweep in the general Jacobi kernels
+    W32, sigma = planted(2048, 2304, 300, seed=21)
+    tau = float(math.sqrt(sigma[299] * sigma[300]) / sigma[0])
+    out = abt.ab_factorize(dev(W32), tau=tau, k_cap=512)
+    check(W32, out, tau=tau, expect_k=300)
+
+
 def test_rank_deficient_weight_and_k_cap():
     # rank 48 exactly (in fp64; fp32 rounding leaves a tail ~1e-8): tau picks the 48, k_cap clips
     rng = np.random.default_rng(11)
