@@ -201,3 +201,58 @@ def group_train_step(X, dY, A, B, target, state, t, lr, lr_scale=1.0, **hyper):
 def reconstruct(A, B):
     """W <- A B, the hand-off from the factors back to the full-rank weight (Algorithm 1)."""
     return _f64(A) @ _f64(B)
+
+
+# --------------------------------------------------------------------------------------
+# convolutional layer carried as factors (Sec. "Methodology": a weight with more than two
+# dimensions is flattened over its trailing dimensions to give the matrix W of Eq. 3)
+# --------------------------------------------------------------------------------------
+# A convolution weight [m, C, kh, kw] flattened to W [m, kh kw C] factors as W = A B with
+# A [m, k] and B [k, kh kw C]: B is a kh x kw convolution to k channels, A a 1 x 1 convolution.
+# Layout here: activations N x H x W x C (channels last); the flattened axis is ordered tap-major,
+# column (ky kw + kx) C + c.  (The order of the flattened axis only permutes the columns of W
+# and of B; it does not change the factorisation.)  Stride 1, zero padding (kh-1)/2, (kw-1)/2
+# ("same"), kh and kw odd: the 3x3 and 1x1 convolutions of ResNet-50's bottleneck blocks.
+
+def conv_patches(act, kh, kw):
+    """Patch matrix of a channels-last activation: Xcol [N H W, kh kw C] with
+    Xcol[(b, y, x), (ky, kx, c)] = act[b, y + ky - ph, x + kx - pw, c], zero outside the image."""
+    act = _f64(act)
+    N, H, W, C = act.shape
+    assert kh % 2 == 1 and kw % 2 == 1
+    ph, pw = kh // 2, kw // 2
+    padded = np.zeros((N, H + 2 * ph, W + 2 * pw, C), dtype=_F64)
+    padded[:, ph:ph + H, pw:pw + W, :] = act
+    cols = np.empty((N, H, W, kh * kw, C), dtype=_F64)
+    for ky in range(kh):
+        for kx in range(kw):
+            cols[:, :, :, ky * kw + kx, :] = padded[:, ky:ky + H, kx:kx + W, :]
+    return cols.reshape(N * H * W, kh * kw * C)
+
+
+def conv_patches_adjoint(G, shape, kh, kw):
+    """Adjoint of conv_patches: sums every entry of G [N H W, kh kw C] back onto the activation
+    element it was read from.  Returns [N, H, W, C]."""
+    N, H, W, C = shape
+    G = _f64(G).reshape(N, H, W, kh * kw, C)
+    ph, pw = kh // 2, kw // 2
+    padded = np.zeros((N, H + 2 * ph, W + 2 * pw, C), dtype=_F64)
+    for ky in range(kh):
+        for kx in range(kw):
+            padded[:, ky:ky + H, kx:kx + W, :] += G[:, :, :, ky * kw + kx, :]
+    return padded[:, ph:ph + H, pw:pw + W, :]
+
+
+def lr_conv_fwd(act, A, B, kh, kw):
+    """Forward of a convolution whose flattened weight is W = A B: the factored linear layer
+    applied to the patch matrix.  Returns (Y [N H W, m], T [N H W, k])."""
+    return lr_linear_fwd(conv_patches(act, kh, kw), A, B)
+
+
+def lr_conv_bwd(dY, act, A, B, kh, kw):
+    """Backward of the same layer: the factored layer's gradients on the patch matrix, and the
+    activation gradient as the adjoint of the patch extraction applied to dXcol = dT B.
+    Returns (dAct [N, H, W, C], dA, dB, dT)."""
+    act = _f64(act)
+    dXcol, dA, dB, dT = lr_linear_bwd(dY, conv_patches(act, kh, kw), A, B)
+    return conv_patches_adjoint(dXcol, act.shape, kh, kw), dA, dB, dT

@@ -178,6 +178,32 @@ def config4_cases():
     return [(name, M, m, n, r, 3 + 100 + i) for i, (name, M, n, m, r) in enumerate(RESNET50_CONVS)]
 
 
+def conv_case(N: int, H: int, W: int, C: int, m: int, r: int, kh: int, kw: int, seed: int,
+              relu_act: bool = True, dy_std: float = 1e-2):
+    """One factored convolution's training-step inputs, channels last, all bf16-representable:
+    act N x H x W x C ~ max(0, N(0,1)) (post-ReLU feature map; relu_act=False keeps the Gaussian),
+    dY (N H W) x m ~ N(0, dy_std^2), A m x r ~ N(0, 1/r), B r x (kh kw C) ~ N(0, 1/(kh kw C)),
+    B's columns ordered tap-major: (ky kw + kx) C + c."""
+    rng = np.random.default_rng(seed)
+    n = kh * kw * C
+    a = gaussian(rng, (m, r), std=r ** -0.5)
+    b = gaussian(rng, (r, n), std=n ** -0.5)
+    act = gaussian(rng, (N, H, W, C))
+    if relu_act:
+        np.maximum(act, 0.0, out=act)
+    dy = gaussian(rng, (N * H * W, m), std=dy_std)
+    a, b, act, dy = (round_to_bf16(t) for t in (a, b, act, dy))
+    return {"act": act, "dY": dy, "A": a, "B": b, "N": N, "H": H, "W": W, "C": C, "m": m, "r": r,
+            "kh": kh, "kw": kw}
+
+
+# ResNet-50 3x3 convolutions of config 4 in their native form: (name, N, H, W, C, m, r)
+RESNET50_CONVS_NATIVE = (
+    ("conv3x3_256_14", 256, 14, 14, 256, 256, 64),
+    ("conv3x3_512_7", 256, 7, 7, 512, 512, 128),
+)
+
+
 def merge_layer(m: int, n: int, seed: int, k_in: int = CFG5_K_IN, g: int = CFG5_G,
                 gap_at: int = CFG5_GAP_AT, noise_std: float = CFG5_NOISE_STD):
     """One layer of config 5: planted spectrum sigma_i = i^-0.8 with a 10x drop after

@@ -444,3 +444,70 @@ def test_reconstruct_is_the_dense_weight_of_the_layer():
     W = orc.reconstruct(A, B)
     np.testing.assert_allclose(X @ W.T, orc.lr_linear_fwd(X, A, B)[0], rtol=1e-13, atol=1e-13)
     assert np.linalg.matrix_rank(W) == 3
+
+
+# ---------------------------------------------------------------------------------------------
+# convolutional layer carried as factors
+# ---------------------------------------------------------------------------------------------
+
+def test_conv_patches_hand_example_and_shift():
+    # one 3 x 3 single-channel image, 3 x 3 window: the patch of the centre pixel is the image
+    # itself, row-major; the patch of the top-left pixel has the image's top-left 2 x 2 block in
+    # its bottom-right corner and zeros elsewhere
+    img = np.arange(1.0, 10.0).reshape(1, 3, 3, 1)
+    P = orc.conv_patches(img, 3, 3)
+    assert P.shape == (9, 9)
+    np.testing.assert_array_equal(P[4], np.arange(1.0, 10.0))
+    np.testing.assert_array_equal(P[0], [0, 0, 0, 0, 1, 2, 0, 4, 5])
+    np.testing.assert_array_equal(P[8], [5, 6, 0, 8, 9, 0, 0, 0, 0])
+    # a weight with a single one at tap (ky, kx) = (0, 2) shifts the image down-left by (1, -1)
+    w = np.zeros((1, 9)); w[0, 0 * 3 + 2] = 1.0
+    out = (P @ w.T).reshape(3, 3)
+    np.testing.assert_array_equal(out, [[0, 0, 0], [2, 3, 0], [5, 6, 0]])
+
+
+def test_conv_fwd_against_library_correlation():
+    sig = pytest.importorskip("scipy.signal")
+    rng = np.random.default_rng(8)
+    N, H, W, C, m, k = 2, 5, 6, 3, 4, 2
+    for kh, kw in ((3, 3), (1, 1), (3, 1), (5, 3)):
+        act = rng.standard_normal((N, H, W, C))
+        A = rng.standard_normal((m, k)); B = rng.standard_normal((k, kh * kw * C))
+        Y, T = orc.lr_conv_fwd(act, A, B, kh, kw)
+        Wd = (A @ B).reshape(m, kh, kw, C)                      # dense weight, tap-major flattening
+        for b in range(N):
+            for o in range(m):
+                ref = sum(sig.correlate2d(act[b, :, :, c], Wd[o, :, :, c], mode="same") for c in range(C))
+                np.testing.assert_allclose(Y.reshape(N, H, W, m)[b, :, :, o], ref, rtol=1e-11, atol=1e-11)
+    # a 1 x 1 window is the plain factored linear layer on the pixels
+    act = rng.standard_normal((N, H, W, C)); A = rng.standard_normal((m, k)); B = rng.standard_normal((k, C))
+    np.testing.assert_array_equal(orc.lr_conv_fwd(act, A, B, 1, 1)[0],
+                                  orc.lr_linear_fwd(act.reshape(-1, C), A, B)[0])
+
+
+def test_conv_patches_adjoint_identity():
+    rng = np.random.default_rng(9)
+    shape = (2, 4, 5, 3)
+    for kh, kw in ((3, 3), (1, 3), (5, 5)):
+        act = rng.standard_normal(shape)
+        G = rng.standard_normal((2 * 4 * 5, kh * kw * 3))
+        lhs = np.sum(orc.conv_patches(act, kh, kw) * G)
+        rhs = np.sum(act * orc.conv_patches_adjoint(G, shape, kh, kw))
+        assert lhs == pytest.approx(rhs, rel=1e-12)
+
+
+def test_conv_bwd_matches_central_finite_differences():
+    rng = np.random.default_rng(10)
+    N, H, W, C, m, k, kh, kw = 2, 4, 3, 2, 3, 2, 3, 3
+    act = rng.standard_normal((N, H, W, C)); A = rng.standard_normal((m, k))
+    B = rng.standard_normal((k, kh * kw * C)); R = rng.standard_normal((N * H * W, m))
+    loss = lambda a_, A_, B_: float(np.sum(orc.lr_conv_fwd(a_, A_, B_, kh, kw)[0] * R))
+    dAct, dA, dB, _ = orc.lr_conv_bwd(R, act, A, B, kh, kw)
+    eps = 1e-6
+    for arr, grad, which in ((act, dAct, 0), (A, dA, 1), (B, dB, 2)):
+        for _ in range(12):
+            idx = tuple(rng.integers(0, s) for s in arr.shape)
+            hi = [act.copy(), A.copy(), B.copy()]; lo = [act.copy(), A.copy(), B.copy()]
+            hi[which][idx] += eps; lo[which][idx] -= eps
+            fd = (loss(*hi) - loss(*lo)) / (2 * eps)
+            assert fd == pytest.approx(grad[idx], rel=1e-6, abs=1e-8)
