@@ -244,6 +244,38 @@ double ab_lr_rebound_scale(int64_t i, int64_t rebound_steps);
 int ab_reconstruct(const float* A, const float* B, float* W,
                    int64_t m, int64_t n, int64_t k, void* stream);
 
+/* -------------------------------------------------------------------------------------
+ * Factored convolution (Sec. "Methodology": a weight with more than two dimensions is flattened
+ * over its trailing dimensions to give the matrix W of Eq. 3).  A kh x kw convolution weight
+ * [m, kh, kw, C] flattened to W [m, kh kw C] = A [m, r] . B [r, kh kw C]: B acts as a kh x kw
+ * convolution to r channels, A as a 1 x 1 convolution.  The patch matrix is never materialised:
+ * the kernels gather it from the activation.
+ * Layout: activation act [N, H, W, C] channels last; the flattened axis of B is tap-major,
+ * column (ky kw + kx) C + c; outputs Y [N H W, m], T [N H W, r] (row = pixel, in act's order).
+ * Stride 1, zero padding kh/2, kw/2 ("same"), kh and kw odd.  bf16 only (fp32 accumulation).
+ *   lr_conv_fwd:  T = patches(act) . B^T,  Y = T . A^T          (T_save may be NULL)
+ *   lr_conv_bwd:  dT = dY . A,  dA = dY^T . T,  dB = dT^T . patches(act),
+ *                 dAct = adjoint of the patch extraction applied to dT . B
+ *     dAct [N, H, W, C] bf16, dA [m, r] and dB [r, kh kw C] fp32; each may be NULL (skipped);
+ *     T may be NULL (recomputed); accumulate != 0 adds into dA, dB.
+ * Limits: C and m multiples of 64; r a multiple of 32, <= 384 and not 224, 288 or 352;
+ * kh kw C <= 2^20; N H W < 2^31.  Errors as for lr_linear_*; ABT_EDTYPE for dtype != ABT_BF16.
+ * ------------------------------------------------------------------------------------- */
+typedef struct {
+    int64_t N, H, W, C;
+    int32_t kh, kw;
+} abt_conv_geom;
+
+int lr_conv_fwd(const void* act, const void* A, const void* B, void* Y, void* T_save,
+                const abt_conv_geom* geom, int64_t m, int64_t r, int dtype, void* stream);
+
+int lr_conv_bwd(const void* dY, const void* act, const void* T, const void* A, const void* B,
+                void* dAct, float* dA, float* dB,
+                const abt_conv_geom* geom, int64_t m, int64_t r, int dtype, int accumulate,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+size_t lr_conv_bwd_workspace_bytes(const abt_conv_geom* geom, int64_t m, int64_t r, int dtype);
+
 /* Sweep cap of the Jacobi SVD (default 30, clamped to [1, 64]; sweeps stop as soon as every layer
  * has converged: 8-9 for the 384-wide cores of config 5, about 15 for dense 768-wide weights);
  * returns the previous value. */

@@ -24,6 +24,7 @@ EXPORTS = (
     "ab_factorize", "ab_factorize_workspace_bytes",
     "ab_factorize_batched", "ab_factorize_batched_workspace_bytes",
     "ab_adamw_step", "ab_lr_rebound_scale", "ab_reconstruct",
+    "lr_conv_fwd", "lr_conv_bwd", "lr_conv_bwd_workspace_bytes",
 )
 
 
@@ -36,6 +37,11 @@ class FactorizeDesc(ctypes.Structure):
                 ("tau", ctypes.c_float), ("k_fixed", ctypes.c_int64),
                 ("A_out", ctypes.c_void_p), ("B_out", ctypes.c_void_p), ("S_out", ctypes.c_void_p),
                 ("k_out", ctypes.c_void_p), ("k_cap", ctypes.c_int64)]
+
+
+class ConvGeom(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int64), ("H", ctypes.c_int64), ("W", ctypes.c_int64), ("C", ctypes.c_int64),
+                ("kh", ctypes.c_int32), ("kw", ctypes.c_int32)]
 
 
 class AdamwTensor(ctypes.Structure):
@@ -111,6 +117,13 @@ def load():
     lib.ab_lr_rebound_scale.argtypes = [i64, i64]
     lib.ab_reconstruct.restype = ci
     lib.ab_reconstruct.argtypes = [vp, vp, vp, i64, i64, i64, vp]
+    pg = ctypes.POINTER(ConvGeom)
+    lib.lr_conv_fwd.restype = ci
+    lib.lr_conv_fwd.argtypes = [vp, vp, vp, vp, vp, pg, i64, i64, ci, vp]
+    lib.lr_conv_bwd.restype = ci
+    lib.lr_conv_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, pg, i64, i64, ci, ci, vp, sz, vp]
+    lib.lr_conv_bwd_workspace_bytes.restype = sz
+    lib.lr_conv_bwd_workspace_bytes.argtypes = [pg, i64, i64, ci]
     _lib = lib
     return lib
 
@@ -223,6 +236,74 @@ def lr_linear_bwd(dY, X, T, A, B, need_dX: bool = True, need_dA: bool = True, ne
                              _ptr(dB if need_dB else None), M, m, n, r, dt, int(bool(accumulate)),
                              _ptr(ws), ws.numel(), _stream()), "lr_linear_bwd")
     return (dX if need_dX else None), (dA if need_dA else None), (dB if need_dB else None)
+
+
+def _conv_geom(act, B, kh, kw):
+    torch = _torch()
+    _dev_tensor(act, "act")
+    if act.dim() != 4 or act.dtype != torch.bfloat16:
+        raise AbtError("act must be a bf16 tensor [N, H, W, C] (channels last)")
+    N, H, W, C = act.shape
+    if B.dim() != 2 or B.shape[1] != kh * kw * C:
+        raise AbtError("B must be [r, kh*kw*C] with tap-major columns")
+    return ConvGeom(N, H, W, C, kh, kw), N * H * W
+
+
+def lr_conv_fwd(act, A, B, kh: int, kw: int, save_T: bool = True, Y=None, T=None):
+    """Factored kh x kw convolution (stride 1, zero padding): Y [N*H*W, m], T [N*H*W, r] from the
+    channels-last activation act [N, H, W, C], A [m, r], B [r, kh*kw*C] (all bf16, on the GPU)."""
+    torch = _torch()
+    lib = load()
+    A, B = _dev_tensor(A, "A"), _dev_tensor(B, "B")
+    geom, M = _conv_geom(act, B, kh, kw)
+    m, r = A.shape
+    if B.shape[0] != r:
+        raise AbtError("shape mismatch: A [m,r], B [r, kh*kw*C]")
+    if Y is None:
+        Y = torch.empty((M, m), dtype=act.dtype, device=act.device)
+    if save_T and T is None:
+        T = torch.empty((M, r), dtype=act.dtype, device=act.device)
+    if not save_T:
+        T = None
+    _check(lib.lr_conv_fwd(_ptr(act), _ptr(A), _ptr(B), _ptr(Y), _ptr(T), ctypes.byref(geom), m, r, _dt(act), _stream()),
+           "lr_conv_fwd")
+    return Y, T
+
+
+def lr_conv_bwd(dY, act, T, A, B, kh: int, kw: int, need_dAct: bool = True, need_dA: bool = True,
+                need_dB: bool = True, dAct=None, dA=None, dB=None, accumulate: bool = False, workspace=None):
+    """Gradients of the factored convolution: dAct [N,H,W,C] bf16, dA [m,r] fp32, dB [r, kh*kw*C] fp32;
+    skipped gradients are None.  T may be None (recomputed)."""
+    torch = _torch()
+    lib = load()
+    dY, A, B = _dev_tensor(dY, "dY"), _dev_tensor(A, "A"), _dev_tensor(B, "B")
+    geom, M = _conv_geom(act, B, kh, kw)
+    m, r = A.shape
+    if tuple(dY.shape) != (M, m) or B.shape[0] != r or (T is not None and tuple(_dev_tensor(T, "T").shape) != (M, r)):
+        raise AbtError("shape mismatch: dY [N*H*W, m], A [m,r], B [r, kh*kw*C], T [N*H*W, r]")
+    dev = act.device
+    if need_dAct and dAct is None:
+        dAct = torch.empty_like(act)
+    if need_dA and dA is None:
+        dA = torch.zeros((m, r), dtype=torch.float32, device=dev) if accumulate else \
+            torch.empty((m, r), dtype=torch.float32, device=dev)
+    if need_dB and dB is None:
+        dB = torch.zeros(tuple(B.shape), dtype=torch.float32, device=dev) if accumulate else \
+            torch.empty(tuple(B.shape), dtype=torch.float32, device=dev)
+    if not need_dAct:
+        dAct = None
+    if not need_dA:
+        dA = None
+    if not need_dB:
+        dB = None
+    need = lib.lr_conv_bwd_workspace_bytes(ctypes.byref(geom), m, r, _dt(act))
+    if need == 0:
+        raise AbtError("lr_conv_bwd: unsupported shape")
+    ws = _workspace(need, dev, workspace)
+    _check(lib.lr_conv_bwd(_ptr(dY), _ptr(act), _ptr(T), _ptr(A), _ptr(B), _ptr(dAct), _ptr(dA), _ptr(dB),
+                           ctypes.byref(geom), m, r, _dt(act), 1 if accumulate else 0,
+                           _ptr(ws), ws.numel() * ws.element_size(), _stream()), "lr_conv_bwd")
+    return dAct, dA, dB
 
 
 def _ptr_array(tensors: Sequence):

@@ -101,6 +101,129 @@ const char* abt_status_string(int status) {
     }
 }
 
+namespace {
+
+int check_conv(const abt_conv_geom* g, int64_t m, int64_t r, int dt) {
+    if (!g) return ABT_EINVAL;
+    if (dt != ABT_BF16) return ABT_EDTYPE;
+    if (g->N < 1 || g->H < 1 || g->W < 1 || g->C < 1 || m < 1 || r < 1 || g->kh < 1 || g->kw < 1) return ABT_ESHAPE;
+    if (!(g->kh & 1) || !(g->kw & 1) || g->kh > 15 || g->kw > 15) return ABT_ESHAPE;
+    if (g->C % 64 || m % 64 || r % 32 || r > 384 || r == 224 || r == 288 || r == 352) return ABT_ESHAPE;
+    if (g->H > (1 << 20) || g->W > (1 << 20) || g->C > (1 << 20) || m > (1 << 20)) return ABT_ESHAPE;
+    if ((int64_t)g->kh * g->kw * g->C > (1 << 20)) return ABT_ESHAPE;
+    if (g->N > 0x7fffffff / (g->H * g->W)) return ABT_ESHAPE;     // pixel count fits an int
+    // the window of the image that one 64-row block's patches touch is addressed with 32-bit offsets
+    if ((64 + 2 * ((g->kh / 2) * g->W + g->kw / 2)) * g->C * 2 >= kBufMaxBytes) return ABT_ESHAPE;
+    return ABT_OK;
+}
+
+// column block of the activation gradient computed per launch: the widest supported tile that divides C
+int conv_dact_chunk(int64_t C) {
+    static const int sizes[] = {384, 320, 256, 192, 160, 128, 96, 64};
+    for (int v : sizes) if (C % v == 0) return v;
+    return 64;
+}
+
+struct ConvBwdLayout { size_t At, dT, T, Pst, partials, total; int r_pad; };
+
+ConvBwdLayout conv_bwd_layout(const abt_conv_geom& g, int64_t m, int64_t r) {
+    ConvBwdLayout w{};
+    const int64_t M = g.N * g.H * g.W, taps = (int64_t)g.kh * g.kw;
+    w.r_pad = (int)((r + 63) / 64 * 64);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    w.At = take((size_t)r * m * 2);
+    w.dT = take((size_t)M * r * 2);
+    w.T = take((size_t)M * r * 2);
+    w.Pst = take((size_t)g.C * taps * w.r_pad * 2);
+    const TnJob ja{nullptr, nullptr, nullptr, (int)m, 0}, jb{nullptr, nullptr, nullptr, (int)(taps * g.C), 1};
+    const size_t pa = tn_partials_bytes(M, &ja, 1, (int)r), pb = tn_partials_bytes(M, &jb, 1, (int)r);
+    w.partials = take(pa > pb ? pa : pb);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+size_t lr_conv_bwd_workspace_bytes(const abt_conv_geom* geom, int64_t m, int64_t r, int dt) {
+    if (check_conv(geom, m, r, dt) != ABT_OK) return 0;
+    return conv_bwd_layout(*geom, m, r).total;
+}
+
+int lr_conv_fwd(const void* act, const void* A, const void* B, void* Y, void* T_save,
+                const abt_conv_geom* geom, int64_t m, int64_t r, int dt, void* stream) {
+    int st = check_conv(geom, m, r, dt);
+    if (st != ABT_OK) return st;
+    if (!act || !A || !B || !Y) return ABT_EINVAL;
+    if (!aligned(act, 16) || !aligned(A, 16) || !aligned(B, 16) || !aligned(Y, 16) || !aligned(T_save, 16))
+        return ABT_EALIGN;
+    const abt_conv_geom& g = *geom;
+    const int64_t M = g.N * g.H * g.W;
+    const PatchGeom pg{(int)g.H, (int)g.W, (int)g.C, g.kh, g.kw, +1};
+    return launch_chain2_gather_bf16(act, pg, B, A, Y, T_save, (int)r, M, (int)m, (int)r, (hipStream_t)stream) == hipSuccess
+               ? ABT_OK : ABT_EHIP;
+}
+
+int lr_conv_bwd(const void* dY, const void* act, const void* T, const void* A, const void* B,
+                void* dAct, float* dA, float* dB,
+                const abt_conv_geom* geom, int64_t m, int64_t r, int dt, int accumulate,
+                void* workspace, size_t workspace_bytes, void* stream) {
+    int st = check_conv(geom, m, r, dt);
+    if (st != ABT_OK) return st;
+    if (!dY || !act || !A || !B) return ABT_EINVAL;
+    if (!aligned(dY, 16) || !aligned(act, 16) || !aligned(T, 16) || !aligned(A, 16) || !aligned(B, 16) ||
+        !aligned(dAct, 16) || !aligned(dA, 16) || !aligned(dB, 16))
+        return ABT_EALIGN;
+    const abt_conv_geom& g = *geom;
+    const ConvBwdLayout w = conv_bwd_layout(g, m, r);
+    if (!workspace || workspace_bytes < w.total) return ABT_EWORKSPACE;
+    if (!aligned(workspace, 256)) return ABT_EALIGN;
+    if (!dAct && !dA && !dB) return ABT_OK;
+    hipStream_t s = (hipStream_t)stream;
+    char* ws = (char*)workspace;
+    const int64_t M = g.N * g.H * g.W;
+    const int taps = g.kh * g.kw;
+    const int acc = accumulate ? 1 : 0;
+    const PatchGeom fwd_geom{(int)g.H, (int)g.W, (int)g.C, g.kh, g.kw, +1};
+    void* dT = ws + w.dT;
+    const void* Tp = T;
+    if (!Tp && dA) {   // recompute T = patches(act) B^T (first stage of the chain only)
+        if (launch_chain2_gather_bf16(act, fwd_geom, B, nullptr, nullptr, ws + w.T, (int)r, M, 64, (int)r, s) != hipSuccess)
+            return ABT_EHIP;
+        Tp = ws + w.T;
+    }
+    if (dAct || dB) {
+        // dT = dY A = dY (A^T)^T: first stage of the plain chain on the transposed factor
+        const TransposeJob tj{A, ws + w.At, (int)m, (int)r};
+        if (launch_transpose_bf16(&tj, 1, s) != hipSuccess) return ABT_EHIP;
+        if (launch_chain2_bf16(dY, ws + w.At, nullptr, nullptr, dT, M, (int)m, 64, (int)r, s) != hipSuccess) return ABT_EHIP;
+    }
+    if (dAct) {
+        // dAct[q, c] = sum over taps and j of dT[q - shift(tap), j] B[j, tap, c]: the same gathered
+        // product as the forward, on the image dT [N, H, W, r] with mirrored shifts, against the
+        // re-laid-out factor Pst [C, taps r_pad]; one launch per block of output channels
+        if (launch_conv_bstack_bf16(B, ws + w.Pst, (int)r, (int)g.C, taps, w.r_pad, s) != hipSuccess) return ABT_EHIP;
+        const PatchGeom adj{(int)g.H, (int)g.W, (int)r, g.kh, g.kw, -1};
+        const int chunk = conv_dact_chunk(g.C);
+        const int64_t pst_pitch = (int64_t)taps * w.r_pad;
+        for (int64_t c0 = 0; c0 < g.C; c0 += chunk) {
+            const char* Pc = ws + w.Pst + (size_t)c0 * pst_pitch * 2;
+            if (launch_chain2_gather_bf16(dT, adj, Pc, nullptr, nullptr, (char*)dAct + c0 * 2, (int)g.C, M, 64, chunk, s) !=
+                hipSuccess)
+                return ABT_EHIP;
+        }
+    }
+    if (dA) {
+        const TnJob ja{dY, Tp, dA, (int)m, 0};
+        if (launch_tn_bf16(&ja, 1, M, (int)r, acc, (float*)(ws + w.partials), s) != hipSuccess) return ABT_EHIP;
+    }
+    if (dB) {
+        const TnJob jb{act, dT, dB, taps * (int)g.C, 1};
+        if (launch_tn_gather_bf16(jb, fwd_geom, M, (int)r, acc, (float*)(ws + w.partials), s) != hipSuccess) return ABT_EHIP;
+    }
+    return ABT_OK;
+}
+
 int ab_adamw_step(const abt_adamw_tensor* tensors, int n, int64_t step,
                   double lr, double lr_scale, double beta1, double beta2, double eps,
                   double weight_decay, void* stream) {

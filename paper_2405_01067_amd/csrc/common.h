@@ -61,6 +61,15 @@ hipError_t launch_chain_bf16(const void* Xin, const void* P, const void* Q, void
 bool chain2_supports(int R, int p, int q);
 hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                               int64_t M, int p, int q, int R, hipStream_t s);
+// The same chain with the first operand gathered from a channels-last image [M / (H W), H, W, Cin]
+// instead of read from a matrix: row i of the virtual operand is the kh x kw patch around pixel i
+// (zero outside the image), columns ordered (tap, channel) with every tap padded to a multiple of
+// 64 channels: p = kh kw ceil(Cin / 64) 64 columns, which is the row length of P [R, p].
+// sign = +1 reads pixel (y + ky - kh/2, x + kx - kw/2) for tap (ky, kx); sign = -1 the mirrored
+// pixel (the adjoint gather).  Tout rows are t_pitch elements apart (>= R).
+struct PatchGeom { int H, W, Cin, kh, kw, sign; };
+hipError_t launch_chain2_gather_bf16(const void* image, const PatchGeom& g, const void* P, const void* Q,
+                                     void* Yout, void* Tout, int t_pitch, int64_t M, int q, int R, hipStream_t s);
 // dst[c, r] = src[r, c] for a bf16 matrix of `rows` x `cols`.
 struct TransposeJob { const void* src; void* dst; int rows, cols; };   // dst[cols, rows] = src[rows, cols]^T
 hipError_t launch_transpose_bf16(const TransposeJob* jobs, int njobs, hipStream_t s);
@@ -73,6 +82,13 @@ struct TnJob {
 size_t tn_partials_bytes(int64_t M, const TnJob* jobs, int njobs, int R);
 hipError_t launch_tn_bf16(const TnJob* jobs, int njobs, int64_t M, int R, int accumulate,
                           float* partials, hipStream_t s);
+
+// Pst [C, taps r_pad] (bf16) from B [r, taps C]: Pst[c, tap r_pad + j] = B[j, tap C + c], zero for j >= r.
+hipError_t launch_conv_bstack_bf16(const void* B, void* Pst, int r, int C, int taps, int r_pad, hipStream_t s);
+// One job whose U is the patch matrix of a channels-last image (g.sign is ignored: always +1):
+// column tap Cin + c of row i is channel c of pixel (y + ky - kh/2, x + kx - kw/2).  job.P = kh kw Cin.
+hipError_t launch_tn_gather_bf16(const TnJob& job, const PatchGeom& g, int64_t M, int R, int accumulate,
+                                 float* partials, hipStream_t s);
 
 // ------------------------------------------------------------------ fp32 GEMM (MFMA)
 // C[P,Q] = alpha * op(A) . op(B) (+ C if accumulate).  op(A) is P x K: transA == 0 reads

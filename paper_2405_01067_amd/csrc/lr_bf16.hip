@@ -256,7 +256,34 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(TrArgs args) {
     }
 }
 
+// Re-layout of the factor B [r, taps C] of a factored convolution for the activation gradient:
+// Pst [C, taps r_pad] with Pst[c, tap r_pad + j] = B[j, tap C + c] for j < r and 0 for r <= j < r_pad
+// (every tap padded to a multiple of 64 columns, the slab width of the chain kernel).  One thread
+// writes eight consecutive j (16 bytes).
+__global__ __launch_bounds__(256) void conv_bstack_kernel(const uint16_t* __restrict__ B, uint16_t* __restrict__ Pst,
+                                                          int r, int C, int taps, int r_pad) {
+    const int per_row = taps * (r_pad / 8);
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)C * per_row) return;
+    const int c = (int)(idx / per_row), rest = (int)(idx % per_row);
+    const int tap = rest / (r_pad / 8), j0 = (rest % (r_pad / 8)) * 8;
+    uint16_t v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = j0 + i < r ? B[(int64_t)(j0 + i) * taps * C + (int64_t)tap * C + c] : (uint16_t)0;
+    u32x4 o = {(uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16),
+               (uint32_t)v[4] | ((uint32_t)v[5] << 16), (uint32_t)v[6] | ((uint32_t)v[7] << 16)};
+    *reinterpret_cast<u32x4*>(Pst + (int64_t)c * taps * r_pad + (int64_t)tap * r_pad + j0) = o;
+}
+
 }  // namespace
+
+hipError_t launch_conv_bstack_bf16(const void* B, void* Pst, int r, int C, int taps, int r_pad, hipStream_t s) {
+    if (r < 1 || C < 1 || taps < 1 || r_pad % 64 || r_pad < r) return hipErrorInvalidValue;
+    const int64_t n = (int64_t)C * taps * (r_pad / 8);
+    hipLaunchKernelGGL(conv_bstack_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s,
+                       (const uint16_t*)B, (uint16_t*)Pst, r, C, taps, r_pad);
+    return hipGetLastError();
+}
 
 #define ABT_DISPATCH_R(R_, CALL)                          \
     switch (R_) {                                         \

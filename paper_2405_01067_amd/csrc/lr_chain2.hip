@@ -126,13 +126,21 @@ struct Ch2Cfg {
     static_assert(C::RS * C::CS * C::KS == NMW_ && CB * C::CS * 32 == R && RA * C::RS == 2, "wave split");
 };
 
-template <int R>
+// Gather form of the Xin operand (GATHER = true): Xin is not a matrix but a channels-last image
+// [pixels / (H W), H, W, Cin], and row i of the virtual matrix is the patch around pixel i: virtual
+// column (tap, block, c) with tap = ky kw + kx, `cpb` 64-column blocks per tap, reads channel
+// 64 block + c of pixel (y + sign (ky - kh/2), x + sign (kx - kw/2)) of the same image, zero outside
+// the image and for channels >= Cin.  A slab of 64 contraction columns is then one tap and one
+// channel block: 128 contiguous bytes per row, as in the plain case.  p = kh kw cpb 64.
+struct Ch2Gather { int H, W, Cin, cpb, kh, kw, sign; };
+
+template <int R, bool GATHER>
 __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restrict__ Xin,
                                                          const uint16_t* __restrict__ Pm,
                                                          const uint16_t* __restrict__ Qm,
                                                          uint16_t* __restrict__ Yout,
                                                          uint16_t* __restrict__ Tout,
-                                                         int64_t M, int p, int q) {
+                                                         int64_t M, int p, int q, int t_pitch, Ch2Gather gg) {
     extern __shared__ __align__(1024) unsigned char lds[];
     using C = Ch2<R>;
     using L = Ch2Cfg<R>;
@@ -167,7 +175,12 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
         // rows past M read as zeros and stores to them are dropped.
         const int lt = tid - NMT;
         const int64_t rows_valid = M - row0 < 64 ? M - row0 : 64;
-        const rsrc_t xres = make_rsrc(Xin + row0 * p, rows_valid * p * 2);
+        // gather: the descriptor covers the pixels this work-group's patches can touch
+        const int reach = GATHER ? (gg.kh / 2) * gg.W + gg.kw / 2 : 0;
+        const int64_t gpix0 = row0 > reach ? row0 - reach : 0;
+        const int64_t gpix1 = row0 + 64 + reach < M ? row0 + 64 + reach : M;
+        const rsrc_t xres = GATHER ? make_rsrc(Xin + gpix0 * gg.Cin, (gpix1 - gpix0) * gg.Cin * 2)
+                                   : make_rsrc(Xin + row0 * p, rows_valid * p * 2);
         const rsrc_t pres = make_rsrc(Pm, (int64_t)R * p * 2);
         // stage-2 chunk assignment (computed first: the first Q slabs are requested before stage 1's
         // epilogue so that their latency hides behind the reduction and the T tile)
@@ -183,13 +196,38 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
             // stage 1: one ring entry = this thread's chunks of one slab (64 rows of Xin, then the R
             // rows of P), D1 slabs ahead
             int xsrc[L::NCHX], off[L::NCHX];
+            int gy[L::NCHX], gx[L::NCHX];                // gather: image coordinates of the thread's rows
 #pragma unroll
             for (int e = 0; e < L::NCHX; ++e) {
                 const int ci = e * NLT + lt;
                 const int row = ci / CPR1, ch = ci % CPR1;
                 off[e] = row * (BK1 * 2) + swz<CPR1>(ch, row) * 16;
-                xsrc[e] = (row * p + ch * 8) * 2;
+                if constexpr (GATHER) {
+                    const int64_t pix = row0 + row;
+                    gx[e] = (int)(pix % gg.W);
+                    gy[e] = pix < M ? (int)((pix / gg.W) % gg.H) : -(1 << 20);   // rows past M: never valid
+                    xsrc[e] = ((int)(pix - gpix0) * gg.Cin + ch * 8) * 2;
+                } else {
+                    gx[e] = gy[e] = 0;
+                    xsrc[e] = (row * p + ch * 8) * 2;
+                }
             }
+            // per-lane and wave-uniform offset of chunk e of (virtual) slab vs
+            auto xaddr = [&](int e, int vs, int& voff, int& soff) {
+                if constexpr (GATHER) {
+                    const int tap = vs / gg.cpb, cb = vs - tap * gg.cpb;
+                    const int ky = tap / gg.kw, kx = tap - ky * gg.kw;
+                    const int dy = gg.sign * (ky - gg.kh / 2), dx = gg.sign * (kx - gg.kw / 2);
+                    const int ch8 = (lt % CPR1) * 8;
+                    const bool ok = (unsigned)(gy[e] + dy) < (unsigned)gg.H && (unsigned)(gx[e] + dx) < (unsigned)gg.W &&
+                                    cb * 64 + ch8 < gg.Cin;
+                    voff = ok ? xsrc[e] + ((dy * gg.W + dx) * gg.Cin + cb * 64) * 2 : kBufNowhere;
+                    soff = 0;
+                } else {
+                    voff = xsrc[e];
+                    soff = vs * (BK1 * 2);
+                }
+            };
             // P chunk e of this thread: row 32 e + lt / 8, chunk lt % 8
             const int prow0 = lt / CPR1, pch = lt % CPR1;
             const int psrc = (prow0 * p + pch * 8) * 2;
@@ -202,9 +240,14 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
             }
             u32x4 ring[D1][L::NCHX + L::NCHP];
             auto load = [&](u32x4 (&dst)[L::NCHX + L::NCHP], int s) {
-                const int so = slab1_of(s) * (BK1 * 2);
+                const int vs = slab1_of(s);
+                const int so = vs * (BK1 * 2);
 #pragma unroll
-                for (int e = 0; e < L::NCHX; ++e) dst[e] = buf_load16(xres, xsrc[e], so);
+                for (int e = 0; e < L::NCHX; ++e) {
+                    int vo, xo;
+                    xaddr(e, vs, vo, xo);
+                    dst[e] = buf_load16(xres, vo, xo);
+                }
 #pragma unroll
                 for (int e = 0; e < L::NCHP; ++e) dst[L::NCHX + e] = buf_load16(pres, psrc, so + e * pstep);
             };
@@ -220,11 +263,14 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
             // address path then both stay busy instead of taking turns
             auto step1 = [&](u32x4 (&rg)[L::NCHX + L::NCHP], int s) {
                 const int slot = (s + 1) & 1;
-                const int so = slab1_of(s + 1 + D1) * (BK1 * 2);
+                const int vs = slab1_of(s + 1 + D1);
+                const int so = vs * (BK1 * 2);
 #pragma unroll
                 for (int e = 0; e < L::NCHX; ++e) {
+                    int vo, xo;
+                    xaddr(e, vs, vo, xo);
                     *reinterpret_cast<u32x4*>(lds + slot * L::slab1 + off[e]) = rg[e];
-                    rg[e] = buf_load16(xres, xsrc[e], so);
+                    rg[e] = buf_load16(xres, vo, xo);
                     __builtin_amdgcn_sched_barrier(0);
                 }
 #pragma unroll
@@ -278,11 +324,14 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
         }
         // T tile is in LDS: store it (the MFMA waves load their operands from it meanwhile)
         if (Tout != nullptr) {
-            const rsrc_t tres = make_rsrc(Tout + row0 * R, rows_valid * R * 2);
+            // rows of Tout are t_pitch elements apart (R for a plain T; more when the tile is a
+            // column block of a wider matrix); the descriptor ends with the last valid row
+            const rsrc_t tres = make_rsrc(Tout + row0 * t_pitch, ((rows_valid - 1) * t_pitch + R) * 2);
             constexpr int CPT = R / 8;   // 16-byte chunks per T row
             for (int i = lt; i < 64 * CPT; i += NLT) {
                 const int row = i / CPT, ch = i % CPT;
-                buf_store16(*reinterpret_cast<const u32x4*>(ttile + row * L::tpitch + ch * 16), tres, i * 16, 0);
+                buf_store16(*reinterpret_cast<const u32x4*>(ttile + row * L::tpitch + ch * 16), tres,
+                            (row * t_pitch + ch * 8) * 2, 0);
             }
         }
         if (Yout == nullptr) return;
@@ -547,22 +596,34 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
     TMARK(0, 6);
 }
 
-template <int R>
+template <int R, bool GATHER>
 hipError_t launch_chain2_r(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
-                           int64_t M, int p, int q, hipStream_t s) {
+                           int64_t M, int p, int q, int t_pitch, const Ch2Gather& gg, hipStream_t s) {
     constexpr int lds_bytes = Ch2Cfg<R>::lds_bytes;
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chain2_bf16_kernel<R>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chain2_bf16_kernel<R, GATHER>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(chain2_bf16_kernel<R>, dim3((unsigned)ceil_div(M, 64)), dim3(NT), lds_bytes, s,
+    hipLaunchKernelGGL((chain2_bf16_kernel<R, GATHER>), dim3((unsigned)ceil_div(M, 64)), dim3(NT), lds_bytes, s,
                        (const uint16_t*)Xin, (const uint16_t*)P, (const uint16_t*)Q,
-                       (uint16_t*)Yout, (uint16_t*)Tout, M, p, q);
+                       (uint16_t*)Yout, (uint16_t*)Tout, M, p, q, t_pitch, gg);
     return hipGetLastError();
+}
+
+template <bool GATHER>
+hipError_t launch_chain2_any(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
+                             int64_t M, int p, int q, int R, int t_pitch, const Ch2Gather& gg, hipStream_t s) {
+    switch (R) {
+#define ABT_CASE(RR) case RR: return launch_chain2_r<RR, GATHER>(Xin, P, Q, Yout, Tout, M, p, q, t_pitch, gg, s);
+        ABT_CASE(32) ABT_CASE(64) ABT_CASE(96) ABT_CASE(128) ABT_CASE(160) ABT_CASE(192)
+        ABT_CASE(256) ABT_CASE(320) ABT_CASE(384)
+#undef ABT_CASE
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace
@@ -577,18 +638,20 @@ bool chain2_supports(int R, int p, int q) {
 
 hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                               int64_t M, int p, int q, int R, hipStream_t s) {
-    switch (R) {
-        case 32: return launch_chain2_r<32>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 64: return launch_chain2_r<64>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 96: return launch_chain2_r<96>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 128: return launch_chain2_r<128>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 160: return launch_chain2_r<160>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 192: return launch_chain2_r<192>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 256: return launch_chain2_r<256>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 320: return launch_chain2_r<320>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        case 384: return launch_chain2_r<384>(Xin, P, Q, Yout, Tout, M, p, q, s);
-        default: return hipErrorInvalidValue;
-    }
+    return launch_chain2_any<false>(Xin, P, Q, Yout, Tout, M, p, q, R, R, Ch2Gather{}, s);
+}
+
+hipError_t launch_chain2_gather_bf16(const void* image, const PatchGeom& g, const void* P, const void* Q,
+                                     void* Yout, void* Tout, int t_pitch, int64_t M, int q, int R, hipStream_t s) {
+    const int cpb = (g.Cin + 63) / 64;
+    const int64_t p = (int64_t)g.kh * g.kw * cpb * 64;
+    // 32-bit offsets: a work-group's window of the image, and the factor P [R, p]
+    if (g.H < 1 || g.W < 1 || g.Cin < 8 || g.Cin % 8 || g.kh < 1 || g.kw < 1 || !(g.kh & 1) || !(g.kw & 1) ||
+        (g.sign != 1 && g.sign != -1) || M % ((int64_t)g.H * g.W) != 0 || p > (1 << 20) || !chain2_supports(R, (int)p, q) ||
+        ((int64_t)64 + 2 * ((g.kh / 2) * (int64_t)g.W + g.kw / 2)) * g.Cin * 2 >= kBufMaxBytes || t_pitch < R)
+        return hipErrorInvalidValue;
+    const Ch2Gather gg{g.H, g.W, g.Cin, cpb, g.kh, g.kw, g.sign};
+    return launch_chain2_any<true>(image, P, Q, Yout, Tout, M, (int)p, q, R, t_pitch, gg, s);
 }
 
 }  // namespace abt

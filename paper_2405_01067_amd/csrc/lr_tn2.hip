@@ -56,7 +56,11 @@ struct Tn2 {
 };
 
 struct Tn2Job { const uint16_t* U; const uint16_t* V; float* part; int P; int tile_begin; int transposed; };
-struct Tn2Args { Tn2Job job[2]; int njobs; int tiles; int splits; int64_t M; int64_t rows_per_split; };
+// Gather form of U (one job per launch): U is a channels-last image [M / (H W), H, W, C] and column
+// tap C + c of row i of the virtual U is channel c of pixel (y + ky - kh/2, x + kx - kw/2) of the
+// same image (tap = ky kw + kx), zero outside it.  job.P = kh kw C.
+struct Tn2Gather { int H, W, C, kh, kw; };
+struct Tn2Args { Tn2Job job[2]; int njobs; int tiles; int splits; int64_t M; int64_t rows_per_split; Tn2Gather g; };
 
 // LDS slab: column-major, 64 batch rows = 128 bytes per column, two columns per 256-byte line.  The
 // sixteen 16-byte units of a line are XOR-swizzled with bits of the column-pair index p so that
@@ -73,10 +77,11 @@ __device__ __forceinline__ int slab_addr(int col, int unit) {
 // Loader role: moves NCOLS columns (multiple of 8) of a row-major bf16 matrix, 64 batch rows at a
 // time, into LDS columns [col0, col0 + NCOLS) transposed: a thread loads an 8 x 8 block as eight
 // 16-byte row pieces, transposes it in registers, and stores eight 16-byte column pieces.
-template <int NCOLS, int BPT, int D>
+template <int NCOLS, int BPT, int D, bool GATHER = false>
 __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int cols_valid, int col0, int lt,
                                           int64_t k_begin, int64_t k_end, int np, int slab_bytes,
-                                          unsigned char* lds) {
+                                          unsigned char* lds, const Tn2Gather tg = Tn2Gather{}, int vcol0 = 0,
+                                          int64_t pixels = 0) {
     constexpr int NCC = NCOLS / 8;                       // 16-byte chunks per row
     constexpr int RGS = 8 / BPT;                         // row groups per block index
     const int cc = lt % NCC, rg0 = lt / NCC;
@@ -104,6 +109,43 @@ __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int co
 #pragma unroll
         for (int e = 0; e < 8; ++e) dst[e] = buf_load16(res, goff[e] + b * gstep, 0);
     };
+    // gather: this thread's eight virtual columns lie in one tap (C is a multiple of 8)
+    const bool colok = active && cc * 8 < cols_valid;
+    const int gtap = GATHER ? (vcol0 + cc * 8) / tg.C : 0;
+    const int gc = GATHER ? (vcol0 + cc * 8) - gtap * tg.C : 0;
+    const int gky = GATHER ? gtap / tg.kw : 0;
+    const int gdy = GATHER ? gky - tg.kh / 2 : 0, gdx = GATHER ? (gtap - gky * tg.kw) - tg.kw / 2 : 0;
+    const int reach = GATHER ? (tg.kh / 2) * tg.W + tg.kw / 2 : 0;
+    const int xs = GATHER ? (int)(k_begin % tg.W) : 0;                 // image coordinates of row k_begin
+    const int ys = GATHER ? (int)((k_begin / tg.W) % tg.H) : 0;
+    const int64_t span = k_end - k_begin;
+    const int rows_in_split = span > 0x7fffffff ? 0x7fffffff : (int)span;
+    auto load_block_gather = [&](u32x4 (&dst)[8], int s, int b) {
+        // the descriptor covers the pixels that the patches of this slab's 64 rows can touch
+        const int64_t kr0 = k_begin + (int64_t)s * BKM;
+        const int64_t bp = kr0 > reach ? kr0 - reach : 0;
+        int64_t ep = kr0 + BKM + reach;
+        if (ep > pixels) ep = pixels;
+        const rsrc_t res = make_rsrc(src + bp * tg.C, (ep - bp) * tg.C * 2);
+        const int rel = s * BKM + 8 * rg0 + 32 * b;                    // first row of the block, from k_begin
+        const unsigned t = (unsigned)xs + (unsigned)rel;
+        const unsigned xq = t / (unsigned)tg.W;
+        int x = (int)(t - xq * (unsigned)tg.W);
+        int y = (int)(((unsigned)ys + xq) % (unsigned)tg.H);
+        const int left = rows_in_split - rel;                          // rows e < left are inside the split
+        const int o0 = (((int)(kr0 - bp) + 8 * rg0 + 32 * b + gdy * tg.W + gdx) * tg.C + gc) * 2;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const bool ok = colok && e < left && (unsigned)(y + gdy) < (unsigned)tg.H &&
+                            (unsigned)(x + gdx) < (unsigned)tg.W;
+            dst[e] = buf_load16(res, ok ? o0 + e * tg.C * 2 : kBufNowhere, 0);
+            if (++x == tg.W) { x = 0; if (++y == tg.H) y = 0; }
+        }
+    };
+    auto fetch = [&](u32x4 (&dst)[8], rsrc_t res, int s, int b) {
+        if constexpr (GATHER) load_block_gather(dst, s, b);
+        else load_block(dst, res, b);
+    };
     auto store_block = [&](const u32x4 (&v)[8], unsigned char* base, int b) {
         // 8 x 8 transpose of 16-bit elements: word i of output column j packs rows 2i, 2i+1
         u32x4 out[8];
@@ -123,12 +165,12 @@ __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int co
     for (int d = 0; d < D; ++d) {
         const rsrc_t res = descriptor(d);
 #pragma unroll
-        for (int b = 0; b < BPT; ++b) load_block(ring[d][b], res, b);
+        for (int b = 0; b < BPT; ++b) fetch(ring[d][b], res, d, b);
     }
     {
         const rsrc_t res = descriptor(D);
 #pragma unroll
-        for (int b = 0; b < BPT; ++b) { store_block(ring[0][b], lds, b); load_block(ring[0][b], res, b); }
+        for (int b = 0; b < BPT; ++b) { store_block(ring[0][b], lds, b); fetch(ring[0][b], res, D, b); }
     }
     ring_barrier();                                      // slab 0 is in slot 0
     for (int s0 = 0; s0 < np; s0 += D) {
@@ -141,7 +183,7 @@ __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int co
 #pragma unroll
             for (int b = 0; b < BPT; ++b) {
                 store_block(ring[(d + 1) % D][b], base, b);
-                load_block(ring[(d + 1) % D][b], res, b);
+                fetch(ring[(d + 1) % D][b], res, s + 1 + D, b);
                 __builtin_amdgcn_sched_barrier(0);
             }
             TN_STAMP(1, 1, s);
@@ -150,7 +192,7 @@ __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int co
     }
 }
 
-template <int R>
+template <int R, bool GATHER>
 __global__ __launch_bounds__(Tn2<R>::NT) void tn2_bf16_kernel(Tn2Args args) {
     extern __shared__ __align__(1024) unsigned char lds[];
     using C = Tn2<R>;
@@ -178,7 +220,11 @@ __global__ __launch_bounds__(Tn2<R>::NT) void tn2_bf16_kernel(Tn2Args args) {
         return;
     }
     if (wave >= NMW) {
-        tn_loader<TP, C::BPT, D>(job.U + p0, job.P, job.P - p0, 0, tid - 64 * NMW, k_begin, k_end, np, C::slab, lds);
+        if constexpr (GATHER)
+            tn_loader<TP, C::BPT, D, true>(job.U, job.P, job.P - p0, 0, tid - 64 * NMW, k_begin, k_end, np, C::slab, lds,
+                                           args.g, p0, args.M);
+        else
+            tn_loader<TP, C::BPT, D>(job.U + p0, job.P, job.P - p0, 0, tid - 64 * NMW, k_begin, k_end, np, C::slab, lds);
         return;
     }
 
@@ -289,17 +335,17 @@ int tn2_choose_splits(int64_t M, int total_tiles) {
     return (int)want;
 }
 
-template <int R>
+template <int R, bool GATHER>
 hipError_t launch_tn2_r(const Tn2Args& args, int tiles, int splits, hipStream_t s) {
     constexpr int lds_bytes = Tn2<R>::lds_bytes;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tn2_bf16_kernel<R>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tn2_bf16_kernel<R, GATHER>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(tn2_bf16_kernel<R>, dim3(8 * tiles * ((splits + 7) / 8)), dim3(Tn2<R>::NT), lds_bytes, s, args);
+    hipLaunchKernelGGL((tn2_bf16_kernel<R, GATHER>), dim3(8 * tiles * ((splits + 7) / 8)), dim3(Tn2<R>::NT), lds_bytes, s, args);
     return hipGetLastError();
 }
 
@@ -312,9 +358,10 @@ size_t tn_partials_bytes(int64_t M, const TnJob* jobs, int njobs, int R) {
     return elems * splits * sizeof(float);
 }
 
-hipError_t launch_tn_bf16(const TnJob* jobs, int njobs, int64_t M, int R, int accumulate,
-                          float* partials, hipStream_t s) {
-    if (njobs < 1 || njobs > 2) return hipErrorInvalidValue;
+namespace {
+hipError_t launch_tn_common(const TnJob* jobs, int njobs, int64_t M, int R, int accumulate,
+                            float* partials, const Tn2Gather* gather, hipStream_t s) {
+    if (njobs < 1 || njobs > 2 || (gather && njobs != 1)) return hipErrorInvalidValue;
     const int tiles = tn2_total_tiles(jobs, njobs);
     const int splits = tn2_choose_splits(M, tiles);
     Tn2Args args{};
@@ -322,6 +369,7 @@ hipError_t launch_tn_bf16(const TnJob* jobs, int njobs, int64_t M, int R, int ac
     args.njobs = red.njobs = njobs;
     args.tiles = tiles; args.splits = splits;
     args.M = M;
+    if (gather) args.g = *gather;
     int64_t rps = ceil_div(M, splits);
     rps = ceil_div(rps, 64) * 64;
     args.rows_per_split = rps;
@@ -346,7 +394,8 @@ hipError_t launch_tn_bf16(const TnJob* jobs, int njobs, int64_t M, int R, int ac
     }
     hipError_t e;
     switch (R) {
-#define ABT_CASE(RR) case RR: e = launch_tn2_r<RR>(args, tiles, splits, s); break;
+#define ABT_CASE(RR) case RR: e = gather ? launch_tn2_r<RR, true>(args, tiles, splits, s) \
+                                         : launch_tn2_r<RR, false>(args, tiles, splits, s); break;
         ABT_CASE(32) ABT_CASE(64) ABT_CASE(96) ABT_CASE(128) ABT_CASE(160) ABT_CASE(192)
         ABT_CASE(224) ABT_CASE(256) ABT_CASE(288) ABT_CASE(320) ABT_CASE(352) ABT_CASE(384)
 #undef ABT_CASE
@@ -355,6 +404,23 @@ hipError_t launch_tn_bf16(const TnJob* jobs, int njobs, int64_t M, int R, int ac
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(tn2_reduce_kernel, dim3(red_blocks), dim3(256), 0, s, red);
     return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_tn_bf16(const TnJob* jobs, int njobs, int64_t M, int R, int accumulate,
+                          float* partials, hipStream_t s) {
+    return launch_tn_common(jobs, njobs, M, R, accumulate, partials, nullptr, s);
+}
+
+hipError_t launch_tn_gather_bf16(const TnJob& job, const PatchGeom& g, int64_t M, int R, int accumulate,
+                                 float* partials, hipStream_t s) {
+    // 32-bit offsets inside the window of the image that one slab's patches touch
+    if (g.H < 1 || g.W < 1 || g.Cin < 8 || g.Cin % 8 || g.kh < 1 || g.kw < 1 || !(g.kh & 1) || !(g.kw & 1) ||
+        M % ((int64_t)g.H * g.W) != 0 || job.P != g.kh * g.kw * g.Cin ||
+        ((int64_t)64 + 2 * ((g.kh / 2) * (int64_t)g.W + g.kw / 2)) * g.Cin * 2 >= kBufMaxBytes)
+        return hipErrorInvalidValue;
+    const Tn2Gather tg{g.H, g.W, g.Cin, g.kh, g.kw};
+    return launch_tn_common(&job, 1, M, R, accumulate, partials, &tg, s);
 }
 
 }  // namespace abt
