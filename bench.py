@@ -41,6 +41,7 @@ def main():
                     help="also run one plain 256 MiB device copy: the reference dispatch that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command")
     ap.add_argument("--no-group", action="store_true", help="skip the group-training step timings")
+    ap.add_argument("--no-conv", action="store_true", help="skip the native factored-convolution timings")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time every config-3 / config-4 case (extra key `cases`)")
     args = ap.parse_args()
@@ -183,6 +184,41 @@ def main():
             del st
             torch.cuda.empty_cache()
         out["cases"] = cases
+
+    # ------------------------------------------------------------------ factored 3x3 convolutions, native (extra key)
+    # config 4's two 3x3 cases without the patch matrix: same flops as the im2col form, the
+    # activation read at its true size (lr_conv_fwd + lr_conv_bwd, all three gradients)
+    if not args.no_conv:
+        conv = []
+        for name, N, H, W, C, m, r in gen.RESNET50_CONVS_NATIVE:
+            c = gen.conv_case(N, H, W, C, m, r, 3, 3, seed=11)
+            act, dYc, Ac, Bc = (up(c[k], bf16) for k in ("act", "dY", "A", "B"))
+            Mc, nc = N * H * W, 9 * C
+            Yc = torch.empty((Mc, m), dtype=bf16, device=dev)
+            Tc = torch.empty((Mc, r), dtype=bf16, device=dev)
+            dAct = torch.empty_like(act)
+            dAc = torch.empty((m, r), dtype=torch.float32, device=dev)
+            dBc = torch.empty((r, nc), dtype=torch.float32, device=dev)
+            geom = abt.ConvGeom(N, H, W, C, 3, 3)
+            import ctypes
+            wsb = abt.load().lr_conv_bwd_workspace_bytes(ctypes.byref(geom), m, r, abt.ABT_BF16)
+            wsc = torch.empty(wsb, dtype=torch.uint8, device=dev)
+
+            def conv_step():
+                abt.lr_conv_fwd(act, Ac, Bc, 3, 3, save_T=True, Y=Yc, T=Tc)
+                abt.lr_conv_bwd(dYc, act, Tc, Ac, Bc, 3, 3, dAct=dAct, dA=dAc, dB=dBc, workspace=wsc)
+
+            sc = time_steps(conv_step, 50, 10)
+            flops = 6.0 * Mc * r * (m + nc)
+            # algorithmic bytes: activation, its gradient, Y, dY, T (written, read), dT (written, read twice)
+            byt = 2.0 * (2 * Mc * C + 2 * Mc * m + 5 * Mc * r + 2 * (m * r + r * nc)) + 4.0 * (m * r + r * nc)
+            conv.append({"case": name, "N": N, "H": H, "W": W, "C": C, "m": m, "r": r, "ms": round(sc * 1e3, 4),
+                         "tflops": round(flops / sc / 1e12, 1),
+                         "pct_mfma_peak": round(100 * flops / sc / 1e12 / PEAK_BF16_TFLOPS, 2),
+                         "hbm_frac": round(byt / sc / 1e9 / PEAK_HBM_GBS, 4)})
+            del act, dYc, Ac, Bc, Yc, Tc, dAct, dAc, dBc, wsc
+            torch.cuda.empty_cache()
+        out["conv_native"] = conv
 
     # ------------------------------------------------------------------ merge: config 5 (gap-centred threshold)
     if not args.no_merge:

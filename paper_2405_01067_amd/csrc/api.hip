@@ -137,8 +137,10 @@ ConvBwdLayout conv_bwd_layout(const abt_conv_geom& g, int64_t m, int64_t r) {
     w.T = take((size_t)M * r * 2);
     w.Pst = take((size_t)g.C * taps * w.r_pad * 2);
     const TnJob ja{nullptr, nullptr, nullptr, (int)m, 0}, jb{nullptr, nullptr, nullptr, (int)(taps * g.C), 1};
+    const TnJob both[2] = {ja, jb};
     const size_t pa = tn_partials_bytes(M, &ja, 1, (int)r), pb = tn_partials_bytes(M, &jb, 1, (int)r);
-    w.partials = take(pa > pb ? pa : pb);
+    const size_t pab = tn_partials_bytes(M, both, 2, (int)r);
+    w.partials = take(pa > pb ? (pa > pab ? pa : pab) : (pb > pab ? pb : pab));
     w.total = off;
     return w;
 }
@@ -213,13 +215,15 @@ int lr_conv_bwd(const void* dY, const void* act, const void* T, const void* A, c
                 return ABT_EHIP;
         }
     }
-    if (dA) {
-        const TnJob ja{dY, Tp, dA, (int)m, 0};
-        if (launch_tn_bf16(&ja, 1, M, (int)r, acc, (float*)(ws + w.partials), s) != hipSuccess) return ABT_EHIP;
-    }
+    // factor gradients: dA = dY^T T (plain) and dB = patches(act)^T dT (gathered), one launch
+    TnJob jobs[2];
+    int nj = 0;
+    if (dA) jobs[nj++] = TnJob{dY, Tp, dA, (int)m, 0};
+    if (dB) jobs[nj++] = TnJob{act, dT, dB, taps * (int)g.C, 1};
     if (dB) {
-        const TnJob jb{act, dT, dB, taps * (int)g.C, 1};
-        if (launch_tn_gather_bf16(jb, fwd_geom, M, (int)r, acc, (float*)(ws + w.partials), s) != hipSuccess) return ABT_EHIP;
+        if (launch_tn_gather_bf16(jobs, nj, fwd_geom, M, (int)r, acc, (float*)(ws + w.partials), s) != hipSuccess) return ABT_EHIP;
+    } else if (dA) {
+        if (launch_tn_bf16(jobs, 1, M, (int)r, acc, (float*)(ws + w.partials), s) != hipSuccess) return ABT_EHIP;
     }
     return ABT_OK;
 }

@@ -85,9 +85,10 @@ hipError_t launch_tn_bf16(const TnJob* jobs, int njobs, int64_t M, int R, int ac
 
 // Pst [C, taps r_pad] (bf16) from B [r, taps C]: Pst[c, tap r_pad + j] = B[j, tap C + c], zero for j >= r.
 hipError_t launch_conv_bstack_bf16(const void* B, void* Pst, int r, int C, int taps, int r_pad, hipStream_t s);
-// One job whose U is the patch matrix of a channels-last image (g.sign is ignored: always +1):
-// column tap Cin + c of row i is channel c of pixel (y + ky - kh/2, x + kx - kw/2).  job.P = kh kw Cin.
-hipError_t launch_tn_gather_bf16(const TnJob& job, const PatchGeom& g, int64_t M, int R, int accumulate,
+// One or two jobs; the U of the LAST one is the patch matrix of a channels-last image (g.sign is
+// ignored: always +1): column tap Cin + c of row i is channel c of pixel (y + ky - kh/2, x + kx - kw/2),
+// and its P = kh kw Cin.  A job before it is a plain one.  Partials as for launch_tn_bf16.
+hipError_t launch_tn_gather_bf16(const TnJob* jobs, int njobs, const PatchGeom& g, int64_t M, int R, int accumulate,
                                  float* partials, hipStream_t s);
 
 // ------------------------------------------------------------------ fp32 GEMM (MFMA)

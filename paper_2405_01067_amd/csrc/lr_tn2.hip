@@ -51,12 +51,14 @@ struct Tn2 {
     static constexpr int NUW = (TP / BPT + 63) / 64;         // loader waves for the U part
     static constexpr int NVW = (R / BPT + 63) / 64;          // loader waves for the V part
     static constexpr int NT = 64 * (NMW + NUW + NVW);
-    static constexpr int D = 2;                              // slabs in flight in the loaders' register ring
+    // slabs in flight in the loaders' register ring: a CU wants about 64 KB of loads outstanding,
+    // which two slabs only give when a slab is 40 KB or more (R >= 192)
+    static constexpr int D = slab * 2 >= 64 * 1024 ? 2 : (slab * 3 >= 64 * 1024 ? 3 : 4);
     static_assert(lds_bytes <= 160 * 1024, "slab shape");
 };
 
-struct Tn2Job { const uint16_t* U; const uint16_t* V; float* part; int P; int tile_begin; int transposed; };
-// Gather form of U (one job per launch): U is a channels-last image [M / (H W), H, W, C] and column
+struct Tn2Job { const uint16_t* U; const uint16_t* V; float* part; int P; int tile_begin; int transposed; int gather; };
+// Gather form of U (jobs with gather != 0): U is a channels-last image [M / (H W), H, W, C] and column
 // tap C + c of row i of the virtual U is channel c of pixel (y + ky - kh/2, x + kx - kw/2) of the
 // same image (tap = ky kw + kx), zero outside it.  job.P = kh kw C.
 struct Tn2Gather { int H, W, C, kh, kw; };
@@ -116,10 +118,19 @@ __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int co
     const int gky = GATHER ? gtap / tg.kw : 0;
     const int gdy = GATHER ? gky - tg.kh / 2 : 0, gdx = GATHER ? (gtap - gky * tg.kw) - tg.kw / 2 : 0;
     const int reach = GATHER ? (tg.kh / 2) * tg.W + tg.kw / 2 : 0;
-    const int xs = GATHER ? (int)(k_begin % tg.W) : 0;                 // image coordinates of row k_begin
-    const int ys = GATHER ? (int)((k_begin / tg.W) % tg.H) : 0;
     const int64_t span = k_end - k_begin;
     const int rows_in_split = span > 0x7fffffff ? 0x7fffffff : (int)span;
+    // Image coordinates of the first row of each of the thread's blocks, for the slab that block
+    // fetches next.  Slabs are fetched in order (0, 1, 2, ...), 64 rows apart: the coordinates are
+    // carried along with one add-and-wrap per slab instead of two integer divisions.
+    int bx[BPT], by[BPT];
+    const int step_x = GATHER ? BKM % tg.W : 0, step_y = GATHER ? (BKM / tg.W) % tg.H : 0;
+#pragma unroll
+    for (int b = 0; b < BPT; ++b) {
+        const int64_t first = k_begin + 8 * rg0 + 32 * b;
+        bx[b] = GATHER ? (int)(first % tg.W) : 0;
+        by[b] = GATHER ? (int)((first / tg.W) % tg.H) : 0;
+    }
     auto load_block_gather = [&](u32x4 (&dst)[8], int s, int b) {
         // the descriptor covers the pixels that the patches of this slab's 64 rows can touch
         const int64_t kr0 = k_begin + (int64_t)s * BKM;
@@ -128,17 +139,21 @@ __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int co
         if (ep > pixels) ep = pixels;
         const rsrc_t res = make_rsrc(src + bp * tg.C, (ep - bp) * tg.C * 2);
         const int rel = s * BKM + 8 * rg0 + 32 * b;                    // first row of the block, from k_begin
-        const unsigned t = (unsigned)xs + (unsigned)rel;
-        const unsigned xq = t / (unsigned)tg.W;
-        int x = (int)(t - xq * (unsigned)tg.W);
-        int y = (int)(((unsigned)ys + xq) % (unsigned)tg.H);
+        int x = bx[b], y = by[b];
+        // advance to the next slab (this lambda is called once per slab and block, in slab order)
+        bx[b] += step_x;
+        const int carry = bx[b] >= tg.W ? 1 : 0;
+        bx[b] -= carry ? tg.W : 0;
+        by[b] += step_y + carry;
+        by[b] -= by[b] >= tg.H ? tg.H : 0;
         const int left = rows_in_split - rel;                          // rows e < left are inside the split
-        const int o0 = (((int)(kr0 - bp) + 8 * rg0 + 32 * b + gdy * tg.W + gdx) * tg.C + gc) * 2;
+        int off = (((int)(kr0 - bp) + 8 * rg0 + 32 * b + gdy * tg.W + gdx) * tg.C + gc) * 2;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const bool ok = colok && e < left && (unsigned)(y + gdy) < (unsigned)tg.H &&
                             (unsigned)(x + gdx) < (unsigned)tg.W;
-            dst[e] = buf_load16(res, ok ? o0 + e * tg.C * 2 : kBufNowhere, 0);
+            dst[e] = buf_load16(res, ok ? off : kBufNowhere, 0);
+            off += tg.C * 2;
             if (++x == tg.W) { x = 0; if (++y == tg.H) y = 0; }
         }
     };
@@ -220,11 +235,14 @@ __global__ __launch_bounds__(Tn2<R>::NT) void tn2_bf16_kernel(Tn2Args args) {
         return;
     }
     if (wave >= NMW) {
-        if constexpr (GATHER)
-            tn_loader<TP, C::BPT, D, true>(job.U, job.P, job.P - p0, 0, tid - 64 * NMW, k_begin, k_end, np, C::slab, lds,
-                                           args.g, p0, args.M);
-        else
-            tn_loader<TP, C::BPT, D>(job.U + p0, job.P, job.P - p0, 0, tid - 64 * NMW, k_begin, k_end, np, C::slab, lds);
+        if constexpr (GATHER) {
+            if (job.gather) {
+                tn_loader<TP, C::BPT, D, true>(job.U, job.P, job.P - p0, 0, tid - 64 * NMW, k_begin, k_end, np, C::slab, lds,
+                                               args.g, p0, args.M);
+                return;
+            }
+        }
+        tn_loader<TP, C::BPT, D>(job.U + p0, job.P, job.P - p0, 0, tid - 64 * NMW, k_begin, k_end, np, C::slab, lds);
         return;
     }
 
@@ -359,9 +377,10 @@ size_t tn_partials_bytes(int64_t M, const TnJob* jobs, int njobs, int R) {
 }
 
 namespace {
+// gather != NULL: the LAST job's U is gathered from an image, any job before it is plain
 hipError_t launch_tn_common(const TnJob* jobs, int njobs, int64_t M, int R, int accumulate,
                             float* partials, const Tn2Gather* gather, hipStream_t s) {
-    if (njobs < 1 || njobs > 2 || (gather && njobs != 1)) return hipErrorInvalidValue;
+    if (njobs < 1 || njobs > 2) return hipErrorInvalidValue;
     const int tiles = tn2_total_tiles(jobs, njobs);
     const int splits = tn2_choose_splits(M, tiles);
     Tn2Args args{};
@@ -383,6 +402,7 @@ hipError_t launch_tn_common(const TnJob* jobs, int njobs, int64_t M, int R, int 
         args.job[i].P = jobs[i].P;
         args.job[i].tile_begin = tile_begin;
         args.job[i].transposed = jobs[i].transposed;
+        args.job[i].gather = (gather && i == njobs - 1) ? 1 : 0;
         red.job[i].part = part;
         red.job[i].out = jobs[i].out;
         red.job[i].total = (int64_t)jobs[i].P * R;
@@ -412,15 +432,16 @@ hipError_t launch_tn_bf16(const TnJob* jobs, int njobs, int64_t M, int R, int ac
     return launch_tn_common(jobs, njobs, M, R, accumulate, partials, nullptr, s);
 }
 
-hipError_t launch_tn_gather_bf16(const TnJob& job, const PatchGeom& g, int64_t M, int R, int accumulate,
+hipError_t launch_tn_gather_bf16(const TnJob* jobs, int njobs, const PatchGeom& g, int64_t M, int R, int accumulate,
                                  float* partials, hipStream_t s) {
     // 32-bit offsets inside the window of the image that one slab's patches touch
-    if (g.H < 1 || g.W < 1 || g.Cin < 8 || g.Cin % 8 || g.kh < 1 || g.kw < 1 || !(g.kh & 1) || !(g.kw & 1) ||
-        M % ((int64_t)g.H * g.W) != 0 || job.P != g.kh * g.kw * g.Cin ||
+    if (njobs < 1 || njobs > 2 ||
+        g.H < 1 || g.W < 1 || g.Cin < 8 || g.Cin % 8 || g.kh < 1 || g.kw < 1 || !(g.kh & 1) || !(g.kw & 1) ||
+        M % ((int64_t)g.H * g.W) != 0 || jobs[njobs - 1].P != g.kh * g.kw * g.Cin ||
         ((int64_t)64 + 2 * ((g.kh / 2) * (int64_t)g.W + g.kw / 2)) * g.Cin * 2 >= kBufMaxBytes)
         return hipErrorInvalidValue;
     const Tn2Gather tg{g.H, g.W, g.Cin, g.kh, g.kw};
-    return launch_tn_common(&job, 1, M, R, accumulate, partials, &tg, s);
+    return launch_tn_common(jobs, njobs, M, R, accumulate, partials, &tg, s);
 }
 
 }  // namespace abt

@@ -175,6 +175,36 @@ def test_group_step_validation_and_rebound_factor_without_device(lib):
     assert r(p, p, ctypes.c_void_p(base + 4), 8, 8, 4, null) == -3
 
 
+def test_conv_validation_without_device(lib):
+    buf = ctypes.create_string_buffer(4096 + 256)
+    base = (ctypes.addressof(buf) + 255) // 256 * 256          # fake, aligned, never dereferenced
+    p, null, odd = ctypes.c_void_p(base), ctypes.c_void_p(0), ctypes.c_void_p(base + 2)
+    BF = abt.ABT_BF16
+    good = abt.ConvGeom(2, 14, 14, 256, 3, 3)
+    need = lib.lr_conv_bwd_workspace_bytes(ctypes.byref(good), 256, 64, BF)
+    M = 2 * 14 * 14
+    assert need >= 2 * M * 64 * 2 + 256 * 9 * 64 * 2            # dT, T, the re-laid-out factor
+    assert lib.lr_conv_bwd_workspace_bytes(ctypes.byref(good), 256, 64, abt.ABT_F32) == 0
+    fwd = lambda g, m=256, r=64, dt=BF, act=p, Y=p: lib.lr_conv_fwd(act, p, p, Y, null, ctypes.byref(g), m, r, dt, null)
+    assert fwd(good, dt=abt.ABT_F32) == -5                      # bf16 only
+    assert lib.lr_conv_fwd(p, p, p, p, null, None, 256, 64, BF, null) == -1
+    assert fwd(good, act=null) == -1
+    assert fwd(good, Y=odd) == -3
+    for bad in (abt.ConvGeom(2, 14, 14, 48, 3, 3),              # C not a multiple of 64
+                abt.ConvGeom(2, 14, 14, 256, 2, 3),             # even window
+                abt.ConvGeom(0, 14, 14, 256, 3, 3),
+                abt.ConvGeom(2, 14, 14, 256, 17, 3),
+                abt.ConvGeom(2, 14, 14, 1 << 20, 3, 3),         # kh kw C too wide
+                abt.ConvGeom(1 << 31, 14, 14, 64, 3, 3)):       # too many pixels
+        assert fwd(bad) == -2
+        assert lib.lr_conv_bwd_workspace_bytes(ctypes.byref(bad), 256, 64, BF) == 0
+    assert fwd(good, m=100) == -2 and fwd(good, r=48) == -2 and fwd(good, r=224) == -2 and fwd(good, r=416) == -2
+    bwd = lambda ws, wsb, dY=p: lib.lr_conv_bwd(dY, p, p, p, p, p, p, p, ctypes.byref(good), 256, 64, BF, 0, ws, wsb, null)
+    assert bwd(null, 0) == -4 and bwd(p, need - 1) == -4
+    assert bwd(odd, 1 << 40) == -3
+    assert bwd(p, 1 << 40, dY=null) == -1
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     x = torch.zeros(4, 64, dtype=torch.bfloat16)
