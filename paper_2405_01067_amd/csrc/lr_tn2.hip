@@ -120,41 +120,79 @@ __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int co
     const int reach = GATHER ? (tg.kh / 2) * tg.W + tg.kw / 2 : 0;
     const int64_t span = k_end - k_begin;
     const int rows_in_split = span > 0x7fffffff ? 0x7fffffff : (int)span;
-    // Image coordinates of the first row of each of the thread's blocks, for the slab that block
-    // fetches next.  Slabs are fetched in order (0, 1, 2, ...), 64 rows apart: the coordinates are
-    // carried along with one add-and-wrap per slab instead of two integer divisions.
-    int bx[BPT], by[BPT];
+    // Gather state of each of the thread's blocks for the slab that block fetches next: image
+    // coordinates of its first row, and that row's byte offset (tap shift and channel included).
+    // Slabs are fetched in order (0, 1, 2, ...), 64 rows apart: the state is carried with an
+    // add-and-wrap per slab, no integer division and no descriptor arithmetic in the loop.  One
+    // descriptor serves the whole split: it covers the pixels that the patches of the split's rows
+    // can touch (the host keeps that window below 2 GiB).
+    int bx[BPT], by[BPT], boff[BPT];
     const int step_x = GATHER ? BKM % tg.W : 0, step_y = GATHER ? (BKM / tg.W) % tg.H : 0;
+    const int64_t sp0 = k_begin > reach ? k_begin - reach : 0;
+    int64_t sp1 = k_end + reach;
+    if (sp1 > pixels) sp1 = pixels;
+    const rsrc_t gres = make_rsrc(src + sp0 * tg.C, GATHER ? (sp1 - sp0) * tg.C * 2 : 0);
 #pragma unroll
     for (int b = 0; b < BPT; ++b) {
         const int64_t first = k_begin + 8 * rg0 + 32 * b;
         bx[b] = GATHER ? (int)(first % tg.W) : 0;
         by[b] = GATHER ? (int)((first / tg.W) % tg.H) : 0;
+        boff[b] = (((int)(first - sp0) + gdy * tg.W + gdx) * tg.C + gc) * 2;
     }
     auto load_block_gather = [&](u32x4 (&dst)[8], int s, int b) {
-        // the descriptor covers the pixels that the patches of this slab's 64 rows can touch
-        const int64_t kr0 = k_begin + (int64_t)s * BKM;
-        const int64_t bp = kr0 > reach ? kr0 - reach : 0;
-        int64_t ep = kr0 + BKM + reach;
-        if (ep > pixels) ep = pixels;
-        const rsrc_t res = make_rsrc(src + bp * tg.C, (ep - bp) * tg.C * 2);
-        const int rel = s * BKM + 8 * rg0 + 32 * b;                    // first row of the block, from k_begin
-        int x = bx[b], y = by[b];
+        const int x = bx[b], y = by[b], off = boff[b];
         // advance to the next slab (this lambda is called once per slab and block, in slab order)
+        boff[b] += BKM * tg.C * 2;
         bx[b] += step_x;
         const int carry = bx[b] >= tg.W ? 1 : 0;
         bx[b] -= carry ? tg.W : 0;
         by[b] += step_y + carry;
         by[b] -= by[b] >= tg.H ? tg.H : 0;
-        const int left = rows_in_split - rel;                          // rows e < left are inside the split
-        int off = (((int)(kr0 - bp) + 8 * rg0 + 32 * b + gdy * tg.W + gdx) * tg.C + gc) * 2;
+        const int left = rows_in_split - (s * BKM + 8 * rg0 + 32 * b);   // rows e < left are inside the split
+        if (tg.W >= 4) {
+            // Eight consecutive pixels cross at most one image-row boundary (two when W < 8), the
+            // first after `ew` of them.  Rows between two boundaries share y, and among them the rows
+            // whose shifted x stays inside the image form one interval: the valid rows are two
+            // (three) intervals of [0, 8), built as a bit mask with a few operations per slab instead
+            // of a chain of compares per row (a loader wave has no second wave on its SIMD to hide
+            // instruction latencies behind, so its instruction count is its time).
+            auto bits = [](int a, int b) -> unsigned {       // bits a .. b-1, clamped to [0, 8)
+                a = a < 0 ? 0 : a;
+                b = b > 8 ? 8 : b;
+                return b > a ? (1u << b) - (1u << a) : 0u;
+            };
+            const int ew = tg.W - x;                          // first row (of 8) on the next image row
+            const int y1 = y + 1 == tg.H ? 0 : y + 1;
+            const bool vy0 = (unsigned)(y + gdy) < (unsigned)tg.H, vy1 = (unsigned)(y1 + gdy) < (unsigned)tg.H;
+            const int ewc = ew < 8 ? ew : 8;
+            const int lo0 = -gdx - x, hi0 = tg.W - gdx - x;
+            unsigned mask = vy0 ? bits(lo0, hi0 < ewc ? hi0 : ewc) : 0u;
+            const int lo1 = ew - gdx > ew ? ew - gdx : ew;
+            const int ew2 = ew + tg.W;                        // second boundary (inside the block only if W < 8)
+            const int hi1 = ew - gdx + tg.W;
+            mask |= vy1 ? bits(lo1, hi1 < ew2 ? hi1 : ew2) : 0u;
+            if (tg.W < 8) {
+                const int y2 = y1 + 1 == tg.H ? 0 : y1 + 1;
+                const bool vy2 = (unsigned)(y2 + gdy) < (unsigned)tg.H;
+                const int lo2 = ew2 - gdx > ew2 ? ew2 - gdx : ew2;
+                mask |= vy2 ? bits(lo2, ew2 - gdx + tg.W) : 0u;
+            }
+            mask &= bits(0, left);
+            mask = colok ? mask : 0u;
+            const int pitch2 = tg.C * 2;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const bool ok = colok && e < left && (unsigned)(y + gdy) < (unsigned)tg.H &&
-                            (unsigned)(x + gdx) < (unsigned)tg.W;
-            dst[e] = buf_load16(res, ok ? off : kBufNowhere, 0);
-            off += tg.C * 2;
-            if (++x == tg.W) { x = 0; if (++y == tg.H) y = 0; }
+            for (int e = 0; e < 8; ++e)
+                dst[e] = buf_load16(gres, (mask >> e) & 1u ? off + e * pitch2 : kBufNowhere, 0);
+        } else {
+            int xx = x, yy = y, o = off;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const bool ok = colok && e < left && (unsigned)(yy + gdy) < (unsigned)tg.H &&
+                                (unsigned)(xx + gdx) < (unsigned)tg.W;
+                dst[e] = buf_load16(gres, ok ? o : kBufNowhere, 0);
+                o += tg.C * 2;
+                if (++xx == tg.W) { xx = 0; if (++yy == tg.H) yy = 0; }
+            }
         }
     };
     auto fetch = [&](u32x4 (&dst)[8], rsrc_t res, int s, int b) {
@@ -440,6 +478,14 @@ hipError_t launch_tn_gather_bf16(const TnJob* jobs, int njobs, const PatchGeom& 
         M % ((int64_t)g.H * g.W) != 0 || jobs[njobs - 1].P != g.kh * g.kw * g.Cin ||
         ((int64_t)64 + 2 * ((g.kh / 2) * (int64_t)g.W + g.kw / 2)) * g.Cin * 2 >= kBufMaxBytes)
         return hipErrorInvalidValue;
+    // one descriptor per row split: its window of the image (the split's rows, the reach of the
+    // window on both sides, the padded slabs of the loaders' ring) must stay below 2 GiB
+    {
+        const int splits = tn2_choose_splits(M, tn2_total_tiles(jobs, njobs));
+        const int64_t rps = ceil_div(ceil_div(M, splits), 64) * 64;
+        const int64_t reach = (g.kh / 2) * (int64_t)g.W + g.kw / 2;
+        if ((rps + 2 * reach + 64 * 8) * g.Cin * 2 >= kBufMaxBytes) return hipErrorInvalidValue;
+    }
     const Tn2Gather tg{g.H, g.W, g.Cin, g.kh, g.kw};
     return launch_tn_common(jobs, njobs, M, R, accumulate, partials, &tg, s);
 }
