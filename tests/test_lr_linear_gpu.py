@@ -231,3 +231,52 @@ def test_config4_full_size_sampled(case):
     c = gen.lr_case(M, m, n, r, seed, relu_x=True)
     errs = sampled_check(c, TOL_BF16, seed=seed)
     print(name, errs)
+
+
+# ------------------------------------------------------------------ HIP graph capture
+
+def test_step_replays_from_a_captured_graph():
+    # The step only enqueues kernels on the caller's stream (no allocation, no synchronisation, no
+    # memset), so a caller may capture it once and replay it.  Every replay, with the program's own
+    # eager work and synchronisations in between and fresh inputs copied into the captured buffers,
+    # must reproduce the eager result bit for bit.
+    M, m, n, r = 1000, 256, 192, 96
+    cases = [gen.lr_case(M=M, m=m, n=n, r=r, seed=600 + i) for i in range(3)]
+    bf = torch.bfloat16
+    X, dY, A, B = (torch.empty(s, dtype=bf, device="cuda:0") for s in ((M, n), (M, m), (m, r), (r, n)))
+    Y = torch.empty((M, m), dtype=bf, device="cuda:0")
+    T = torch.empty((M, r), dtype=bf, device="cuda:0")
+    dX = torch.empty((M, n), dtype=bf, device="cuda:0")
+    dA = torch.empty((m, r), dtype=torch.float32, device="cuda:0")
+    dB = torch.empty((r, n), dtype=torch.float32, device="cuda:0")
+    ws = torch.empty(abt.load().lr_linear_bwd_workspace_bytes(M, m, n, r, abt.ABT_BF16), dtype=torch.uint8, device="cuda:0")
+
+    def load_case(c):
+        for dst, key in ((X, "X"), (dY, "dY"), (A, "A"), (B, "B")):
+            dst.copy_(dev(c[key], bf))
+
+    def step():
+        abt.lr_linear_fwd(X, A, B, save_T=True, Y=Y, T=T, workspace=ws)
+        abt.lr_linear_bwd(dY, X, T, A, B, dX=dX, dA=dA, dB=dB, workspace=ws)
+
+    eager = []
+    for c in cases:                      # eager results (also the warm-up that sets kernel attributes)
+        load_case(c)
+        step()
+        torch.cuda.synchronize()
+        eager.append([t.clone() for t in (Y, T, dX, dA, dB)])
+    graph = torch.cuda.CUDAGraph()
+    load_case(cases[0])
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(2):
+        for c, want in zip(cases, eager):
+            load_case(c)
+            for t in (Y, T, dX, dA, dB):
+                t.fill_(7.0)             # eager work between the replays; stale results must not survive
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for got, ref in zip((Y, T, dX, dA, dB), want):
+                assert torch.equal(got, ref)
