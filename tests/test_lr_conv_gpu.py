@@ -60,6 +60,8 @@ CASES = [
     (1, 8, 8, 512, 64, 32, 3, 3),      # activation gradient in two blocks of 256 channels
     (4, 3, 2, 64, 64, 384, 3, 3),      # widest rank; image narrower than the window
     (37, 14, 14, 64, 256, 64, 3, 3),   # 7252 pixels: several row splits of the factor gradients
+    (8, 56, 56, 64, 64, 32, 3, 3),     # ResNet-50's widest feature map: a patch reaches 57 pixels, nearly a row block
+    (2, 5, 40, 128, 128, 128, 7, 7),   # 7 x 7 window: taller than the image, reach 123 pixels
 ]
 
 
