@@ -276,6 +276,12 @@ int lr_conv_bwd(const void* dY, const void* act, const void* T, const void* A, c
 
 size_t lr_conv_bwd_workspace_bytes(const abt_conv_geom* geom, int64_t m, int64_t r, int dtype);
 
+/* Work-group height of the bf16 chain kernel (T = X B^T, Y = T A^T and the dT / dX half of the
+ * backward): 0 = chosen from the batch size (default), 64 or 128 = forced where the rank allows it.
+ * A tuning and test switch; the results do not depend on it beyond fp32 summation order.  Other
+ * values are ignored.  Returns the previous setting. */
+int abt_set_chain_rows(int rows);
+
 /* Sweep cap of the Jacobi SVD (default 30, clamped to [1, 64]; sweeps stop as soon as every layer
  * has converged: 8-9 for the 384-wide cores of config 5, about 15 for dense 768-wide weights);
  * returns the previous value. */

@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "lib
 _lib = None
 
 EXPORTS = (
-    "abt_status_string", "abt_set_jacobi_max_sweeps",
+    "abt_status_string", "abt_set_jacobi_max_sweeps", "abt_set_chain_rows",
     "lr_linear_fwd", "lr_linear_fwd_workspace_bytes",
     "lr_linear_bwd", "lr_linear_bwd_workspace_bytes",
     "ab_merge", "ab_merge_workspace_bytes",
@@ -80,6 +80,8 @@ def load():
     i64, vp, sz, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
     lib.abt_status_string.restype = ctypes.c_char_p
     lib.abt_status_string.argtypes = [ci]
+    lib.abt_set_chain_rows.restype = ci
+    lib.abt_set_chain_rows.argtypes = [ci]
     lib.abt_set_jacobi_max_sweeps.restype = ci
     lib.abt_set_jacobi_max_sweeps.argtypes = [ci]
     lib.lr_linear_fwd.restype = ci
@@ -135,6 +137,11 @@ def status_string(code: int) -> str:
 def _check(code: int, what: str):
     if code != 0:
         raise AbtError(f"{what} failed: {status_string(code)} ({code})")
+
+
+def set_chain_rows(rows: int) -> int:
+    """Force the chain kernel's work-group height (64 or 128; 0 = automatic); returns the previous setting."""
+    return load().abt_set_chain_rows(int(rows))
 
 
 def set_jacobi_max_sweeps(n: int) -> int:

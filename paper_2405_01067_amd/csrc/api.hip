@@ -11,10 +11,17 @@ namespace {
 
 int g_max_sweeps = 30;
 
-// Chain kernel choice: the 64-row kernel with loader and MFMA waves wherever it supports the rank
-// (32, 64, 96, 128, 160, 192, 256, 320, 384), else the older 128-row kernel (224, 288, 352).
+// Chain kernel choice: for large batches the 128-row kernel where it supports the rank (32, 64, 96,
+// 128, 192); else the 64-row kernel with loader and MFMA waves wherever that supports the rank
+// (32, 64, 96, 128, 160, 192, 256, 320, 384), else the older kernel (224, 288, 352).
+int g_chain_rows = 0;   // 0: automatic; 64 or 128: force that work-group height where the rank allows it
+
 hipError_t chain(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                  int64_t M, int p, int q, int R, hipStream_t s) {
+    // 128-row work-groups take about 1.3 times as long as 64-row ones and there are half as many:
+    // they win as soon as the 64-row grid needs more than one round of the 256 compute units
+    const bool tall = g_chain_rows == 128 || (g_chain_rows == 0 && ceil_div(M, 64) > 256);
+    if (tall && chain3_supports(R, p, q)) return launch_chain3_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
     if (chain2_supports(R, p, q)) return launch_chain2_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
     return launch_chain_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
 }
@@ -275,6 +282,12 @@ int ab_reconstruct(const float* A, const float* B, float* W,
     if (!aligned(A, 16) || !aligned(B, 16) || !aligned(W, 16)) return ABT_EALIGN;
     return launch_gemm_f32_one(gemm(A, B, W, m, n, k, k, n, n, 0, 0, 0), (hipStream_t)stream) == hipSuccess
                ? ABT_OK : ABT_EHIP;
+}
+
+int abt_set_chain_rows(int rows) {
+    const int prev = g_chain_rows;
+    if (rows == 0 || rows == 64 || rows == 128) g_chain_rows = rows;
+    return prev;
 }
 
 int abt_set_jacobi_max_sweeps(int max_sweeps) {

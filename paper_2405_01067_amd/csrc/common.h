@@ -61,6 +61,11 @@ hipError_t launch_chain_bf16(const void* Xin, const void* P, const void* Q, void
 bool chain2_supports(int R, int p, int q);
 hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                               int64_t M, int p, int q, int R, hipStream_t s);
+// The same chain with 128-row work-groups (eight MFMA waves in two row groups fed by four loader
+// waves): every slab of a factor serves twice the rows.  For large M; R in {32, 64, 96, 128, 192}.
+bool chain3_supports(int R, int p, int q);
+hipError_t launch_chain3_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
+                              int64_t M, int p, int q, int R, hipStream_t s);
 // The same chain with the first operand gathered from a channels-last image [M / (H W), H, W, Cin]
 // instead of read from a matrix: row i of the virtual operand is the kh x kw patch around pixel i
 // (zero outside the image), columns ordered (tap, channel) with every tap padded to a multiple of

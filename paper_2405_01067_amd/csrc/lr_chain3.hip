@@ -1,0 +1,628 @@
+// Chain kernel, 128-row work-groups:  Tout[M,R] = Xin[M,p] . P[R,p]^T  then  Yout[M,q] = Tout . Q[q,R]^T
+// (bf16 in, fp32 accumulate): the variant of the 64-row chain kernel for large batches.
+//
+// A 64-row work-group's time is set by streaming the two factors through LDS, not by its rows: the
+// loader waves are busy for about 1650 cycles per 128 rows of Q while the MFMA waves need 768.  Here a
+// work-group owns 128 rows as two row groups of 64: eight MFMA waves, four per row group, each group
+// working exactly as the four MFMA waves of the 64-row kernel do, on its own rows of the Xin part of
+// a slab, its own reduction scratch, T tile and output staging tiles, while both groups read the
+// same P and Q slabs.  Four loader waves feed them.  Every slab of a factor now serves twice the
+// rows; twelve waves leave 168 registers per lane, so the register rings are shallower and a
+// stage-2 slab holds at most 96 contraction columns (two slabs per output tile for R = 192), which
+// also keeps four staging tiles plus two slab slots inside the 160 KB of LDS.
+// Everything else (slab layouts, swizzles, barrier discipline, buffer addressing, slab rotation)
+// is the 64-row kernel's; see lr_chain2.hip for the reasoning.
+#include "common.h"
+
+// Phase timing for tuning, compiled out of the library: with -DABT_TIMING, wave 0 (role 0, an MFMA
+// wave) and wave 4 (role 1, a loader wave) of work-group 5 record the cycle counter at the marked
+// points into abt_tbuf (once per launch) and abt_tl (per slab of stage 2); a test program that
+// includes this file reads them back with hipMemcpyFromSymbol.
+#ifdef ABT_TIMING
+__device__ long long abt_tbuf[2][64];
+#define TMARK(role, i) do { if (blockIdx.x == 5 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 4 : 0)) abt_tbuf[role][i] = __builtin_readcyclecounter(); } while (0)
+__device__ long long abt_tl[2][4][32];
+#define TSTAMP(role, k, it) do { if (blockIdx.x == 5 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 4 : 0) && (it) < 32) abt_tl[role][k][it] = __builtin_readcyclecounter(); } while (0)
+#else
+#define TMARK(role, i) do {} while (0)
+#define TSTAMP(role, k, it) do {} while (0)
+#endif
+
+namespace abt {
+
+namespace {
+
+__device__ __forceinline__ bf16x8 as_bf(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ f32x16 mfma16(u32x4 a, u32x4 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(a), as_bf(b), c, 0, 0, 0);
+}
+
+// The only barrier used in this kernel (both roles execute the same sequence of them): this wave's
+// LDS traffic has completed, then s_barrier.  Deliberately not __syncthreads(): that also drains
+// outstanding global loads, which are exactly the prefetches that must stay in flight.
+__device__ __forceinline__ void wg_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// chunk swizzle for rows of CPR 16-byte chunks: XOR the low bits of the chunk index with row bits
+// chosen so that 16 consecutive rows, same logical chunk, hit 16 different 16-byte bank groups.
+template <int CPR>
+__device__ __forceinline__ int swz(int chunk, int row) {
+    if constexpr (CPR % 16 == 0) return chunk ^ (row & 15);
+    else if constexpr (CPR % 8 == 0) return chunk ^ ((row >> 1) & 7);
+    else return chunk ^ ((row >> 2) & 3);
+}
+
+// Work split of the four MFMA waves in stage 1: RS row groups x CS column groups x KS contraction
+// groups (product 4).  Splitting the rows (RS = 2) would need no partial sums, but every wave then
+// reads more operands from LDS per MFMA, and LDS bandwidth (shared with the loaders' stores) is
+// what limits stage 1: measured slower than contraction groups plus a tree reduction.
+template <int R> struct Ch2;
+template <> struct Ch2<32>  { static constexpr int RS = 1, CS = 1, KS = 4; };
+template <> struct Ch2<64>  { static constexpr int RS = 1, CS = 1, KS = 4; };
+template <> struct Ch2<96>  { static constexpr int RS = 1, CS = 1, KS = 4; };
+template <> struct Ch2<128> { static constexpr int RS = 1, CS = 2, KS = 2; };
+template <> struct Ch2<160> { static constexpr int RS = 1, CS = 1, KS = 4; };
+template <> struct Ch2<192> { static constexpr int RS = 1, CS = 2, KS = 2; };
+template <> struct Ch2<256> { static constexpr int RS = 1, CS = 2, KS = 2; };
+template <> struct Ch2<320> { static constexpr int RS = 1, CS = 2, KS = 2; };
+template <> struct Ch2<384> { static constexpr int RS = 1, CS = 4, KS = 1; };
+
+constexpr int NMW = 8, NLW = 4;                 // MFMA waves (two row groups of four), loader waves
+constexpr int NMW_ = 4;                         // MFMA waves per row group
+constexpr int ROWS = 128;                       // rows per work-group
+constexpr int NMT = 64 * NMW, NLT = 64 * NLW;   // threads per role
+constexpr int NT = NMT + NLT;
+constexpr int BK1 = 64, CPR1 = BK1 / 8;         // stage-1 slab: 64 contraction columns
+constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v / 2); }
+constexpr int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+constexpr int gcdi(int a, int b) { return b == 0 ? a : gcdi(b, a % b); }
+
+template <int R>
+struct Ch2Cfg {
+    using C = Ch2<R>;
+    static constexpr int CB = R / 32 / C::CS;                 // column blocks per wave
+    static constexpr int RA = 2 / C::RS;                      // row blocks per wave
+    static constexpr int SPW = BK1 / (16 * C::KS);            // k16 steps per wave per slab
+    static constexpr int xpart = ROWS * BK1 * 2;              // slot = [128 rows of Xin][R rows of P]
+    static constexpr int slab1 = (ROWS + R) * BK1 * 2;
+    static constexpr int NCHX = ROWS * CPR1 / NLT;            // 16-byte chunks per loader thread (Xin part) = 4
+    static constexpr int NCHP = R * CPR1 / NLT;               // chunks per loader thread (P part) = R / 32
+    static constexpr int D1 = clampi(30 / (NCHX + NCHP), 2, 4);   // stage-1 slabs in flight (register ring depth)
+    // stage 2: a slab is 128 rows of Q times BK2 = R / KSL columns
+    static constexpr int KSL = R <= 128 ? 1 : R / 96;         // at most 96 contraction columns per slab beyond R = 128
+    static constexpr int BK2 = R / KSL, CPR2 = BK2 / 8;
+    static constexpr int slab2 = 128 * BK2 * 2;
+    static constexpr int NCHQ = 128 * CPR2 / NLT;             // chunks per loader thread = BK2 / 16
+    static constexpr int D2 = clampi(20 / NCHQ, 2, 4);        // stage-2 slabs in flight
+    static constexpr int U2 = D2 * KSL / gcdi(D2, KSL);       // stage-2 trip count is padded to a multiple of this
+    static constexpr int ypitch = 128 * 2 + 16;
+    static constexpr int ytile = 64 * ypitch;
+    static constexpr int red = (C::KS / 2) * C::CS * C::RS * RA * CB * 4096;   // first (largest) round of the tree
+    static constexpr int tpitch = R * 2 + 16;
+    static constexpr int ttile = 64 * tpitch;
+    static constexpr int a = 2 * slab1, b = 2 * (red + ttile), c = 2 * slab2 + 4 * ytile;   // per row group: red, ttile, two ytiles
+    static constexpr int lds_bytes = a > b ? (a > c ? a : c) : (b > c ? b : c);
+    static constexpr int n_mid_barriers = C::KS > 1 ? 2 * ilog2(C::KS) : 1;  // tree + T tile written
+    static_assert(SPW >= 1 && NCHX == 4 && R % 32 == 0 && BK2 % 16 == 0 && R % KSL == 0, "slab shape");
+    static_assert(C::RS * C::CS * C::KS == NMW_ && CB * C::CS * 32 == R && RA * C::RS == 2, "wave split");
+};
+
+// Gather form of the Xin operand (GATHER = true): Xin is not a matrix but a channels-last image
+// [pixels / (H W), H, W, Cin], and row i of the virtual matrix is the patch around pixel i: virtual
+// column (tap, block, c) with tap = ky kw + kx, `cpb` 64-column blocks per tap, reads channel
+// 64 block + c of pixel (y + sign (ky - kh/2), x + sign (kx - kw/2)) of the same image, zero outside
+// the image and for channels >= Cin.  A slab of 64 contraction columns is then one tap and one
+// channel block: 128 contiguous bytes per row, as in the plain case.  p = kh kw cpb 64.
+struct Ch2Gather { int H, W, Cin, cpb, kh, kw, sign; };
+
+template <int R, bool GATHER>
+__global__ __launch_bounds__(NT) void chain3_bf16_kernel(const uint16_t* __restrict__ Xin,
+                                                         const uint16_t* __restrict__ Pm,
+                                                         const uint16_t* __restrict__ Qm,
+                                                         uint16_t* __restrict__ Yout,
+                                                         uint16_t* __restrict__ Tout,
+                                                         int64_t M, int p, int q, int t_pitch, Ch2Gather gg) {
+    extern __shared__ __align__(1024) unsigned char lds[];
+    using C = Ch2<R>;
+    using L = Ch2Cfg<R>;
+    constexpr int RS = C::RS, CS = C::CS, KS = C::KS, CB = L::CB, RA = L::RA, SPW = L::SPW;
+    constexpr int BK2 = L::BK2, CPR2 = L::CPR2, KSL = L::KSL;
+    constexpr int D1 = L::D1, D2 = L::D2;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row0 = (int64_t)blockIdx.x * ROWS;
+    const int ns1 = p / BK1;
+    const int n1p = (ns1 + D1 - 1) / D1 * D1;           // stage-1 trip count, padded to the loaders' ring
+    const int ntile = (q + 127) / 128;                  // stage-2 output tiles of 128 columns
+    const int ns2 = ntile * KSL;
+    const int n2p = (ns2 + L::U2 - 1) / L::U2 * L::U2;  // stage-2 trip count, padded likewise
+    // per row group g: reduction scratch at g * red, T tile at 2 * red + g * ttile (stage 1 and T phase);
+    // output staging tile (g, buffer) at 2 * slab2 + (2 g + buffer) * ytile (stage 2)
+    unsigned char* const ttile = lds + 2 * L::red;
+    unsigned char* const ytile = lds + 2 * L::slab2;
+    // Work-groups walk the contraction slabs (stage 1) and the output tiles (stage 2) from
+    // different starting points, so that at any instant they touch different columns of
+    // Xin / Yout and different rows of the factors.
+    const int rot1 = (int)(blockIdx.x % (unsigned)ns1);
+    const int rot2 = (int)(blockIdx.x % (unsigned)ntile);
+    auto slab1_of = [&](int s) { if (s > ns1 - 1) s = ns1 - 1; s += rot1; return s >= ns1 ? s - ns1 : s; };
+    auto tile_of = [&](int t) { if (t > ntile - 1) t = ntile - 1; t += rot2; return t >= ntile ? t - ntile : t; };
+
+    if (wave >= NMW) {
+        // ================================================================== loader waves
+        // Every global access here is a buffer instruction: a wave-uniform descriptor and scalar
+        // offset plus one 32-bit offset per lane.  Loads addressed by 64-bit per-lane pointers issue
+        // at little more than half the rate while the MFMA waves on the same SIMDs are busy; buffer
+        // loads do not slow down.  The descriptors cover exactly this work-group's valid rows and the
+        // row offset is part of the per-lane offset (the only part the hardware range-checks), so
+        // rows past M read as zeros and stores to them are dropped.
+        const int lt = tid - NMT;
+        const int64_t rows_valid = M - row0 < ROWS ? M - row0 : ROWS;
+        // gather: the descriptor covers the pixels this work-group's patches can touch
+        const int reach = GATHER ? (gg.kh / 2) * gg.W + gg.kw / 2 : 0;
+        const int64_t gpix0 = row0 > reach ? row0 - reach : 0;
+        const int64_t gpix1 = row0 + ROWS + reach < M ? row0 + ROWS + reach : M;
+        const rsrc_t xres = GATHER ? make_rsrc(Xin + gpix0 * gg.Cin, (gpix1 - gpix0) * gg.Cin * 2)
+                                   : make_rsrc(Xin + row0 * p, rows_valid * p * 2);
+        const rsrc_t pres = make_rsrc(Pm, (int64_t)R * p * 2);
+        // stage-2 chunk assignment (computed first: the first Q slabs are requested before stage 1's
+        // epilogue so that their latency hides behind the reduction and the T tile)
+        int qoff[L::NCHQ], qsrc[L::NCHQ];
+#pragma unroll
+        for (int e = 0; e < L::NCHQ; ++e) {
+            const int ci = e * NLT + lt;
+            const int row = ci / CPR2, ch = ci % CPR2;
+            qsrc[e] = (row * R + ch * 8) * 2;
+            qoff[e] = row * (BK2 * 2) + swz<CPR2>(ch, row) * 16;
+        }
+        {
+            // stage 1: one ring entry = this thread's chunks of one slab (64 rows of Xin, then the R
+            // rows of P), D1 slabs ahead
+            int xsrc[L::NCHX], off[L::NCHX];
+            int gy[L::NCHX], gx[L::NCHX];                // gather: image coordinates of the thread's rows
+#pragma unroll
+            for (int e = 0; e < L::NCHX; ++e) {
+                const int ci = e * NLT + lt;
+                const int row = ci / CPR1, ch = ci % CPR1;
+                off[e] = row * (BK1 * 2) + swz<CPR1>(ch, row) * 16;
+                if constexpr (GATHER) {
+                    const int64_t pix = row0 + row;
+                    gx[e] = (int)(pix % gg.W);
+                    gy[e] = pix < M ? (int)((pix / gg.W) % gg.H) : -(1 << 20);   // rows past M: never valid
+                    xsrc[e] = ((int)(pix - gpix0) * gg.Cin + ch * 8) * 2;
+                } else {
+                    gx[e] = gy[e] = 0;
+                    xsrc[e] = (row * p + ch * 8) * 2;
+                }
+            }
+            // per-lane and wave-uniform offset of chunk e of (virtual) slab vs
+            auto xaddr = [&](int e, int vs, int& voff, int& soff) {
+                if constexpr (GATHER) {
+                    const int tap = vs / gg.cpb, cb = vs - tap * gg.cpb;
+                    const int ky = tap / gg.kw, kx = tap - ky * gg.kw;
+                    const int dy = gg.sign * (ky - gg.kh / 2), dx = gg.sign * (kx - gg.kw / 2);
+                    const int ch8 = (lt % CPR1) * 8;
+                    const bool ok = (unsigned)(gy[e] + dy) < (unsigned)gg.H && (unsigned)(gx[e] + dx) < (unsigned)gg.W &&
+                                    cb * 64 + ch8 < gg.Cin;
+                    voff = ok ? xsrc[e] + ((dy * gg.W + dx) * gg.Cin + cb * 64) * 2 : kBufNowhere;
+                    soff = 0;
+                } else {
+                    voff = xsrc[e];
+                    soff = vs * (BK1 * 2);
+                }
+            };
+            // P chunk e of this thread: row 32 e + lt / 8, chunk lt % 8
+            const int prow0 = lt / CPR1, pch = lt % CPR1;
+            const int psrc = (prow0 * p + pch * 8) * 2;
+            const int pstep = (NLT / CPR1) * p * 2;      // 32 rows of P, in bytes
+            int poff[L::NCHP];
+#pragma unroll
+            for (int e = 0; e < L::NCHP; ++e) {
+                const int row = e * (NLT / CPR1) + prow0;
+                poff[e] = L::xpart + row * (BK1 * 2) + swz<CPR1>(pch, row) * 16;
+            }
+            u32x4 ring[D1][L::NCHX + L::NCHP];
+            auto load = [&](u32x4 (&dst)[L::NCHX + L::NCHP], int s) {
+                const int vs = slab1_of(s);
+                const int so = vs * (BK1 * 2);
+#pragma unroll
+                for (int e = 0; e < L::NCHX; ++e) {
+                    int vo, xo;
+                    xaddr(e, vs, vo, xo);
+                    dst[e] = buf_load16(xres, vo, xo);
+                }
+#pragma unroll
+                for (int e = 0; e < L::NCHP; ++e) dst[L::NCHX + e] = buf_load16(pres, psrc, so + e * pstep);
+            };
+            auto store = [&](const u32x4 (&srcv)[L::NCHX + L::NCHP], int slot) {
+#pragma unroll
+                for (int e = 0; e < L::NCHX; ++e) *reinterpret_cast<u32x4*>(lds + slot * L::slab1 + off[e]) = srcv[e];
+#pragma unroll
+                for (int e = 0; e < L::NCHP; ++e)
+                    *reinterpret_cast<u32x4*>(lds + slot * L::slab1 + poff[e]) = srcv[L::NCHX + e];
+            };
+            // steady state: chunk e of slab s+1 goes to LDS (slot s&1 is being read) and the same
+            // chunk of slab s+1+D1 is requested, alternating: the LDS port and the vector-memory
+            // address path then both stay busy instead of taking turns
+            auto step1 = [&](u32x4 (&rg)[L::NCHX + L::NCHP], int s) {
+                const int slot = (s + 1) & 1;
+                const int vs = slab1_of(s + 1 + D1);
+                const int so = vs * (BK1 * 2);
+#pragma unroll
+                for (int e = 0; e < L::NCHX; ++e) {
+                    int vo, xo;
+                    xaddr(e, vs, vo, xo);
+                    *reinterpret_cast<u32x4*>(lds + slot * L::slab1 + off[e]) = rg[e];
+                    rg[e] = buf_load16(xres, vo, xo);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int e = 0; e < L::NCHP; ++e) {
+                    *reinterpret_cast<u32x4*>(lds + slot * L::slab1 + poff[e]) = rg[L::NCHX + e];
+                    rg[L::NCHX + e] = buf_load16(pres, psrc, so + e * pstep);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            // all D1 slabs are requested before the first one is waited for
+#pragma unroll
+            for (int d = 0; d < D1; ++d) load(ring[d], d);
+            store(ring[0], 0);
+            load(ring[0], D1);
+            TMARK(1, 0);
+            wg_barrier();                                   // slab 0 is in slot 0
+            for (int s0 = 0; s0 < n1p; s0 += D1) {
+#pragma unroll
+                for (int d = 0; d < D1; ++d) {
+                    step1(ring[(d + 1) % D1], s0 + d);
+                    wg_barrier();
+                }
+            }
+            TMARK(1, 1);
+        }
+        // stage-2 ring: D2 slabs of Q in flight.  The descriptor is rebuilt per slab (scalar work) to
+        // cover exactly the tile's rows: the wave-uniform offset of a buffer access is not range
+        // checked, only the per-lane part is.  Rows of a ragged last tile that lie past the end of Q
+        // then read as zeros; their output columns are never stored.
+        u32x4 ring2[D2][L::NCHQ];
+        auto load_q = [&](u32x4 (&dst)[L::NCHQ], int s) {
+            if (s > ns2 - 1) s = ns2 - 1;
+            const int t = tile_of(s / KSL);
+            const int rows = q - t * 128 < 128 ? q - t * 128 : 128;
+            const rsrc_t qres = make_rsrc(Qm + (int64_t)t * 128 * R, (int64_t)rows * R * 2);
+            const int so = (s % KSL) * BK2 * 2;
+#pragma unroll
+            for (int e = 0; e < L::NCHQ; ++e) dst[e] = buf_load16(qres, qsrc[e], so);
+        };
+        // The first D2 slabs of Q are requested around the barriers of the T phase, one slab per
+        // barrier and the rest after the last: requesting them all first would hold the MFMA waves
+        // at the first of those barriers for as long as the requests take to issue.
+#pragma unroll
+        for (int i = 0; i <= L::n_mid_barriers; ++i) {
+            if (Yout != nullptr) {
+#pragma unroll
+                for (int d = 0; d < D2; ++d)
+                    if ((d < L::n_mid_barriers ? d : L::n_mid_barriers) == i) load_q(ring2[d], d);
+            }
+            if (i < L::n_mid_barriers) wg_barrier();
+        }
+        // T tile is in LDS: store it (the MFMA waves load their operands from it meanwhile)
+        if (Tout != nullptr) {
+            // rows of Tout are t_pitch elements apart (R for a plain T; more when the tile is a
+            // column block of a wider matrix); the descriptor ends with the last valid row
+            const rsrc_t tres = make_rsrc(Tout + row0 * t_pitch, ((rows_valid - 1) * t_pitch + R) * 2);
+            constexpr int CPT = R / 8;   // 16-byte chunks per T row
+            for (int i = lt; i < ROWS * CPT; i += NLT) {
+                const int row = i / CPT, ch = i % CPT;
+                buf_store16(*reinterpret_cast<const u32x4*>(ttile + (row >> 6) * L::ttile + (row & 63) * L::tpitch + ch * 16),
+                            tres, (row * t_pitch + ch * 8) * 2, 0);
+            }
+        }
+        if (Yout == nullptr) return;
+        const rsrc_t yres = make_rsrc(Yout + row0 * q, rows_valid * q * 2);
+        wg_barrier();                                    // T tile consumed: LDS belongs to stage 2
+#pragma unroll
+        for (int e = 0; e < L::NCHQ; ++e) *reinterpret_cast<u32x4*>(lds + qoff[e]) = ring2[0][e];
+        load_q(ring2[0], D2);
+        wg_barrier();                                    // Q slab 0 is in slot 0
+        // stage 2: the Q slabs, and the finished output tiles: tile t was staged in LDS by the MFMA
+        // waves during the last slab of t and leaves here, one slab later, as full 256-byte rows, in
+        // four pieces per thread (64 rows x 16 chunks over 256 threads): the LDS reads are issued
+        // first, the stores are spread between the slab's loads.
+        constexpr int NY = ROWS * 16 / NLT;              // 16-byte pieces of a 128 x 128 tile per thread = 8
+        u32x4 ypiece[NY];
+        int ydst[NY];
+        bool yleft[NY];
+#pragma unroll
+        for (int e = 0; e < NY; ++e) {
+            const int ci = e * NLT + lt;
+            ydst[e] = ((ci >> 4) * q + (ci & 15) * 8) * 2;
+            yleft[e] = (ci & 15) < 8;                    // in the left 64 columns: all a ragged last tile has
+        }
+        auto flush_read = [&](int seq) {
+#pragma unroll
+            for (int e = 0; e < NY; ++e) {
+                const int ci = e * NLT + lt;
+                const int r = ci >> 4;
+                const unsigned char* yt = ytile + ((r >> 6) * 2 + (seq & 1)) * L::ytile;
+                ypiece[e] = *reinterpret_cast<const u32x4*>(yt + (r & 63) * L::ypitch + (ci & 15) * 16);
+            }
+        };
+        auto flush_store = [&](int seq, int e) {
+            const int t = tile_of(seq);
+            const bool whole = q - t * 128 >= 128;
+            if (whole || yleft[e]) buf_store16(ypiece[e], yres, ydst[e], t * 256);
+        };
+        auto step2 = [&](u32x4 (&rg)[L::NCHQ], int s, bool flush, int seq) {
+            const int slot = (s + 1) & 1;
+            int sn = s + 1 + D2;
+            if (sn > ns2 - 1) sn = ns2 - 1;
+            const int tn = tile_of(sn / KSL);
+            const int rows = q - tn * 128 < 128 ? q - tn * 128 : 128;
+            const rsrc_t qres = make_rsrc(Qm + (int64_t)tn * 128 * R, (int64_t)rows * R * 2);
+            const int so = (sn % KSL) * BK2 * 2;
+            if (flush) flush_read(seq);
+#pragma unroll
+            for (int e = 0; e < L::NCHQ; ++e) {
+                *reinterpret_cast<u32x4*>(lds + slot * L::slab2 + qoff[e]) = rg[e];
+                rg[e] = buf_load16(qres, qsrc[e], so);
+                __builtin_amdgcn_sched_barrier(0);
+                if (e < NY && flush) flush_store(seq, e);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (flush) {
+#pragma unroll
+                for (int e = L::NCHQ; e < NY; ++e) flush_store(seq, e);
+            }
+        };
+        int flushed = 0;
+        for (int s0 = 0; s0 < n2p; s0 += D2) {
+#pragma unroll
+            for (int d = 0; d < D2; ++d) {
+                const int s = s0 + d;
+                const bool flush = s > 0 && s % KSL == 0 && flushed < ntile;
+                TSTAMP(1, 0, s);
+                step2(ring2[(d + 1) % D2], s, flush, flushed);
+                if (flush) ++flushed;
+                TSTAMP(1, 3, s);
+                wg_barrier();
+            }
+        }
+        if (flushed < ntile) {
+            flush_read(flushed);
+#pragma unroll
+            for (int e = 0; e < NY; ++e) flush_store(flushed, e);
+        }
+        TMARK(1, 2);
+        return;
+    }
+
+    // ====================================================================== MFMA waves
+    const int lj = lane & 31, lh = lane >> 5;
+    const int grp = wave >> 2, w4 = wave & 3;           // row group, wave inside the group
+    const int cs = w4 % CS, rs = (w4 / CS) % RS, ks = w4 / (CS * RS);
+    unsigned char* const ttile_g = ttile + grp * L::ttile;
+    unsigned char* const red_g = lds + grp * L::red;
+
+    // ------------------------------------------------------------------ stage 1
+    f32x16 acc1[RA][CB];
+#pragma unroll
+    for (int a = 0; a < RA; ++a)
+#pragma unroll
+        for (int b = 0; b < CB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc1[a][b][v] = 0.0f;
+
+    TMARK(0, 0);
+    wg_barrier();                                       // slab 0 is in slot 0
+    TMARK(0, 1);
+    for (int s = 0; s < n1p; ++s) {
+        if (s < ns1) {
+            const unsigned char* base = lds + (s & 1) * L::slab1;
+#pragma unroll
+            for (int j = 0; j < SPW; ++j) {
+                const int kk = ks * SPW + j;            // k16 step inside the slab
+                const int qc = 2 * kk + lh;             // logical chunk of this lane's 8 values
+                u32x4 xf[RA], pf[CB];
+#pragma unroll
+                for (int a = 0; a < RA; ++a) {
+                    const int row = 64 * grp + 32 * (rs * RA + a) + lj;
+                    xf[a] = *reinterpret_cast<const u32x4*>(base + row * (BK1 * 2) + swz<CPR1>(qc, row) * 16);
+                }
+#pragma unroll
+                for (int b = 0; b < CB; ++b) {
+                    const int row = ROWS + (cs * CB + b) * 32 + lj;
+                    pf[b] = *reinterpret_cast<const u32x4*>(base + row * (BK1 * 2) + swz<CPR1>(qc, row) * 16);
+                }
+#pragma unroll
+                for (int a = 0; a < RA; ++a)
+#pragma unroll
+                    for (int b = 0; b < CB; ++b) acc1[a][b] = mfma16(pf[b], xf[a], acc1[a][b]);
+            }
+        }
+        wg_barrier();
+    }
+
+    TMARK(0, 2);
+    // ------------------------------------------------------------------ sum over the KS groups, T tile (bf16) to LDS
+    // lane holds T[32(rs RA + a) + lj][32(cs CB + b) + 8g + 4 lh + (0..3)] in acc1[a][b][4g .. 4g+3]
+    auto emit_T = [&](const f32x16 (&blk)[CB], int a) {
+#pragma unroll
+        for (int b = 0; b < CB; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                u32x2 o = {pack2_bf16(blk[b][4 * g + 0], blk[b][4 * g + 1]),
+                           pack2_bf16(blk[b][4 * g + 2], blk[b][4 * g + 3])};
+                *reinterpret_cast<u32x2*>(ttile_g + (32 * (rs * RA + a) + lj) * L::tpitch +
+                                          (32 * (cs * CB + b) + 8 * g + 4 * lh) * 2) = o;
+            }
+    };
+    if constexpr (KS == 2 && RA == 2) {
+        // Two contraction groups: the partners swap halves instead of one sending everything.  Wave ks
+        // sends its row block 1 - ks, adds what it receives to its row block ks and converts that
+        // half of T itself: every wave stores and loads half as much, and all four convert.
+        f32x4* red = reinterpret_cast<f32x4*>(red_g);
+        auto swap_and_emit = [&](const f32x16 (&send)[CB], f32x16 (&keep)[CB], int a_keep) {
+            f32x4* dst = red + (size_t)((ks * CS + cs) * CB) * 4 * 64;
+#pragma unroll
+            for (int b = 0; b < CB; ++b)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    dst[(b * 4 + g) * 64 + lane] = f32x4{send[b][4 * g], send[b][4 * g + 1], send[b][4 * g + 2], send[b][4 * g + 3]};
+            wg_barrier();
+            const f32x4* src = red + (size_t)(((1 - ks) * CS + cs) * CB) * 4 * 64;
+#pragma unroll
+            for (int b = 0; b < CB; ++b)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 v = src[(b * 4 + g) * 64 + lane];
+                    keep[b][4 * g] += v[0]; keep[b][4 * g + 1] += v[1];
+                    keep[b][4 * g + 2] += v[2]; keep[b][4 * g + 3] += v[3];
+                }
+            TMARK(0, 3);
+            emit_T(keep, a_keep);
+        };
+        if (ks == 0) swap_and_emit(acc1[1], acc1[0], 0);
+        else swap_and_emit(acc1[0], acc1[1], 1);
+    } else {
+        if constexpr (KS > 1) {
+            // tree; layout: [wave slot][block (a,b)][quad g][lane][4 floats]: one 16-byte access per quad
+            f32x4* red = reinterpret_cast<f32x4*>(red_g);
+            const int wslot = rs * CS + cs;
+#pragma unroll
+            for (int half = KS / 2; half >= 1; half >>= 1) {
+                if (ks >= half && ks < 2 * half) {
+                    f32x4* dst = red + (size_t)(((ks - half) * (CS * RS) + wslot) * (RA * CB)) * 4 * 64;
+#pragma unroll
+                    for (int a = 0; a < RA; ++a)
+#pragma unroll
+                        for (int b = 0; b < CB; ++b)
+#pragma unroll
+                            for (int g = 0; g < 4; ++g)
+                                dst[((a * CB + b) * 4 + g) * 64 + lane] =
+                                    f32x4{acc1[a][b][4 * g], acc1[a][b][4 * g + 1], acc1[a][b][4 * g + 2], acc1[a][b][4 * g + 3]};
+                }
+                wg_barrier();
+                if (ks < half) {
+                    const f32x4* src = red + (size_t)((ks * (CS * RS) + wslot) * (RA * CB)) * 4 * 64;
+#pragma unroll
+                    for (int a = 0; a < RA; ++a)
+#pragma unroll
+                        for (int b = 0; b < CB; ++b)
+#pragma unroll
+                            for (int g = 0; g < 4; ++g) {
+                                const f32x4 v = src[((a * CB + b) * 4 + g) * 64 + lane];
+                                acc1[a][b][4 * g] += v[0]; acc1[a][b][4 * g + 1] += v[1];
+                                acc1[a][b][4 * g + 2] += v[2]; acc1[a][b][4 * g + 3] += v[3];
+                            }
+                }
+                if (half > 1) wg_barrier();             // the next round overwrites what was just read
+            }
+        }
+        TMARK(0, 3);
+        if (ks == 0) {
+#pragma unroll
+            for (int a = 0; a < RA; ++a) emit_T(acc1[a], a);
+        }
+    }
+    wg_barrier();                                       // last of the mid barriers: T tile complete
+    if (Yout == nullptr) return;
+
+    // Stage 2: wave w4 of a row group owns the group's 64 rows of T (in registers, as MFMA B operands)
+    // and column block w4 (32 columns) of every 128-column output tile.
+    constexpr int KB = R / 16;
+    u32x4 tf[2][KB];   // T[32a + lj][16kb + 8 lh .. +7]
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+            tf[a][kb] = *reinterpret_cast<const u32x4*>(ttile_g + (32 * a + lj) * L::tpitch + (16 * kb + 8 * lh) * 2);
+    wg_barrier();                                       // T tile consumed; stage 2 takes over the LDS
+    TMARK(0, 4);
+    wg_barrier();                                       // Q slab 0 is in slot 0
+    TMARK(0, 5);
+
+    // ------------------------------------------------------------------ stage 2
+    f32x16 acc2[2];
+    for (int s0 = 0; s0 < n2p; s0 += KSL) {
+        const int t = s0 / KSL;
+        const bool live = s0 < ns2;                     // padded trips only keep the barrier count
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc2[a][v] = 0.0f;
+#pragma unroll
+        for (int kslab = 0; kslab < KSL; ++kslab) {
+            TSTAMP(0, 0, s0 + kslab);
+            if (live) {
+                const unsigned char* base = lds + ((s0 + kslab) & 1) * L::slab2;
+                const int row = 32 * w4 + lj;
+#pragma unroll
+                for (int kk = 0; kk < BK2 / 16; ++kk) {
+                    const u32x4 qf = *reinterpret_cast<const u32x4*>(
+                        base + row * (BK2 * 2) + swz<CPR2>(2 * kk + lh, row) * 16);
+                    const int kb = kslab * (BK2 / 16) + kk;
+                    acc2[0] = mfma16(qf, tf[0][kb], acc2[0]);
+                    acc2[1] = mfma16(qf, tf[1][kb], acc2[1]);
+                }
+                if (kslab == KSL - 1) {
+                    // lane holds Y[32a + lj][32 wave + 8g + 4 lh + (0..3)] of this 64 x 128 tile
+                    unsigned char* yt = ytile + (grp * 2 + (t & 1)) * L::ytile;
+#pragma unroll
+                    for (int a = 0; a < 2; ++a)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            u32x2 o = {pack2_bf16(acc2[a][4 * g + 0], acc2[a][4 * g + 1]),
+                                       pack2_bf16(acc2[a][4 * g + 2], acc2[a][4 * g + 3])};
+                            *reinterpret_cast<u32x2*>(yt + (32 * a + lj) * L::ypitch + (32 * w4 + 8 * g + 4 * lh) * 2) = o;
+                        }
+                }
+            }
+            TSTAMP(0, 1, s0 + kslab);
+            wg_barrier();
+        }
+    }
+    TMARK(0, 6);
+}
+
+template <int R>
+hipError_t launch_chain3_r(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
+                           int64_t M, int p, int q, hipStream_t s) {
+    constexpr int lds_bytes = Ch2Cfg<R>::lds_bytes;
+    static_assert(lds_bytes <= 160 * 1024, "LDS budget");
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chain3_bf16_kernel<R, false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((chain3_bf16_kernel<R, false>), dim3((unsigned)ceil_div(M, ROWS)), dim3(NT), lds_bytes, s,
+                       (const uint16_t*)Xin, (const uint16_t*)P, (const uint16_t*)Q,
+                       (uint16_t*)Yout, (uint16_t*)Tout, M, p, q, R, Ch2Gather{});
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Ranks whose two reduction scratches, T tiles and staging tiles fit the LDS and whose T operands
+// fit the 168 registers twelve waves leave (R = 384 would need 192 for them alone).
+bool chain3_supports(int R, int p, int q) {
+    if (p % 64 != 0 || p > (1 << 20) || q > (1 << 20)) return false;
+    switch (R) {
+        case 32: case 64: case 96: case 128: case 192: return true;
+        default: return false;
+    }
+}
+
+hipError_t launch_chain3_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
+                              int64_t M, int p, int q, int R, hipStream_t s) {
+    switch (R) {
+#define ABT_CASE(RR) case RR: return launch_chain3_r<RR>(Xin, P, Q, Yout, Tout, M, p, q, s);
+        ABT_CASE(32) ABT_CASE(64) ABT_CASE(96) ABT_CASE(128) ABT_CASE(192)
+#undef ABT_CASE
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace abt

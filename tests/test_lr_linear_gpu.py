@@ -280,3 +280,36 @@ def test_step_replays_from_a_captured_graph():
             torch.cuda.synchronize()
             for got, ref in zip((Y, T, dX, dA, dB), want):
                 assert torch.equal(got, ref)
+
+
+# ------------------------------------------------------------------ 128-row work-groups (large batches)
+
+@pytest.fixture
+def tall_chain():
+    prev = abt.set_chain_rows(128)
+    yield
+    abt.set_chain_rows(prev)
+
+
+@pytest.mark.parametrize("r", [32, 64, 96, 128, 192])
+@pytest.mark.parametrize("M", [1, 64, 129, 1000])
+def test_bf16_tall_work_groups(tall_chain, M, r):
+    # forced on small batches so that the oracle can check every element: one row, one row group,
+    # a ragged second work-group, several work-groups; n, m give several slabs and a ragged last tile
+    c = gen.lr_case(M=M, m=320, n=192, r=r, seed=7000 + M + r)
+    check_full(c, torch.bfloat16, TOL_BF16)
+
+
+def test_bf16_tall_work_groups_chosen_for_large_batches():
+    # above one round of 64-row work-groups the library picks the 128-row kernel by itself; the
+    # result must agree with the 64-row kernel's up to summation order, and with the oracle on samples
+    c = gen.lr_case(M=20000, m=768, n=768, r=192, seed=31)
+    sampled_check(c, TOL_BF16, seed=1)
+    X, dY, A, B, Y, T, dX, dA, dB = run_step(c, torch.bfloat16)
+    prev = abt.set_chain_rows(64)
+    try:
+        _, _, _, _, Y64, T64, dX64, dA64, dB64 = run_step(c, torch.bfloat16)
+    finally:
+        abt.set_chain_rows(prev)
+    for a, b in ((Y, Y64), (T, T64), (dX, dX64), (dA, dA64), (dB, dB64)):
+        assert rel(host(a), host(b)) < 2e-3
