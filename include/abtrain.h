@@ -282,6 +282,12 @@ size_t lr_conv_bwd_workspace_bytes(const abt_conv_geom* geom, int64_t m, int64_t
  * values are ignored.  Returns the previous setting. */
 int abt_set_chain_rows(int rows);
 
+/* Column parts of the 128-row chain kernel: 0 = chosen from the shape (default), 1..8 = forced
+ * (capped by the number of 128-column output tiles).  With n parts every row block is served by n
+ * work-groups that each repeat the first product and do 1/n of the second.  A tuning and test
+ * switch.  Returns the previous setting. */
+int abt_set_chain_parts(int parts);
+
 /* Sweep cap of the Jacobi SVD (default 30, clamped to [1, 64]; sweeps stop as soon as every layer
  * has converged: 8-9 for the 384-wide cores of config 5, about 15 for dense 768-wide weights);
  * returns the previous value. */

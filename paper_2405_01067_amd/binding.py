@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "lib
 _lib = None
 
 EXPORTS = (
-    "abt_status_string", "abt_set_jacobi_max_sweeps", "abt_set_chain_rows",
+    "abt_status_string", "abt_set_jacobi_max_sweeps", "abt_set_chain_rows", "abt_set_chain_parts",
     "lr_linear_fwd", "lr_linear_fwd_workspace_bytes",
     "lr_linear_bwd", "lr_linear_bwd_workspace_bytes",
     "ab_merge", "ab_merge_workspace_bytes",
@@ -82,6 +82,8 @@ def load():
     lib.abt_status_string.argtypes = [ci]
     lib.abt_set_chain_rows.restype = ci
     lib.abt_set_chain_rows.argtypes = [ci]
+    lib.abt_set_chain_parts.restype = ci
+    lib.abt_set_chain_parts.argtypes = [ci]
     lib.abt_set_jacobi_max_sweeps.restype = ci
     lib.abt_set_jacobi_max_sweeps.argtypes = [ci]
     lib.lr_linear_fwd.restype = ci
@@ -142,6 +144,11 @@ def _check(code: int, what: str):
 def set_chain_rows(rows: int) -> int:
     """Force the chain kernel's work-group height (64 or 128; 0 = automatic); returns the previous setting."""
     return load().abt_set_chain_rows(int(rows))
+
+
+def set_chain_parts(parts: int) -> int:
+    """Force the column parts of the 128-row chain kernel (1..8; 0 = automatic); returns the previous setting."""
+    return load().abt_set_chain_parts(int(parts))
 
 
 def set_jacobi_max_sweeps(n: int) -> int:

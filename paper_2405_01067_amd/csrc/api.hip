@@ -14,14 +14,47 @@ int g_max_sweeps = 30;
 // Chain kernel choice: for large batches the 128-row kernel where it supports the rank (32, 64, 96,
 // 128, 192); else the 64-row kernel with loader and MFMA waves wherever that supports the rank
 // (32, 64, 96, 128, 160, 192, 256, 320, 384), else the older kernel (224, 288, 352).
-int g_chain_rows = 0;   // 0: automatic; 64 or 128: force that work-group height where the rank allows it
+int g_chain_rows = 0;    // 0: automatic; 64 or 128: force that work-group height where the rank allows it
+int g_chain_parts = 0;   // 0: automatic; n: force n column parts for 128-row work-groups
+
+// Launch shape of the chain kernel.  Measured on gfx950 (forward of configs 2 and 3 and four other
+// shapes): a 128-row work-group takes 1.58 times as long as a 64-row one on the same factors (its
+// LDS traffic per slab, not its loaders, sets the pace), so it only pays through the rounds the
+// grid needs on the 256 compute units: 4 rounds of 64-row work-groups against 2 of 128-row ones at
+// M = 50432 (148 -> 127 us), 2 against 1 at M = 25216.  Column parts (several work-groups per row
+// block) never paid in those measurements and are only used when forced.
+struct ChainShape { int rows, parts; };
+
+ChainShape choose_chain_shape(int64_t M, int p, int q, int R, bool second_stage) {
+    const ChainShape small{64, 1};
+    if (g_chain_rows == 64 || !chain3_supports(R, p, q)) return small;
+    int parts = 1;
+    if (second_stage && g_chain_parts > 1) {
+        const int ntile = (int)ceil_div(q, 128);
+        parts = g_chain_parts < ntile ? g_chain_parts : ntile;
+    }
+    if (g_chain_rows == 128 || !chain2_supports(R, p, q)) return ChainShape{128, parts};
+    const double cost64 = (double)ceil_div(ceil_div(M, 64), 256);
+    const double cost128 = 1.58 * (double)ceil_div(ceil_div(M, 128) * parts, 256);
+    return cost128 < cost64 ? ChainShape{128, parts} : small;
+}
+
+// the gathered chain (factored convolution): same choice of work-group height, no column parts
+hipError_t chain_gather(const void* image, const PatchGeom& g, const void* P, const void* Q, void* Yout, void* Tout,
+                        int t_pitch, int64_t M, int q, int R, hipStream_t s) {
+    const int p = g.kh * g.kw * ((g.Cin + 63) / 64) * 64;
+    const int saved = g_chain_parts;
+    g_chain_parts = 0;
+    const ChainShape sh = choose_chain_shape(M, p, q, R, Yout != nullptr);
+    g_chain_parts = saved;
+    if (sh.rows == 128) return launch_chain3_gather_bf16(image, g, P, Q, Yout, Tout, t_pitch, M, q, R, s);
+    return launch_chain2_gather_bf16(image, g, P, Q, Yout, Tout, t_pitch, M, q, R, s);
+}
 
 hipError_t chain(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                  int64_t M, int p, int q, int R, hipStream_t s) {
-    // 128-row work-groups take about 1.3 times as long as 64-row ones and there are half as many:
-    // they win as soon as the 64-row grid needs more than one round of the 256 compute units
-    const bool tall = g_chain_rows == 128 || (g_chain_rows == 0 && ceil_div(M, 64) > 256);
-    if (tall && chain3_supports(R, p, q)) return launch_chain3_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
+    const ChainShape sh = choose_chain_shape(M, p, q, R, Yout != nullptr);
+    if (sh.rows == 128) return launch_chain3_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, sh.parts, s);
     if (chain2_supports(R, p, q)) return launch_chain2_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
     return launch_chain_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
 }
@@ -169,7 +202,7 @@ int lr_conv_fwd(const void* act, const void* A, const void* B, void* Y, void* T_
     const abt_conv_geom& g = *geom;
     const int64_t M = g.N * g.H * g.W;
     const PatchGeom pg{(int)g.H, (int)g.W, (int)g.C, g.kh, g.kw, +1};
-    return launch_chain2_gather_bf16(act, pg, B, A, Y, T_save, (int)r, M, (int)m, (int)r, (hipStream_t)stream) == hipSuccess
+    return chain_gather(act, pg, B, A, Y, T_save, (int)r, M, (int)m, (int)r, (hipStream_t)stream) == hipSuccess
                ? ABT_OK : ABT_EHIP;
 }
 
@@ -197,7 +230,7 @@ int lr_conv_bwd(const void* dY, const void* act, const void* T, const void* A, c
     void* dT = ws + w.dT;
     const void* Tp = T;
     if (!Tp && dA) {   // recompute T = patches(act) B^T (first stage of the chain only)
-        if (launch_chain2_gather_bf16(act, fwd_geom, B, nullptr, nullptr, ws + w.T, (int)r, M, 64, (int)r, s) != hipSuccess)
+        if (chain_gather(act, fwd_geom, B, nullptr, nullptr, ws + w.T, (int)r, M, 64, (int)r, s) != hipSuccess)
             return ABT_EHIP;
         Tp = ws + w.T;
     }
@@ -205,7 +238,7 @@ int lr_conv_bwd(const void* dY, const void* act, const void* T, const void* A, c
         // dT = dY A = dY (A^T)^T: first stage of the plain chain on the transposed factor
         const TransposeJob tj{A, ws + w.At, (int)m, (int)r};
         if (launch_transpose_bf16(&tj, 1, s) != hipSuccess) return ABT_EHIP;
-        if (launch_chain2_bf16(dY, ws + w.At, nullptr, nullptr, dT, M, (int)m, 64, (int)r, s) != hipSuccess) return ABT_EHIP;
+        if (chain(dY, ws + w.At, nullptr, nullptr, dT, M, (int)m, 64, (int)r, s) != hipSuccess) return ABT_EHIP;
     }
     if (dAct) {
         // dAct[q, c] = sum over taps and j of dT[q - shift(tap), j] B[j, tap, c]: the same gathered
@@ -217,7 +250,7 @@ int lr_conv_bwd(const void* dY, const void* act, const void* T, const void* A, c
         const int64_t pst_pitch = (int64_t)taps * w.r_pad;
         for (int64_t c0 = 0; c0 < g.C; c0 += chunk) {
             const char* Pc = ws + w.Pst + (size_t)c0 * pst_pitch * 2;
-            if (launch_chain2_gather_bf16(dT, adj, Pc, nullptr, nullptr, (char*)dAct + c0 * 2, (int)g.C, M, 64, chunk, s) !=
+            if (chain_gather(dT, adj, Pc, nullptr, nullptr, (char*)dAct + c0 * 2, (int)g.C, M, 64, chunk, s) !=
                 hipSuccess)
                 return ABT_EHIP;
         }
@@ -287,6 +320,12 @@ int ab_reconstruct(const float* A, const float* B, float* W,
 int abt_set_chain_rows(int rows) {
     const int prev = g_chain_rows;
     if (rows == 0 || rows == 64 || rows == 128) g_chain_rows = rows;
+    return prev;
+}
+
+int abt_set_chain_parts(int parts) {
+    const int prev = g_chain_parts;
+    if (parts >= 0 && parts <= 8) g_chain_parts = parts;
     return prev;
 }
 

@@ -1,28 +1,31 @@
 // Chain kernel, 128-row work-groups:  Tout[M,R] = Xin[M,p] . P[R,p]^T  then  Yout[M,q] = Tout . Q[q,R]^T
 // (bf16 in, fp32 accumulate): the variant of the 64-row chain kernel for large batches.
 //
-// A 64-row work-group's time is set by streaming the two factors through LDS, not by its rows: the
-// loader waves are busy for about 1650 cycles per 128 rows of Q while the MFMA waves need 768.  Here a
-// work-group owns 128 rows as two row groups of 64: eight MFMA waves, four per row group, each group
-// working exactly as the four MFMA waves of the 64-row kernel do, on its own rows of the Xin part of
-// a slab, its own reduction scratch, T tile and output staging tiles, while both groups read the
-// same P and Q slabs.  Four loader waves feed them.  Every slab of a factor now serves twice the
-// rows; twelve waves leave 168 registers per lane, so the register rings are shallower and a
-// stage-2 slab holds at most 96 contraction columns (two slabs per output tile for R = 192), which
-// also keeps four staging tiles plus two slab slots inside the 160 KB of LDS.
+// A 64-row work-group streams both factors through LDS for its 64 rows; a grid of them that needs
+// several rounds on the 256 compute units leaves a partial last round.  Here a work-group owns 128
+// rows as two row groups of 64: eight MFMA waves, four per row group, each group working exactly as
+// the four MFMA waves of the 64-row kernel do, on its own rows of the Xin part of a slab, its own
+// reduction scratch, T tile and output staging tiles, while both groups read the same P and Q slabs
+// that four loader waves bring in once.  Measured: such a work-group takes 1.58 times as long as a
+// 64-row one on the same factors (the slab is stored once but read by both groups, and twice the
+// output is staged: LDS traffic per output tile goes from 128 KB to 208 KB at the same ~77 B/clk),
+// so a compute unit gets through rows 1.27 times as fast, and a grid of half as many work-groups
+// often needs fewer rounds.  Twelve waves leave 168 registers per lane, so the register rings are
+// shallower and a stage-2 slab holds at most 96 contraction columns (two slabs per output tile for
+// R = 192), which also keeps four staging tiles plus two slab slots inside the 160 KB of LDS.
 // Everything else (slab layouts, swizzles, barrier discipline, buffer addressing, slab rotation)
 // is the 64-row kernel's; see lr_chain2.hip for the reasoning.
 #include "common.h"
 
 // Phase timing for tuning, compiled out of the library: with -DABT_TIMING, wave 0 (role 0, an MFMA
-// wave) and wave 4 (role 1, a loader wave) of work-group 5 record the cycle counter at the marked
+// wave) and wave 8 (role 1, a loader wave) of work-group 5 record the cycle counter at the marked
 // points into abt_tbuf (once per launch) and abt_tl (per slab of stage 2); a test program that
 // includes this file reads them back with hipMemcpyFromSymbol.
 #ifdef ABT_TIMING
 __device__ long long abt_tbuf[2][64];
-#define TMARK(role, i) do { if (blockIdx.x == 5 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 4 : 0)) abt_tbuf[role][i] = __builtin_readcyclecounter(); } while (0)
+#define TMARK(role, i) do { if (blockIdx.x == 5 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 8 : 0)) abt_tbuf[role][i] = __builtin_readcyclecounter(); } while (0)
 __device__ long long abt_tl[2][4][32];
-#define TSTAMP(role, k, it) do { if (blockIdx.x == 5 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 4 : 0) && (it) < 32) abt_tl[role][k][it] = __builtin_readcyclecounter(); } while (0)
+#define TSTAMP(role, k, it) do { if (blockIdx.x == 5 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 8 : 0) && (it) < 32) abt_tl[role][k][it] = __builtin_readcyclecounter(); } while (0)
 #else
 #define TMARK(role, i) do {} while (0)
 #define TSTAMP(role, k, it) do {} while (0)
@@ -134,7 +137,11 @@ __global__ __launch_bounds__(NT) void chain3_bf16_kernel(const uint16_t* __restr
     const int64_t row0 = (int64_t)blockIdx.x * ROWS;
     const int ns1 = p / BK1;
     const int n1p = (ns1 + D1 - 1) / D1 * D1;           // stage-1 trip count, padded to the loaders' ring
-    const int ntile = (q + 127) / 128;                  // stage-2 output tiles of 128 columns
+    // stage-2 output tiles of 128 columns: work-group (x, y) of a grid with gridDim.y column parts
+    // does the tiles [tile0, tile0 + ntile) of the ntile_all; every part repeats stage 1 for its rows
+    const int ntile_all = (q + 127) / 128;
+    const int tile0 = (int)(blockIdx.y * (unsigned)ntile_all / gridDim.y);
+    const int ntile = (int)((blockIdx.y + 1) * (unsigned)ntile_all / gridDim.y) - tile0;
     const int ns2 = ntile * KSL;
     const int n2p = (ns2 + L::U2 - 1) / L::U2 * L::U2;  // stage-2 trip count, padded likewise
     // per row group g: reduction scratch at g * red, T tile at 2 * red + g * ttile (stage 1 and T phase);
@@ -147,7 +154,7 @@ __global__ __launch_bounds__(NT) void chain3_bf16_kernel(const uint16_t* __restr
     const int rot1 = (int)(blockIdx.x % (unsigned)ns1);
     const int rot2 = (int)(blockIdx.x % (unsigned)ntile);
     auto slab1_of = [&](int s) { if (s > ns1 - 1) s = ns1 - 1; s += rot1; return s >= ns1 ? s - ns1 : s; };
-    auto tile_of = [&](int t) { if (t > ntile - 1) t = ntile - 1; t += rot2; return t >= ntile ? t - ntile : t; };
+    auto tile_of = [&](int t) { if (t > ntile - 1) t = ntile - 1; t += rot2; return tile0 + (t >= ntile ? t - ntile : t); };
 
     if (wave >= NMW) {
         // ================================================================== loader waves
@@ -307,7 +314,7 @@ __global__ __launch_bounds__(NT) void chain3_bf16_kernel(const uint16_t* __restr
             if (i < L::n_mid_barriers) wg_barrier();
         }
         // T tile is in LDS: store it (the MFMA waves load their operands from it meanwhile)
-        if (Tout != nullptr) {
+        if (Tout != nullptr && blockIdx.y == 0) {
             // rows of Tout are t_pitch elements apart (R for a plain T; more when the tile is a
             // column block of a wider matrix); the descriptor ends with the last valid row
             const rsrc_t tres = make_rsrc(Tout + row0 * t_pitch, ((rows_valid - 1) * t_pitch + R) * 2);
@@ -585,21 +592,21 @@ __global__ __launch_bounds__(NT) void chain3_bf16_kernel(const uint16_t* __restr
     TMARK(0, 6);
 }
 
-template <int R>
+template <int R, bool GATHER>
 hipError_t launch_chain3_r(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
-                           int64_t M, int p, int q, hipStream_t s) {
+                           int64_t M, int p, int q, int t_pitch, const Ch2Gather& gg, int parts, hipStream_t s) {
     constexpr int lds_bytes = Ch2Cfg<R>::lds_bytes;
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chain3_bf16_kernel<R, false>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chain3_bf16_kernel<R, GATHER>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((chain3_bf16_kernel<R, false>), dim3((unsigned)ceil_div(M, ROWS)), dim3(NT), lds_bytes, s,
+    hipLaunchKernelGGL((chain3_bf16_kernel<R, GATHER>), dim3((unsigned)ceil_div(M, ROWS), (unsigned)parts), dim3(NT), lds_bytes, s,
                        (const uint16_t*)Xin, (const uint16_t*)P, (const uint16_t*)Q,
-                       (uint16_t*)Yout, (uint16_t*)Tout, M, p, q, R, Ch2Gather{});
+                       (uint16_t*)Yout, (uint16_t*)Tout, M, p, q, t_pitch, gg);
     return hipGetLastError();
 }
 
@@ -616,9 +623,31 @@ bool chain3_supports(int R, int p, int q) {
 }
 
 hipError_t launch_chain3_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
-                              int64_t M, int p, int q, int R, hipStream_t s) {
+                              int64_t M, int p, int q, int R, int parts, hipStream_t s) {
+    // column parts: each does its share of the 128-column output tiles (and repeats stage 1)
+    if (parts < 1 || parts > 64 || (Yout != nullptr && parts > (q + 127) / 128) || (Yout == nullptr && parts != 1))
+        return hipErrorInvalidValue;
     switch (R) {
-#define ABT_CASE(RR) case RR: return launch_chain3_r<RR>(Xin, P, Q, Yout, Tout, M, p, q, s);
+#define ABT_CASE(RR) case RR: return launch_chain3_r<RR, false>(Xin, P, Q, Yout, Tout, M, p, q, R, Ch2Gather{}, parts, s);
+        ABT_CASE(32) ABT_CASE(64) ABT_CASE(96) ABT_CASE(128) ABT_CASE(192)
+#undef ABT_CASE
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// The 128-row chain with the first operand gathered from a channels-last image (see
+// launch_chain2_gather_bf16 for the operand's definition).
+hipError_t launch_chain3_gather_bf16(const void* image, const PatchGeom& g, const void* P, const void* Q,
+                                     void* Yout, void* Tout, int t_pitch, int64_t M, int q, int R, hipStream_t s) {
+    const int cpb = (g.Cin + 63) / 64;
+    const int64_t p = (int64_t)g.kh * g.kw * cpb * 64;
+    if (g.H < 1 || g.W < 1 || g.Cin < 8 || g.Cin % 8 || g.kh < 1 || g.kw < 1 || !(g.kh & 1) || !(g.kw & 1) ||
+        (g.sign != 1 && g.sign != -1) || M % ((int64_t)g.H * g.W) != 0 || p > (1 << 20) || !chain3_supports(R, (int)p, q) ||
+        ((int64_t)ROWS + 2 * ((g.kh / 2) * (int64_t)g.W + g.kw / 2)) * g.Cin * 2 >= kBufMaxBytes || t_pitch < R)
+        return hipErrorInvalidValue;
+    const Ch2Gather gg{g.H, g.W, g.Cin, cpb, g.kh, g.kw, g.sign};
+    switch (R) {
+#define ABT_CASE(RR) case RR: return launch_chain3_r<RR, true>(image, P, Q, Yout, Tout, M, (int)p, q, t_pitch, gg, 1, s);
         ABT_CASE(32) ABT_CASE(64) ABT_CASE(96) ABT_CASE(128) ABT_CASE(192)
 #undef ABT_CASE
         default: return hipErrorInvalidValue;

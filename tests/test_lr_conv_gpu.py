@@ -71,6 +71,17 @@ def test_conv_step_against_oracle(N, H, W, C, m, r, kh, kw):
     check(c)
 
 
+@pytest.mark.parametrize("N,H,W,C,m,r,kh,kw", [CASES[0], CASES[1], CASES[6], (3, 10, 10, 64, 128, 192, 3, 3)])
+def test_conv_step_with_tall_work_groups(N, H, W, C, m, r, kh, kw):
+    # the 128-row chain kernel (chosen by itself only for large batches) forced on small ones
+    prev = abt.set_chain_rows(128)
+    try:
+        c = gen.conv_case(N, H, W, C, m, r, kh, kw, seed=N * 1000 + H * 100 + C + r + 1)
+        check(c)
+    finally:
+        abt.set_chain_rows(prev)
+
+
 def test_conv_equals_linear_layer_on_explicit_patches():
     # the gathered kernels and the plain kernels on an explicit patch matrix run the same products
     # in the same order: forward bit for bit; the factor gradients too

@@ -300,6 +300,19 @@ def test_bf16_tall_work_groups(tall_chain, M, r):
     check_full(c, torch.bfloat16, TOL_BF16)
 
 
+@pytest.mark.parametrize("parts", [2, 3, 8])
+@pytest.mark.parametrize("M,r", [(129, 192), (1000, 96), (300, 32)])
+def test_bf16_tall_work_groups_with_column_parts(tall_chain, M, r, parts):
+    # several work-groups per row block, each doing a share of the output tiles (m = 448: four
+    # tiles, the last ragged; 8 parts are capped to 4)
+    prev = abt.set_chain_parts(parts)
+    try:
+        c = gen.lr_case(M=M, m=448, n=192, r=r, seed=7100 + M + r + parts)
+        check_full(c, torch.bfloat16, TOL_BF16)
+    finally:
+        abt.set_chain_parts(prev)
+
+
 def test_bf16_tall_work_groups_chosen_for_large_batches():
     # above one round of 64-row work-groups the library picks the 128-row kernel by itself; the
     # result must agree with the 64-row kernel's up to summation order, and with the oracle on samples
