@@ -216,6 +216,17 @@ def test_binding_refuses_cpu_tensors(lib):
         abt.ab_merge([a.float()], [b.float()], tau=0.1)
 
 
+def test_chain_shape_setters(lib):
+    assert abt.set_chain_rows(128) == 0
+    assert abt.set_chain_rows(77) == 128          # ignored value, setting kept
+    assert abt.set_chain_rows(64) == 128
+    assert abt.set_chain_rows(0) == 64
+    assert abt.set_chain_parts(3) == 0
+    assert abt.set_chain_parts(99) == 3           # ignored
+    assert abt.set_chain_parts(0) == 3
+    assert abt.set_chain_parts(0) == 0 and abt.set_chain_rows(0) == 0
+
+
 def test_sweep_cap_setter(lib):
     prev = abt.set_jacobi_max_sweeps(5)
     assert abt.set_jacobi_max_sweeps(1000) == 5
