@@ -253,11 +253,14 @@ __global__ __launch_bounds__(Tn2<R>::NT) void tn2_bf16_kernel(Tn2Args args) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
     // Work-groups are dealt to the eight XCDs round-robin by their linear index, and each XCD has
-    // its own L2: all column tiles of one row split go to the same XCD, so the V rows they share
-    // are fetched from HBM once, not once per XCD.
+    // its own L2.  The (split, tile) pairs are numbered split-major and every XCD takes one
+    // contiguous eighth of them: the column tiles of one row split land on one XCD (two at most),
+    // so the V rows they share are fetched from HBM once, not once per XCD, and every XCD gets the
+    // same number of work-groups whatever the split count is.
     const int xcd = (int)blockIdx.x & 7, slot = (int)blockIdx.x >> 3;
-    const int tile = slot % args.tiles, split = xcd + 8 * (slot / args.tiles);
-    if (split >= args.splits) return;
+    const int pair = xcd * ((int)gridDim.x >> 3) + slot;
+    if (pair >= args.tiles * args.splits) return;
+    const int tile = pair % args.tiles, split = pair / args.tiles;
     const int jid = (args.njobs > 1 && tile >= args.job[1].tile_begin) ? 1 : 0;
     const Tn2Job job = args.job[jid];
     const int p0 = (tile - job.tile_begin) * TP;
@@ -381,13 +384,9 @@ int tn2_choose_splits(int64_t M, int total_tiles) {
     int64_t want = 256 / total_tiles;
     int64_t max_by_rows = M / (8 * 64);
     if (max_by_rows < 1) max_by_rows = 1;
-    if (want > 64) want = 64;
-    // split s runs on XCD s % 8: a multiple of eight splits gives every XCD the same number of
-    // work-groups (ten splits would give two XCDs twice the work of the others)
-    if (want >= 8) want = want / 8 * 8;
-    else want = 8;
-    if (want > max_by_rows) want = max_by_rows >= 8 ? max_by_rows / 8 * 8 : max_by_rows;
+    if (want > max_by_rows) want = max_by_rows;
     if (want < 1) want = 1;
+    if (want > 64) want = 64;
     return (int)want;
 }
 
@@ -401,7 +400,7 @@ hipError_t launch_tn2_r(const Tn2Args& args, int tiles, int splits, hipStream_t 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((tn2_bf16_kernel<R, GATHER>), dim3(8 * tiles * ((splits + 7) / 8)), dim3(Tn2<R>::NT), lds_bytes, s, args);
+    hipLaunchKernelGGL((tn2_bf16_kernel<R, GATHER>), dim3(8 * ((tiles * splits + 7) / 8)), dim3(Tn2<R>::NT), lds_bytes, s, args);
     return hipGetLastError();
 }
 
