@@ -1,4 +1,4 @@
-// Chain kernel, 64-row work-groups:  Tout[M,R] = Xin[M,p] . P[R,p]^T  then  Yout[M,q] = Tout . Q[q,R]^T
+// Chain kernel, 64-row work-groups (RG = 1) and 128-row work-groups (RG = 2):  Tout[M,R] = Xin[M,p] . P[R,p]^T  then  Yout[M,q] = Tout . Q[q,R]^T
 // (bf16 in, fp32 accumulate).  Forward of the factored layer with (Xin,P,Q) = (X,B,A); the
 // dT/dX half of the backward with (dY, A^T, B^T).
 //
@@ -31,17 +31,30 @@
 //
 // MFMA 32x32x16 bf16 layout (lane l, h = l/32): A operand = 8 values A[l%32][8h..8h+7], B operand
 // = B[8h..8h+7][l%32], accumulator v = C[8(v/4) + 4h + v%4][l%32].
+//
+// RG = 2, for large batches.  A 64-row work-group streams both factors through LDS for its 64 rows; a grid of them that needs
+// several rounds on the 256 compute units leaves a partial last round.  Here a work-group owns 128
+// rows as two row groups of 64: eight MFMA waves, four per row group, each group working exactly as
+// the four MFMA waves of the 64-row kernel do, on its own rows of the Xin part of a slab, its own
+// reduction scratch, T tile and output staging tiles, while both groups read the same P and Q slabs
+// that four loader waves bring in once.  Measured: such a work-group takes 1.58 times as long as a
+// 64-row one on the same factors (the slab is stored once but read by both groups, and twice the
+// output is staged: LDS traffic per output tile goes from 128 KB to 208 KB at the same ~77 B/clk),
+// so a compute unit gets through rows 1.27 times as fast, and a grid of half as many work-groups
+// often needs fewer rounds.  Twelve waves leave 168 registers per lane, so the register rings are
+// shallower and a stage-2 slab holds at most 96 contraction columns (two slabs per output tile for
+// R = 192), which also keeps four staging tiles plus two slab slots inside the 160 KB of LDS.
 #include "common.h"
 
 // Phase timing for tuning, compiled out of the library: with -DABT_TIMING, wave 0 (role 0, an MFMA
-// wave) and wave 4 (role 1, a loader wave) of work-group 5 record the cycle counter at the marked
+// wave) and the first loader wave (role 1) of work-group 5 record the cycle counter at the marked
 // points into abt_tbuf (once per launch) and abt_tl (per slab of stage 2); a test program that
 // includes this file reads them back with hipMemcpyFromSymbol.
 #ifdef ABT_TIMING
 __device__ long long abt_tbuf[2][64];
-#define TMARK(role, i) do { if (blockIdx.x == 5 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 4 : 0)) abt_tbuf[role][i] = __builtin_readcyclecounter(); } while (0)
+#define TMARK(role, i) do { if (blockIdx.x == 5 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? ABT_LOADER_WAVE : 0)) abt_tbuf[role][i] = __builtin_readcyclecounter(); } while (0)
 __device__ long long abt_tl[2][4][32];
-#define TSTAMP(role, k, it) do { if (blockIdx.x == 5 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 4 : 0) && (it) < 32) abt_tl[role][k][it] = __builtin_readcyclecounter(); } while (0)
+#define TSTAMP(role, k, it) do { if (blockIdx.x == 5 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? ABT_LOADER_WAVE : 0) && (it) < 32) abt_tl[role][k][it] = __builtin_readcyclecounter(); } while (0)
 #else
 #define TMARK(role, i) do {} while (0)
 #define TSTAMP(role, k, it) do {} while (0)
@@ -87,42 +100,44 @@ template <> struct Ch2<256> { static constexpr int RS = 1, CS = 2, KS = 2; };
 template <> struct Ch2<320> { static constexpr int RS = 1, CS = 2, KS = 2; };
 template <> struct Ch2<384> { static constexpr int RS = 1, CS = 4, KS = 1; };
 
-constexpr int NMW = 4, NLW = 4;                 // MFMA waves, loader waves
-constexpr int NMW_ = NMW;
-constexpr int NMT = 64 * NMW, NLT = 64 * NLW;   // threads per role
-constexpr int NT = NMT + NLT;
+constexpr int NLW = 4;                          // loader waves
+constexpr int NMW_ = 4;                         // MFMA waves per row group (RG row groups of 64 rows)
+constexpr int NLT = 64 * NLW;                   // loader threads
 constexpr int BK1 = 64, CPR1 = BK1 / 8;         // stage-1 slab: 64 contraction columns
 constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v / 2); }
 constexpr int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 constexpr int gcdi(int a, int b) { return b == 0 ? a : gcdi(b, a % b); }
 
-template <int R>
+template <int R, int RG>
 struct Ch2Cfg {
     using C = Ch2<R>;
+    static constexpr int ROWS = 64 * RG;                      // rows per work-group
     static constexpr int CB = R / 32 / C::CS;                 // column blocks per wave
     static constexpr int RA = 2 / C::RS;                      // row blocks per wave
     static constexpr int SPW = BK1 / (16 * C::KS);            // k16 steps per wave per slab
-    static constexpr int xpart = 64 * BK1 * 2;                // slot = [64 rows of Xin][R rows of P]
-    static constexpr int slab1 = (64 + R) * BK1 * 2;
-    static constexpr int NCHX = 64 * CPR1 / NLT;              // 16-byte chunks per loader thread (Xin part) = 2
+    static constexpr int xpart = ROWS * BK1 * 2;              // slot = [ROWS rows of Xin][R rows of P]
+    static constexpr int slab1 = (ROWS + R) * BK1 * 2;
+    static constexpr int NCHX = ROWS * CPR1 / NLT;            // 16-byte chunks per loader thread (Xin part) = 2 RG
     static constexpr int NCHP = R * CPR1 / NLT;               // chunks per loader thread (P part) = R / 32
-    static constexpr int D1 = clampi(32 / (NCHX + NCHP), 2, 6);   // stage-1 slabs in flight (register ring depth)
+    // slabs in flight (register ring depth): twelve waves (RG = 2) leave 168 registers per lane
+    static constexpr int D1 = RG == 1 ? clampi(32 / (NCHX + NCHP), 2, 6) : clampi(30 / (NCHX + NCHP), 2, 4);
     // stage 2: a slab is 128 rows of Q times BK2 = R / KSL columns
-    static constexpr int KSL = R <= 224 ? 1 : 2;
+    // RG = 2: at most 96 contraction columns per slab beyond R = 128 (LDS: four staging tiles)
+    static constexpr int KSL = RG == 1 ? (R <= 224 ? 1 : 2) : (R <= 128 ? 1 : R / 96);
     static constexpr int BK2 = R / KSL, CPR2 = BK2 / 8;
     static constexpr int slab2 = 128 * BK2 * 2;
     static constexpr int NCHQ = 128 * CPR2 / NLT;             // chunks per loader thread = BK2 / 16
-    static constexpr int D2 = clampi(36 / NCHQ, 2, 6);        // stage-2 slabs in flight
+    static constexpr int D2 = RG == 1 ? clampi(36 / NCHQ, 2, 6) : clampi(20 / NCHQ, 2, 4);   // stage-2 slabs in flight
     static constexpr int U2 = D2 * KSL / gcdi(D2, KSL);       // stage-2 trip count is padded to a multiple of this
     static constexpr int ypitch = 128 * 2 + 16;
     static constexpr int ytile = 64 * ypitch;
     static constexpr int red = (C::KS / 2) * C::CS * C::RS * RA * CB * 4096;   // first (largest) round of the tree
     static constexpr int tpitch = R * 2 + 16;
     static constexpr int ttile = 64 * tpitch;
-    static constexpr int a = 2 * slab1, b = red + ttile, c = 2 * slab2 + 2 * ytile;
+    static constexpr int a = 2 * slab1, b = RG * (red + ttile), c = 2 * slab2 + RG * 2 * ytile;   // per row group: red, ttile, two ytiles
     static constexpr int lds_bytes = a > b ? (a > c ? a : c) : (b > c ? b : c);
     static constexpr int n_mid_barriers = C::KS > 1 ? 2 * ilog2(C::KS) : 1;  // tree + T tile written
-    static_assert(SPW >= 1 && NCHX == 2 && R % 32 == 0 && BK2 % 16 == 0, "slab shape");
+    static_assert(SPW >= 1 && NCHX == 2 * RG && R % 32 == 0 && BK2 % 16 == 0 && R % KSL == 0, "slab shape");
     static_assert(C::RS * C::CS * C::KS == NMW_ && CB * C::CS * 32 == R && RA * C::RS == 2, "wave split");
 };
 
@@ -134,8 +149,8 @@ struct Ch2Cfg {
 // channel block: 128 contiguous bytes per row, as in the plain case.  p = kh kw cpb 64.
 struct Ch2Gather { int H, W, Cin, cpb, kh, kw, sign; };
 
-template <int R, bool GATHER>
-__global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restrict__ Xin,
+template <int R, int RG, bool GATHER>
+__global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(const uint16_t* __restrict__ Xin,
                                                          const uint16_t* __restrict__ Pm,
                                                          const uint16_t* __restrict__ Qm,
                                                          uint16_t* __restrict__ Yout,
@@ -143,19 +158,27 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
                                                          int64_t M, int p, int q, int t_pitch, Ch2Gather gg) {
     extern __shared__ __align__(1024) unsigned char lds[];
     using C = Ch2<R>;
-    using L = Ch2Cfg<R>;
+    using L = Ch2Cfg<R, RG>;
+    constexpr int ROWS = L::ROWS, NMW = NMW_ * RG, NMT = 64 * NMW;
+#define ABT_LOADER_WAVE (NMW_ * RG)
     constexpr int RS = C::RS, CS = C::CS, KS = C::KS, CB = L::CB, RA = L::RA, SPW = L::SPW;
     constexpr int BK2 = L::BK2, CPR2 = L::CPR2, KSL = L::KSL;
     constexpr int D1 = L::D1, D2 = L::D2;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t row0 = (int64_t)blockIdx.x * 64;
+    const int64_t row0 = (int64_t)blockIdx.x * ROWS;
     const int ns1 = p / BK1;
     const int n1p = (ns1 + D1 - 1) / D1 * D1;           // stage-1 trip count, padded to the loaders' ring
-    const int ntile = (q + 127) / 128;                  // stage-2 output tiles of 128 columns
+    // stage-2 output tiles of 128 columns: work-group (x, y) of a grid with gridDim.y column parts
+    // does the tiles [tile0, tile0 + ntile) of the ntile_all; every part repeats stage 1 for its rows
+    const int ntile_all = (q + 127) / 128;
+    const int tile0 = (int)(blockIdx.y * (unsigned)ntile_all / gridDim.y);
+    const int ntile = (int)((blockIdx.y + 1) * (unsigned)ntile_all / gridDim.y) - tile0;
     const int ns2 = ntile * KSL;
     const int n2p = (ns2 + L::U2 - 1) / L::U2 * L::U2;  // stage-2 trip count, padded likewise
-    unsigned char* const ttile = lds + L::red;
+    // per row group g: reduction scratch at g * red, T tile at RG * red + g * ttile (stage 1 and T phase);
+    // output staging tile (g, buffer) at 2 * slab2 + (2 g + buffer) * ytile (stage 2)
+    unsigned char* const ttile = lds + RG * L::red;
     unsigned char* const ytile = lds + 2 * L::slab2;
     // Work-groups walk the contraction slabs (stage 1) and the output tiles (stage 2) from
     // different starting points, so that at any instant they touch different columns of
@@ -163,7 +186,7 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
     const int rot1 = (int)(blockIdx.x % (unsigned)ns1);
     const int rot2 = (int)(blockIdx.x % (unsigned)ntile);
     auto slab1_of = [&](int s) { if (s > ns1 - 1) s = ns1 - 1; s += rot1; return s >= ns1 ? s - ns1 : s; };
-    auto tile_of = [&](int t) { if (t > ntile - 1) t = ntile - 1; t += rot2; return t >= ntile ? t - ntile : t; };
+    auto tile_of = [&](int t) { if (t > ntile - 1) t = ntile - 1; t += rot2; return tile0 + (t >= ntile ? t - ntile : t); };
 
     if (wave >= NMW) {
         // ================================================================== loader waves
@@ -174,11 +197,11 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
         // row offset is part of the per-lane offset (the only part the hardware range-checks), so
         // rows past M read as zeros and stores to them are dropped.
         const int lt = tid - NMT;
-        const int64_t rows_valid = M - row0 < 64 ? M - row0 : 64;
+        const int64_t rows_valid = M - row0 < ROWS ? M - row0 : ROWS;
         // gather: the descriptor covers the pixels this work-group's patches can touch
         const int reach = GATHER ? (gg.kh / 2) * gg.W + gg.kw / 2 : 0;
         const int64_t gpix0 = row0 > reach ? row0 - reach : 0;
-        const int64_t gpix1 = row0 + 64 + reach < M ? row0 + 64 + reach : M;
+        const int64_t gpix1 = row0 + ROWS + reach < M ? row0 + ROWS + reach : M;
         const rsrc_t xres = GATHER ? make_rsrc(Xin + gpix0 * gg.Cin, (gpix1 - gpix0) * gg.Cin * 2)
                                    : make_rsrc(Xin + row0 * p, rows_valid * p * 2);
         const rsrc_t pres = make_rsrc(Pm, (int64_t)R * p * 2);
@@ -323,15 +346,15 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
             if (i < L::n_mid_barriers) wg_barrier();
         }
         // T tile is in LDS: store it (the MFMA waves load their operands from it meanwhile)
-        if (Tout != nullptr) {
+        if (Tout != nullptr && blockIdx.y == 0) {
             // rows of Tout are t_pitch elements apart (R for a plain T; more when the tile is a
             // column block of a wider matrix); the descriptor ends with the last valid row
             const rsrc_t tres = make_rsrc(Tout + row0 * t_pitch, ((rows_valid - 1) * t_pitch + R) * 2);
             constexpr int CPT = R / 8;   // 16-byte chunks per T row
-            for (int i = lt; i < 64 * CPT; i += NLT) {
+            for (int i = lt; i < ROWS * CPT; i += NLT) {
                 const int row = i / CPT, ch = i % CPT;
-                buf_store16(*reinterpret_cast<const u32x4*>(ttile + row * L::tpitch + ch * 16), tres,
-                            (row * t_pitch + ch * 8) * 2, 0);
+                buf_store16(*reinterpret_cast<const u32x4*>(ttile + (row >> 6) * L::ttile + (row & 63) * L::tpitch + ch * 16),
+                            tres, (row * t_pitch + ch * 8) * 2, 0);
             }
         }
         if (Yout == nullptr) return;
@@ -345,21 +368,23 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
         // waves during the last slab of t and leaves here, one slab later, as full 256-byte rows, in
         // four pieces per thread (64 rows x 16 chunks over 256 threads): the LDS reads are issued
         // first, the stores are spread between the slab's loads.
-        u32x4 ypiece[4];
-        int ydst[4];
-        bool yleft[4];
+        constexpr int NY = ROWS * 16 / NLT;              // 16-byte pieces of a ROWS x 128 tile per thread
+        u32x4 ypiece[NY];
+        int ydst[NY];
+        bool yleft[NY];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
+        for (int e = 0; e < NY; ++e) {
             const int ci = e * NLT + lt;
             ydst[e] = ((ci >> 4) * q + (ci & 15) * 8) * 2;
             yleft[e] = (ci & 15) < 8;                    // in the left 64 columns: all a ragged last tile has
         }
         auto flush_read = [&](int seq) {
-            const unsigned char* yt = ytile + (seq & 1) * L::ytile;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int e = 0; e < NY; ++e) {
                 const int ci = e * NLT + lt;
-                ypiece[e] = *reinterpret_cast<const u32x4*>(yt + (ci >> 4) * L::ypitch + (ci & 15) * 16);
+                const int r = ci >> 4;
+                const unsigned char* yt = ytile + ((r >> 6) * 2 + (seq & 1)) * L::ytile;
+                ypiece[e] = *reinterpret_cast<const u32x4*>(yt + (r & 63) * L::ypitch + (ci & 15) * 16);
             }
         };
         auto flush_store = [&](int seq, int e) {
@@ -381,12 +406,12 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
                 *reinterpret_cast<u32x4*>(lds + slot * L::slab2 + qoff[e]) = rg[e];
                 rg[e] = buf_load16(qres, qsrc[e], so);
                 __builtin_amdgcn_sched_barrier(0);
-                if (e < 4 && flush) flush_store(seq, e);
+                if (e < NY && flush) flush_store(seq, e);
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (flush) {
 #pragma unroll
-                for (int e = L::NCHQ; e < 4; ++e) flush_store(seq, e);
+                for (int e = L::NCHQ; e < NY; ++e) flush_store(seq, e);
             }
         };
         int flushed = 0;
@@ -405,7 +430,7 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
         if (flushed < ntile) {
             flush_read(flushed);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) flush_store(flushed, e);
+            for (int e = 0; e < NY; ++e) flush_store(flushed, e);
         }
         TMARK(1, 2);
         return;
@@ -413,7 +438,10 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
 
     // ====================================================================== MFMA waves
     const int lj = lane & 31, lh = lane >> 5;
-    const int cs = wave % CS, rs = (wave / CS) % RS, ks = wave / (CS * RS);
+    const int grp = wave >> 2, w4 = wave & 3;           // row group, wave inside the group
+    const int cs = w4 % CS, rs = (w4 / CS) % RS, ks = w4 / (CS * RS);
+    unsigned char* const ttile_g = ttile + grp * L::ttile;
+    unsigned char* const red_g = lds + grp * L::red;
 
     // ------------------------------------------------------------------ stage 1
     f32x16 acc1[RA][CB];
@@ -437,12 +465,12 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
                 u32x4 xf[RA], pf[CB];
 #pragma unroll
                 for (int a = 0; a < RA; ++a) {
-                    const int row = 32 * (rs * RA + a) + lj;
+                    const int row = 64 * grp + 32 * (rs * RA + a) + lj;
                     xf[a] = *reinterpret_cast<const u32x4*>(base + row * (BK1 * 2) + swz<CPR1>(qc, row) * 16);
                 }
 #pragma unroll
                 for (int b = 0; b < CB; ++b) {
-                    const int row = 64 + (cs * CB + b) * 32 + lj;
+                    const int row = ROWS + (cs * CB + b) * 32 + lj;
                     pf[b] = *reinterpret_cast<const u32x4*>(base + row * (BK1 * 2) + swz<CPR1>(qc, row) * 16);
                 }
 #pragma unroll
@@ -464,7 +492,7 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
             for (int g = 0; g < 4; ++g) {
                 u32x2 o = {pack2_bf16(blk[b][4 * g + 0], blk[b][4 * g + 1]),
                            pack2_bf16(blk[b][4 * g + 2], blk[b][4 * g + 3])};
-                *reinterpret_cast<u32x2*>(ttile + (32 * (rs * RA + a) + lj) * L::tpitch +
+                *reinterpret_cast<u32x2*>(ttile_g + (32 * (rs * RA + a) + lj) * L::tpitch +
                                           (32 * (cs * CB + b) + 8 * g + 4 * lh) * 2) = o;
             }
     };
@@ -472,7 +500,7 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
         // Two contraction groups: the partners swap halves instead of one sending everything.  Wave ks
         // sends its row block 1 - ks, adds what it receives to its row block ks and converts that
         // half of T itself: every wave stores and loads half as much, and all four convert.
-        f32x4* red = reinterpret_cast<f32x4*>(lds);
+        f32x4* red = reinterpret_cast<f32x4*>(red_g);
         auto swap_and_emit = [&](const f32x16 (&send)[CB], f32x16 (&keep)[CB], int a_keep) {
             f32x4* dst = red + (size_t)((ks * CS + cs) * CB) * 4 * 64;
 #pragma unroll
@@ -498,7 +526,7 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
     } else {
         if constexpr (KS > 1) {
             // tree; layout: [wave slot][block (a,b)][quad g][lane][4 floats]: one 16-byte access per quad
-            f32x4* red = reinterpret_cast<f32x4*>(lds);
+            f32x4* red = reinterpret_cast<f32x4*>(red_g);
             const int wslot = rs * CS + cs;
 #pragma unroll
             for (int half = KS / 2; half >= 1; half >>= 1) {
@@ -539,15 +567,15 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
     wg_barrier();                                       // last of the mid barriers: T tile complete
     if (Yout == nullptr) return;
 
-    // Stage 2: wave w owns all 64 rows of T (in registers, as MFMA B operands) and column block w
-    // (32 columns) of every 128-column output tile.
+    // Stage 2: wave w4 of a row group owns the group's 64 rows of T (in registers, as MFMA B operands)
+    // and column block w4 (32 columns) of every 128-column output tile.
     constexpr int KB = R / 16;
     u32x4 tf[2][KB];   // T[32a + lj][16kb + 8 lh .. +7]
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
-            tf[a][kb] = *reinterpret_cast<const u32x4*>(ttile + (32 * a + lj) * L::tpitch + (16 * kb + 8 * lh) * 2);
+            tf[a][kb] = *reinterpret_cast<const u32x4*>(ttile_g + (32 * a + lj) * L::tpitch + (16 * kb + 8 * lh) * 2);
     wg_barrier();                                       // T tile consumed; stage 2 takes over the LDS
     TMARK(0, 4);
     wg_barrier();                                       // Q slab 0 is in slot 0
@@ -567,7 +595,7 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
             TSTAMP(0, 0, s0 + kslab);
             if (live) {
                 const unsigned char* base = lds + ((s0 + kslab) & 1) * L::slab2;
-                const int row = 32 * wave + lj;
+                const int row = 32 * w4 + lj;
 #pragma unroll
                 for (int kk = 0; kk < BK2 / 16; ++kk) {
                     const u32x4 qf = *reinterpret_cast<const u32x4*>(
@@ -578,14 +606,14 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
                 }
                 if (kslab == KSL - 1) {
                     // lane holds Y[32a + lj][32 wave + 8g + 4 lh + (0..3)] of this 64 x 128 tile
-                    unsigned char* yt = ytile + (t & 1) * L::ytile;
+                    unsigned char* yt = ytile + (grp * 2 + (t & 1)) * L::ytile;
 #pragma unroll
                     for (int a = 0; a < 2; ++a)
 #pragma unroll
                         for (int g = 0; g < 4; ++g) {
                             u32x2 o = {pack2_bf16(acc2[a][4 * g + 0], acc2[a][4 * g + 1]),
                                        pack2_bf16(acc2[a][4 * g + 2], acc2[a][4 * g + 3])};
-                            *reinterpret_cast<u32x2*>(yt + (32 * a + lj) * L::ypitch + (32 * wave + 8 * g + 4 * lh) * 2) = o;
+                            *reinterpret_cast<u32x2*>(yt + (32 * a + lj) * L::ypitch + (32 * w4 + 8 * g + 4 * lh) * 2) = o;
                         }
                 }
             }
@@ -596,34 +624,60 @@ __global__ __launch_bounds__(NT) void chain2_bf16_kernel(const uint16_t* __restr
     TMARK(0, 6);
 }
 
-template <int R, bool GATHER>
-hipError_t launch_chain2_r(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
-                           int64_t M, int p, int q, int t_pitch, const Ch2Gather& gg, hipStream_t s) {
-    constexpr int lds_bytes = Ch2Cfg<R>::lds_bytes;
+#undef ABT_LOADER_WAVE
+
+template <int R, int RG, bool GATHER>
+hipError_t launch_chain_r(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
+                          int64_t M, int p, int q, int t_pitch, const Ch2Gather& gg, int parts, hipStream_t s) {
+    using L = Ch2Cfg<R, RG>;
+    constexpr int lds_bytes = L::lds_bytes;
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
+    // column parts: each does its share of the 128-column output tiles (and repeats stage 1)
+    if (parts < 1 || parts > 64 || (Yout != nullptr && parts > (q + 127) / 128) || (Yout == nullptr && parts != 1))
+        return hipErrorInvalidValue;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chain2_bf16_kernel<R, GATHER>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chain2_bf16_kernel<R, RG, GATHER>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((chain2_bf16_kernel<R, GATHER>), dim3((unsigned)ceil_div(M, 64)), dim3(NT), lds_bytes, s,
+    hipLaunchKernelGGL((chain2_bf16_kernel<R, RG, GATHER>), dim3((unsigned)ceil_div(M, L::ROWS), (unsigned)parts),
+                       dim3(64 * (NMW_ * RG + NLW)), lds_bytes, s,
                        (const uint16_t*)Xin, (const uint16_t*)P, (const uint16_t*)Q,
                        (uint16_t*)Yout, (uint16_t*)Tout, M, p, q, t_pitch, gg);
     return hipGetLastError();
 }
 
 template <bool GATHER>
-hipError_t launch_chain2_any(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
-                             int64_t M, int p, int q, int R, int t_pitch, const Ch2Gather& gg, hipStream_t s) {
+hipError_t launch_chain_64(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
+                           int64_t M, int p, int q, int R, int t_pitch, const Ch2Gather& gg, hipStream_t s) {
     switch (R) {
-#define ABT_CASE(RR) case RR: return launch_chain2_r<RR, GATHER>(Xin, P, Q, Yout, Tout, M, p, q, t_pitch, gg, s);
+#define ABT_CASE(RR) case RR: return launch_chain_r<RR, 1, GATHER>(Xin, P, Q, Yout, Tout, M, p, q, t_pitch, gg, 1, s);
         ABT_CASE(32) ABT_CASE(64) ABT_CASE(96) ABT_CASE(128) ABT_CASE(160) ABT_CASE(192)
         ABT_CASE(256) ABT_CASE(320) ABT_CASE(384)
 #undef ABT_CASE
         default: return hipErrorInvalidValue;
     }
+}
+
+template <bool GATHER>
+hipError_t launch_chain_128(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
+                            int64_t M, int p, int q, int R, int t_pitch, const Ch2Gather& gg, int parts, hipStream_t s) {
+    switch (R) {
+#define ABT_CASE(RR) case RR: return launch_chain_r<RR, 2, GATHER>(Xin, P, Q, Yout, Tout, M, p, q, t_pitch, gg, parts, s);
+        ABT_CASE(32) ABT_CASE(64) ABT_CASE(96) ABT_CASE(128) ABT_CASE(192)
+#undef ABT_CASE
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// checks shared by the two gathered launchers; rows = work-group height
+bool gather_ok(const PatchGeom& g, int64_t M, int64_t p, int t_pitch, int R, int rows) {
+    return g.H >= 1 && g.W >= 1 && g.Cin >= 8 && g.Cin % 8 == 0 && g.kh >= 1 && g.kw >= 1 && (g.kh & 1) && (g.kw & 1) &&
+           (g.sign == 1 || g.sign == -1) && M % ((int64_t)g.H * g.W) == 0 && p <= (1 << 20) && t_pitch >= R &&
+           // 32-bit offsets inside a work-group's window of the image
+           ((int64_t)rows + 2 * ((g.kh / 2) * (int64_t)g.W + g.kw / 2)) * g.Cin * 2 < kBufMaxBytes;
 }
 
 }  // namespace
@@ -636,22 +690,42 @@ bool chain2_supports(int R, int p, int q) {
     }
 }
 
+// Ranks whose two reduction scratches, T tiles and staging tiles fit the LDS and whose T operands
+// fit the 168 registers twelve waves leave (R = 384 would need 192 for them alone).
+bool chain3_supports(int R, int p, int q) {
+    if (p % 64 != 0 || p > (1 << 20) || q > (1 << 20)) return false;
+    switch (R) {
+        case 32: case 64: case 96: case 128: case 192: return true;
+        default: return false;
+    }
+}
+
 hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                               int64_t M, int p, int q, int R, hipStream_t s) {
-    return launch_chain2_any<false>(Xin, P, Q, Yout, Tout, M, p, q, R, R, Ch2Gather{}, s);
+    return launch_chain_64<false>(Xin, P, Q, Yout, Tout, M, p, q, R, R, Ch2Gather{}, s);
+}
+
+hipError_t launch_chain3_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
+                              int64_t M, int p, int q, int R, int parts, hipStream_t s) {
+    return launch_chain_128<false>(Xin, P, Q, Yout, Tout, M, p, q, R, R, Ch2Gather{}, parts, s);
 }
 
 hipError_t launch_chain2_gather_bf16(const void* image, const PatchGeom& g, const void* P, const void* Q,
                                      void* Yout, void* Tout, int t_pitch, int64_t M, int q, int R, hipStream_t s) {
     const int cpb = (g.Cin + 63) / 64;
     const int64_t p = (int64_t)g.kh * g.kw * cpb * 64;
-    // 32-bit offsets: a work-group's window of the image, and the factor P [R, p]
-    if (g.H < 1 || g.W < 1 || g.Cin < 8 || g.Cin % 8 || g.kh < 1 || g.kw < 1 || !(g.kh & 1) || !(g.kw & 1) ||
-        (g.sign != 1 && g.sign != -1) || M % ((int64_t)g.H * g.W) != 0 || p > (1 << 20) || !chain2_supports(R, (int)p, q) ||
-        ((int64_t)64 + 2 * ((g.kh / 2) * (int64_t)g.W + g.kw / 2)) * g.Cin * 2 >= kBufMaxBytes || t_pitch < R)
-        return hipErrorInvalidValue;
+    if (!gather_ok(g, M, p, t_pitch, R, 64) || !chain2_supports(R, (int)p, q)) return hipErrorInvalidValue;
     const Ch2Gather gg{g.H, g.W, g.Cin, cpb, g.kh, g.kw, g.sign};
-    return launch_chain2_any<true>(image, P, Q, Yout, Tout, M, (int)p, q, R, t_pitch, gg, s);
+    return launch_chain_64<true>(image, P, Q, Yout, Tout, M, (int)p, q, R, t_pitch, gg, s);
+}
+
+hipError_t launch_chain3_gather_bf16(const void* image, const PatchGeom& g, const void* P, const void* Q,
+                                     void* Yout, void* Tout, int t_pitch, int64_t M, int q, int R, hipStream_t s) {
+    const int cpb = (g.Cin + 63) / 64;
+    const int64_t p = (int64_t)g.kh * g.kw * cpb * 64;
+    if (!gather_ok(g, M, p, t_pitch, R, 128) || !chain3_supports(R, (int)p, q)) return hipErrorInvalidValue;
+    const Ch2Gather gg{g.H, g.W, g.Cin, cpb, g.kh, g.kw, g.sign};
+    return launch_chain_128<true>(image, P, Q, Yout, Tout, M, (int)p, q, R, t_pitch, gg, 1, s);
 }
 
 }  // namespace abt
