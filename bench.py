@@ -139,7 +139,7 @@ def main():
     bwd_avg, bwd_med, bwd_min = event_ms(step.bwd, min(args.steps, 100))
     achieved_gbs = step.bytes_fwd / (fwd_avg * 1e-3) / 1e9
     roofline = {
-        "kernel": "chain2_bf16_kernel<192, false> (lr_linear_fwd: T = X B^T, Y = T A^T fused, one launch per call)",
+        "kernel": "chain2_bf16_kernel<192, 1, false> (lr_linear_fwd: T = X B^T, Y = T A^T fused, one launch per call)",
         "bound": "hbm", "achieved": round(achieved_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
         "frac": round(achieved_gbs / PEAK_HBM_GBS, 4), "traffic": CHAIN_FWD_TRAFFIC_BYTES,
         "algorithmic_bytes_per_launch": step.bytes_fwd,
