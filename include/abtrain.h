@@ -6,14 +6,18 @@
  * trains the factors in independent groups and periodically merges the group copies
  * (Algorithm 1: all-reduce of A and of B, W <- A B, re-decomposition with the rank rule
  * "drop singular values below sigmaCutoff * sigma_max").  This library is that hot path on
- * one GPU: the factored layer's forward and backward, and the merge of G factor copies.
+ * one GPU: the factored layer's forward and backward, and the merge of G factor copies; beside
+ * them the decomposition of a dense weight (ab_factorize), the optimiser step of the group phase
+ * (ab_adamw_step), W <- A B (ab_reconstruct) and the factored layer for convolution weights
+ * (lr_conv_fwd, lr_conv_bwd).
  *
  * Conventions shared by every entry point
  *   - All matrices are row-major and contiguous (leading dimension = number of columns).
  *   - Unless a parameter is documented as a HOST pointer it is a DEVICE pointer owned by the
  *     caller; the library never allocates, frees or retains caller memory.
- *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  lr_linear_fwd and
- *     lr_linear_bwd enqueue work on it and return without synchronising the host.  ab_merge and
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  lr_linear_fwd,
+ *     lr_linear_bwd, lr_conv_fwd, lr_conv_bwd, ab_adamw_step and ab_reconstruct enqueue work on it
+ *     and return without synchronising the host.  ab_merge and
  *     ab_merge_batched wait for the stream a few times (after uploading their layer table, and
  *     between Jacobi sweeps to see whether every layer has converged); the back-projection
  *     they enqueue last may still be running when they return.
