@@ -297,6 +297,14 @@ int abt_set_chain_parts(int parts);
  * returns the previous value. */
 int abt_set_jacobi_max_sweeps(int max_sweeps);
 
+/* Upper bound on the layer groups of the Jacobi stage of a batched merge (Section "Methodology",
+ * the re-decomposition of every layer): the layers of a batch are independent, and the library
+ * runs them in up to four groups on streams of its own (default priority, joined back into the
+ * caller's stream before the call returns) so that the phases of their rounds overlap.  0 = as
+ * many as the library allows (default), 1 = everything on the caller's stream.  A measurement
+ * switch; returns the previous setting. */
+int abt_set_merge_groups(int groups);
+
 #ifdef __cplusplus
 }
 #endif

@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "lib
 _lib = None
 
 EXPORTS = (
-    "abt_status_string", "abt_set_jacobi_max_sweeps", "abt_set_chain_rows", "abt_set_chain_parts",
+    "abt_status_string", "abt_set_jacobi_max_sweeps", "abt_set_merge_groups", "abt_set_chain_rows", "abt_set_chain_parts",
     "lr_linear_fwd", "lr_linear_fwd_workspace_bytes",
     "lr_linear_bwd", "lr_linear_bwd_workspace_bytes",
     "ab_merge", "ab_merge_workspace_bytes",
@@ -86,6 +86,8 @@ def load():
     lib.abt_set_chain_parts.argtypes = [ci]
     lib.abt_set_jacobi_max_sweeps.restype = ci
     lib.abt_set_jacobi_max_sweeps.argtypes = [ci]
+    lib.abt_set_merge_groups.restype = ci
+    lib.abt_set_merge_groups.argtypes = [ci]
     lib.lr_linear_fwd.restype = ci
     lib.lr_linear_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, vp, sz, vp]
     lib.lr_linear_fwd_workspace_bytes.restype = sz
@@ -153,6 +155,10 @@ def set_chain_parts(parts: int) -> int:
 
 def set_jacobi_max_sweeps(n: int) -> int:
     return load().abt_set_jacobi_max_sweeps(int(n))
+
+
+def set_merge_groups(n: int) -> int:
+    return load().abt_set_merge_groups(int(n))
 
 
 # --------------------------------------------------------------------------------------

@@ -130,6 +130,7 @@ size_t merge_workspace_bytes(const abt_merge_desc* layers, int L);
 hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int max_sweeps, hipStream_t s);
 hipError_t merge_read_info(const void* workspace, int layer, int32_t out[4], hipStream_t s);
 hipError_t launch_identity_f32(float* dst, int K, hipStream_t s);   // dst[K, K] = I
+int merge_set_groups(int n);   // upper bound on the layer groups (streams) of the Jacobi stage; returns the previous one
 
 // ------------------------------------------------------------------ optimiser step
 // Adam with decoupled weight decay on up to any number of tensors (kAdamwMaxTensors per launch).

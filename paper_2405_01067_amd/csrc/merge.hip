@@ -15,47 +15,15 @@
 //
 // mode 1 (mean of reconstructions) uses the same pipeline on the concatenations
 // Abar = [A_1 .. A_G] / G (m x Gk) and Bbar = [B_1; ..; B_G] (Gk x n).
+#include <atomic>
+#include <mutex>
 #include <vector>
 
-#include "common.h"
+#include "merge_internal.h"
 
 namespace abt {
 
 namespace {
-
-constexpr int kInfoInts = 4;      // per layer: sweeps, n_sigma, converged, k'
-constexpr int kMaxSweepsCap = 64;
-constexpr double kRotateTol = 1e-10;   // |cos| above which a column pair is rotated
-// A sweep in which no visited pair had |cos| above kSignifTol ends the iteration.  Every such pair
-// was still rotated to orthogonality when visited and the later rotations of that sweep disturb it
-// only by O(cos^2), so the cosines left behind are of order 1e-10 (1e-7 gave the same results to
-// the last bit on the config-5 layers at one more sweep).
-constexpr double kSignifTol = 1e-5;
-constexpr double kSigmaFloor = 1e-7;   // sigma_i <= floor * sigma_1: singular vectors returned as zero
-// A column of C with |c|^2 below kZeroColumn2 ||C||_F^2 (|c| < 1e-9 ||C||_F) is numerically zero
-// and is left alone: what it holds is the rounding noise (about 1e-16 ||C||) of the large columns
-// it was rotated with, so its angles are noise at the level the convergence test looks at and
-// would keep the iteration from ending.  It belongs to a singular value far below
-// kSigmaFloor sigma_1 (||C||_F <= sqrt(K) sigma_1).
-constexpr double kZeroColumn2 = 1e-18;
-
-struct LayerDev {
-    const float* const* A_ptrs;
-    const float* const* B_ptrs;
-    int G, mode, m, n, k, K, k_cap, k_fixed;
-    float tau;
-    int jb, nb;            // Jacobi: columns per block, number of blocks
-    float* Abar; float* Bbar;
-    double* LA; double* GB; double* LB; double* Ct; double* Yt;
-    double* sigma; double* s3; double* s5;
-    double* trace;         // [10]: trace(G_A), trace(G_B), then eight partial sums of ||C||_F^2
-    double* nrm;           // [K]: squared column norms of C, refreshed every sweep, updated by rotations
-    int* perm;
-    float* PA; float* PB;
-    int* rotated;          // [kMaxSweepsCap + 1]
-    int* info;             // [kInfoInts]
-    float* S_out; int32_t* k_out;
-};
 
 // ------------------------------------------------------------------------------------------
 // zero-fill by a kernel (fill kernels, not memset nodes, are what stays correct under graph replay)
@@ -417,13 +385,6 @@ __global__ __launch_bounds__(256) void frob2_kernel(const LayerDev* __restrict__
     }
     if (threadIdx.x == 0) L.trace[2 + blockIdx.x] = red[0];
 }
-__device__ __forceinline__ double frob2(const LayerDev& L) {
-    double s = 0.0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) s += L.trace[2 + j];
-    return s;
-}
-
 // ------------------------------------------------------------------------------------------
 // Stage 5: one-sided Jacobi on the columns of C, held as the rows of Ct (K x K, fp64).
 // Columns are grouped in blocks of jb; a sweep = one intra-block pass (all pairs inside every
@@ -436,41 +397,6 @@ __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
     return v;
-}
-
-// Rotation for a pair with squared norms alpha, beta and inner product gamma; returns false when
-// the pair counts as orthogonal.  x' = c x - s y, y' = s x + c y.
-// A column whose squared norm is below `floor2` (kZeroColumn2 ||C||_F^2) is numerically zero and
-// is left alone (rank-deficient cores).
-__device__ __forceinline__ bool jacobi_rotation(double alpha, double beta, double gamma, double floor2,
-                                                double& c, double& s, bool& significant, double* tangent = nullptr) {
-    const double lim = alpha * beta;
-    const double g2 = gamma * gamma;
-    significant = false;
-    if (!(alpha > floor2) || !(beta > floor2)) return false;
-    significant = g2 > (kSignifTol * kSignifTol) * lim;
-    if (!(g2 > (kRotateTol * kRotateTol) * lim)) return false;
-    // tangent of the rotation angle, the smaller root of t^2 + 2 zeta t - 1 = 0 with
-    // zeta = (beta - alpha) / (2 gamma), written so that it costs one square root and one division:
-    // t = 2 gamma sign(d) / (|d| + sqrt(d^2 + 4 gamma^2)), d = beta - alpha
-    const double d = beta - alpha;
-    const double g2x = 2.0 * gamma;
-    const double tn = (d >= 0.0 ? g2x : -g2x) / (fabs(d) + sqrt(fma(d, d, g2x * g2x)));
-    // c = (1 + t^2)^(-1/2): hardware reciprocal square root refined by two Newton steps (the
-    // rotation stays orthogonal to rounding: c^2 + s^2 = c^2 (1 + t^2))
-    const double w = fma(tn, tn, 1.0);
-    double y = __builtin_amdgcn_rsq(w);
-    y = y * fma(-0.5 * w, y * y, 1.5);
-    y = y * fma(-0.5 * w, y * y, 1.5);
-    c = y;
-    s = c * tn;
-    if (tangent) *tangent = tn;
-    return true;
-}
-
-__device__ __forceinline__ bool sweep_finished(const LayerDev& L, int sweep) {
-    // the previous sweep found no significant pair: the iteration has converged
-    return sweep > 0 && L.rotated[sweep - 1] == 0;
 }
 
 // NX = ceil(K / 64) upper bound (elements of one column per lane).
@@ -533,203 +459,6 @@ __global__ __launch_bounds__(1024) void jacobi_cross_kernel(const LayerDev* __re
     for (int e = 0; e < NX; ++e) { const int r = lane + 64 * e; if (r < K) left_col[r] = x[e]; }
     for (int r = lane; r < K; r += 64) right_blk[(int64_t)wave * K + r] = right[wave * K + r];
     if (any_signif && lane == 0) L.rotated[sweep] = 1;
-}
-
-// Sum over each group of 16 consecutive lanes (a DPP row), result in every lane of the group:
-// two quad permutes, then rotations by 4 and 8 lanes inside the row.  No LDS traffic.
-template <int CTRL>
-__device__ __forceinline__ double dpp_f64(double v) {
-    int lo = __double2loint(v), hi = __double2hiint(v);
-    lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xf, 0xf, false);
-    hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xf, 0xf, false);
-    return __hiloint2double(hi, lo);
-}
-__device__ __forceinline__ double row16_sum(double v) {
-    v += dpp_f64<0xB1>(v);    // quad_perm [1,0,3,2]
-    v += dpp_f64<0x4E>(v);    // quad_perm [2,3,0,1]
-    v += dpp_f64<0x124>(v);   // row_ror:4
-    v += dpp_f64<0x128>(v);   // row_ror:8
-    return v;
-}
-
-// Cross round for cores with K <= 32 NE2 <= 768 and blocks of 16 columns.  A work-group of 256
-// threads owns one block pair; a group of 16 lanes owns one left column (in registers, two
-// consecutive rows per lane and 32-row stride) and meets the 16 right columns (in LDS) one per step:
-// four column pairs per wave and step, each needing a single inner product reduced over 16 lanes.
-// The squared norms are not recomputed per pair: they are carried along (nrm, refreshed from the data
-// by the intra-block kernel at the start of every sweep) and updated with the rotation,
-// |x'|^2 = |x|^2 - t gamma, |y'|^2 = |y|^2 + t gamma.
-typedef __attribute__((ext_vector_type(2))) double f64x2;
-template <int NE2>
-__global__ __launch_bounds__(256) void jacobi_cross16_kernel(const LayerDev* __restrict__ layers,
-                                                             const int2* __restrict__ wg_map,
-                                                             int sweep, int round) {
-    extern __shared__ __align__(16) unsigned char lds_raw[];
-    const int2 wm = wg_map[blockIdx.x];                   // (layer, pair slot)
-    const LayerDev& L = layers[wm.x];
-    if (sweep_finished(L, sweep)) return;
-    const int nb = L.nb, K = L.K;
-    if (round >= nb - 1 || L.jb != 16 || K > 32 * NE2) return;
-    int bI, bJ;
-    if (wm.y == 0) { bI = nb - 1; bJ = round; }
-    else { bI = (round + wm.y) % (nb - 1); bJ = (round - wm.y + (nb - 1)) % (nb - 1); }
-    const int pitch = K + 16;                             // columns 128 bytes apart in the banks
-    double* right = reinterpret_cast<double*>(lds_raw);   // [16][pitch]
-    double* rn = right + 16 * pitch;                      // [16] squared norms of the right columns
-    const int tid = threadIdx.x, g = tid >> 4, l16 = tid & 15;
-
-    double* left_col = L.Ct + (int64_t)(bI * 16 + g) * K;
-    double* right_col = L.Ct + (int64_t)(bJ * 16 + g) * K;
-    f64x2 x[NE2];
-#pragma unroll
-    for (int j = 0; j < NE2; ++j) {
-        const int r = 32 * j + 2 * l16;
-        x[j] = f64x2{0.0, 0.0};
-        if (r < K) {
-            x[j] = *reinterpret_cast<const f64x2*>(left_col + r);
-            *reinterpret_cast<f64x2*>(right + g * pitch + r) = *reinterpret_cast<const f64x2*>(right_col + r);
-        }
-    }
-    if (tid < 16) rn[tid] = L.nrm[bJ * 16 + tid];
-    double alpha = L.nrm[bI * 16 + g];
-    __syncthreads();
-
-    const double floor2 = kZeroColumn2 * frob2(L);
-    bool any_signif = false;
-    for (int step = 0; step < 16; ++step) {
-        const int ci = (g + step) & 15;
-        double* ycol = right + ci * pitch;
-        f64x2 y[NE2];
-        double gsum[4] = {0.0, 0.0, 0.0, 0.0};           // four independent chains, fixed order
-#pragma unroll
-        for (int j = 0; j < NE2; ++j) {
-            const int r = 32 * j + 2 * l16;
-            y[j] = f64x2{0.0, 0.0};
-            if (r < K) y[j] = *reinterpret_cast<const f64x2*>(ycol + r);
-            gsum[2 * (j & 1)] = fma(x[j][0], y[j][0], gsum[2 * (j & 1)]);
-            gsum[2 * (j & 1) + 1] = fma(x[j][1], y[j][1], gsum[2 * (j & 1) + 1]);
-        }
-        double gamma = row16_sum((gsum[0] + gsum[1]) + (gsum[2] + gsum[3]));
-        const double beta = rn[ci];
-        double c, s, t; bool signif;
-        if (jacobi_rotation(alpha, beta, gamma, floor2, c, s, signif, &t)) {
-#pragma unroll
-            for (int j = 0; j < NE2; ++j) {
-                const int r = 32 * j + 2 * l16;
-                const f64x2 xn = {c * x[j][0] - s * y[j][0], c * x[j][1] - s * y[j][1]};
-                const f64x2 yn = {s * x[j][0] + c * y[j][0], s * x[j][1] + c * y[j][1]};
-                x[j] = xn;
-                if (r < K) *reinterpret_cast<f64x2*>(ycol + r) = yn;
-            }
-            alpha -= t * gamma;
-            if (l16 == 0) rn[ci] = beta + t * gamma;
-        }
-        any_signif |= signif;
-        __syncthreads();
-    }
-#pragma unroll
-    for (int j = 0; j < NE2; ++j) {
-        const int r = 32 * j + 2 * l16;
-        if (r < K) {
-            *reinterpret_cast<f64x2*>(left_col + r) = x[j];
-            *reinterpret_cast<f64x2*>(right_col + r) = *reinterpret_cast<const f64x2*>(right + g * pitch + r);
-        }
-    }
-    if (l16 == 0) L.nrm[bI * 16 + g] = alpha;
-    if (tid < 16) L.nrm[bJ * 16 + tid] = rn[tid];
-    if (any_signif && l16 == 0) L.rotated[sweep] = 1;
-}
-
-// All pairs inside one block of 16 columns for cores with K <= 32 NE2 <= 768: the block lives in
-// LDS, a work-group of 128 threads = 8 groups of 16 lanes rotates 8 disjoint pairs per step, 15
-// steps (round-robin).  Squared norms are computed once at the start, carried with the rotations,
-// and written out at the end (recomputed from the final data) for the cross rounds to start from.
-template <int NE2>
-__global__ __launch_bounds__(128) void jacobi_intra16_kernel(const LayerDev* __restrict__ layers,
-                                                             const int2* __restrict__ wg_map, int sweep) {
-    extern __shared__ __align__(16) unsigned char lds_raw[];
-    const int2 wm = wg_map[blockIdx.x];                   // (layer, block)
-    const LayerDev& L = layers[wm.x];
-    if (sweep_finished(L, sweep)) return;
-    const int K = L.K;
-    if (L.jb != 16 || K > 32 * NE2) return;
-    const int pitch = K + 16;
-    double* cols = reinterpret_cast<double*>(lds_raw);    // [16][pitch]
-    double* cn = cols + 16 * pitch;                       // [16] squared norms
-    const int tid = threadIdx.x, g = tid >> 4, l16 = tid & 15;
-    double* blk = L.Ct + (int64_t)(wm.y * 16) * K;
-    // load two columns per group, with their squared norms
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int cidx = g + 8 * h;
-        double ss = 0.0;
-#pragma unroll
-        for (int j = 0; j < NE2; ++j) {
-            const int r = 32 * j + 2 * l16;
-            if (r < K) {
-                const f64x2 v = *reinterpret_cast<const f64x2*>(blk + (int64_t)cidx * K + r);
-                *reinterpret_cast<f64x2*>(cols + cidx * pitch + r) = v;
-                ss = fma(v[0], v[0], ss);
-                ss = fma(v[1], v[1], ss);
-            }
-        }
-        ss = row16_sum(ss);
-        if (l16 == 0) cn[cidx] = ss;
-    }
-    __syncthreads();
-    const double floor2 = kZeroColumn2 * frob2(L);
-    bool any_signif = false;
-    for (int round = 0; round < 15; ++round) {
-        int p, q;
-        if (g == 0) { p = 15; q = round; }
-        else { p = (round + g) % 15; q = (round - g + 15) % 15; }
-        double* xc = cols + p * pitch;
-        double* yc = cols + q * pitch;
-        f64x2 x[NE2], y[NE2];
-        double gsum[4] = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-        for (int j = 0; j < NE2; ++j) {
-            const int r = 32 * j + 2 * l16;
-            x[j] = f64x2{0.0, 0.0}; y[j] = f64x2{0.0, 0.0};
-            if (r < K) { x[j] = *reinterpret_cast<const f64x2*>(xc + r); y[j] = *reinterpret_cast<const f64x2*>(yc + r); }
-            gsum[2 * (j & 1)] = fma(x[j][0], y[j][0], gsum[2 * (j & 1)]);
-            gsum[2 * (j & 1) + 1] = fma(x[j][1], y[j][1], gsum[2 * (j & 1) + 1]);
-        }
-        double gamma = row16_sum((gsum[0] + gsum[1]) + (gsum[2] + gsum[3]));
-        const double alpha = cn[p], beta = cn[q];
-        double c, s, t; bool signif;
-        if (jacobi_rotation(alpha, beta, gamma, floor2, c, s, signif, &t)) {
-#pragma unroll
-            for (int j = 0; j < NE2; ++j) {
-                const int r = 32 * j + 2 * l16;
-                if (r < K) {
-                    *reinterpret_cast<f64x2*>(xc + r) = f64x2{c * x[j][0] - s * y[j][0], c * x[j][1] - s * y[j][1]};
-                    *reinterpret_cast<f64x2*>(yc + r) = f64x2{s * x[j][0] + c * y[j][0], s * x[j][1] + c * y[j][1]};
-                }
-            }
-            if (l16 == 0) { cn[p] = alpha - t * gamma; cn[q] = beta + t * gamma; }
-        }
-        any_signif |= signif;
-        __syncthreads();
-    }
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int cidx = g + 8 * h;
-        double ss = 0.0;
-#pragma unroll
-        for (int j = 0; j < NE2; ++j) {
-            const int r = 32 * j + 2 * l16;
-            if (r < K) {
-                const f64x2 v = *reinterpret_cast<const f64x2*>(cols + cidx * pitch + r);
-                *reinterpret_cast<f64x2*>(blk + (int64_t)cidx * K + r) = v;
-                ss = fma(v[0], v[0], ss);
-                ss = fma(v[1], v[1], ss);
-            }
-        }
-        ss = row16_sum(ss);
-        if (l16 == 0) L.nrm[wm.y * 16 + cidx] = ss;
-    }
-    if (any_signif && l16 == 0) L.rotated[sweep] = 1;
 }
 
 // All pairs inside one block of jb columns (jb even): jb - 1 rounds of jb / 2 disjoint pairs.
@@ -956,30 +685,6 @@ hipError_t launch_jacobi_sweep(const Plan& p, const LayerDev* dl, const int2* cr
         if (e != hipSuccess) return e;
         attr_bytes = lds_cross;
     }
-    if (p.K_max <= 768) {
-        // every layer has blocks of 16 columns: the 16-lane-group kernels, sized for the widest core
-        const size_t lds16 = sizeof(double) * (16 * (size_t)(p.K_max + 16) + 16);
-        static size_t attr16_by_size[4] = {0, 0, 0, 0};
-        auto run = [&](auto kern_intra, auto kern_cross, size_t& attr16) -> hipError_t {
-            if (lds16 > attr16) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_intra),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds16);
-                if (e != hipSuccess) return e;
-                e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_cross),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds16);
-                if (e != hipSuccess) return e;
-                attr16 = lds16;
-            }
-            hipLaunchKernelGGL(kern_intra, dim3(p.n_wg_intra), dim3(128), lds16, s, dl, intra, sweep);
-            for (int round = 0; round < p.nb_max - 1; ++round)
-                hipLaunchKernelGGL(kern_cross, dim3(p.n_wg_cross), dim3(256), lds16, s, dl, cross, sweep, round);
-            return hipGetLastError();
-        };
-        if (p.K_max <= 256) return run(&jacobi_intra16_kernel<8>, &jacobi_cross16_kernel<8>, attr16_by_size[0]);
-        if (p.K_max <= 384) return run(&jacobi_intra16_kernel<12>, &jacobi_cross16_kernel<12>, attr16_by_size[1]);
-        if (p.K_max <= 512) return run(&jacobi_intra16_kernel<16>, &jacobi_cross16_kernel<16>, attr16_by_size[2]);
-        return run(&jacobi_intra16_kernel<24>, &jacobi_cross16_kernel<24>, attr16_by_size[3]);
-    }
     hipLaunchKernelGGL(jacobi_intra_kernel<NX>, dim3(p.n_wg_intra), dim3(64 * (p.jb_max / 2)), lds_cross, s,
                        dl, intra, sweep);
     for (int round = 0; round < p.nb_max - 1; ++round)
@@ -988,9 +693,64 @@ hipError_t launch_jacobi_sweep(const Plan& p, const LayerDev* dl, const int2* cr
     return hipGetLastError();
 }
 
+
+// ---- layer groups on side streams -----------------------------------------------------------
+// One round of the block Jacobi iteration is a chain load -> Gram -> rotations -> update -> store,
+// and all work-groups of a launch walk through it side by side: memory, matrix cores and LDS take
+// turns instead of working together.  The layers are independent of each other, so they are split
+// into up to four groups, each with a stream of its own (the caller's stream carries the first
+// group); the groups drift apart and their phases overlap (measured on config 5: 58 -> 38 us per
+// round of all 48 layers).  The streams have the default priority, are created once per process
+// and are joined back into the caller's stream before merge_run returns.
+constexpr int kMaxGroups = 4;
+std::atomic<int> g_merge_groups{0};   // 0: as many as allowed; n: at most n groups (measurement switch)
+struct SideStreams {
+    hipStream_t stream[kMaxGroups - 1] = {};
+    hipEvent_t fork = nullptr, join[kMaxGroups - 1] = {};
+    hipEvent_t polled[kMaxGroups][2] = {};   // "the flags of sweep s have reached the host", per group, two in flight
+    int* flags_host = nullptr;               // pinned: the device-to-host copies of the flags are asynchronous
+    size_t flags_cap = 0;                    // ints
+    int device = -1;
+    bool ok = false;
+};
+std::mutex g_side_mutex;     // one batched merge at a time uses the side streams
+SideStreams g_side;
+
+bool pinned_flags_ready(size_t ints) {
+    if (g_side.flags_cap >= ints) return true;
+    if (g_side.flags_host) { (void)hipHostFree(g_side.flags_host); g_side.flags_host = nullptr; g_side.flags_cap = 0; }
+    if (hipHostMalloc((void**)&g_side.flags_host, sizeof(int) * ints, hipHostMallocDefault) != hipSuccess) {
+        g_side.flags_host = nullptr;
+        return false;
+    }
+    g_side.flags_cap = ints;
+    return true;
+}
+
+bool side_streams_ready() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    if (g_side.ok && g_side.device == dev) return true;
+    if (g_side.ok) return false;             // created for another device: run on the caller's stream only
+    SideStreams t;
+    for (int i = 0; i < kMaxGroups - 1; ++i) {
+        if (hipStreamCreateWithFlags(&t.stream[i], hipStreamNonBlocking) != hipSuccess) return false;
+        if (hipEventCreateWithFlags(&t.join[i], hipEventDisableTiming) != hipSuccess) return false;
+    }
+    if (hipEventCreateWithFlags(&t.fork, hipEventDisableTiming) != hipSuccess) return false;
+    for (int g = 0; g < kMaxGroups; ++g)
+        for (int i = 0; i < 2; ++i)
+            if (hipEventCreateWithFlags(&t.polled[g][i], hipEventDisableTiming) != hipSuccess) return false;
+    t.device = dev; t.ok = true;
+    g_side = t;
+    return true;
+}
+
 }  // namespace
 
 size_t merge_workspace_bytes(const abt_merge_desc* layers, int L) { return make_plan(layers, L).total; }
+
+int merge_set_groups(int n) { return g_merge_groups.exchange(n < 0 ? 0 : n); }
 
 hipError_t launch_identity_f32(float* dst, int K, hipStream_t s) {
     const int64_t n = (int64_t)K * K;
@@ -1131,23 +891,107 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
     const int2* intra = (const int2*)(ws + p.off_wg_intra);
     const int nx = (p.K_max + 63) / 64;
     std::vector<int> flags((size_t)(kMaxSweepsCap + 1) * L);
-    for (int sweep = 0; sweep < max_sweeps; ++sweep) {
-        if (nx <= 8) ABT_TRY(launch_jacobi_sweep<8>(p, dl, cross, intra, sweep, s));
-        else if (nx <= 16) ABT_TRY(launch_jacobi_sweep<16>(p, dl, cross, intra, sweep, s));
-        else ABT_TRY(launch_jacobi_sweep<32>(p, dl, cross, intra, sweep, s));
-        // A sweep is some two dozen launches; once every layer has converged the remaining ones
-        // would all exit at once.  Poll the per-sweep flags (a few KB) instead of issuing them.
-        if (sweep >= 2 && sweep + 1 < max_sweeps) {
-            ABT_TRY(hipMemcpyAsync(flags.data(), ws + p.off_rotated, sizeof(int) * flags.size(),
-                                   hipMemcpyDeviceToHost, s));
-            ABT_TRY(hipStreamSynchronize(s));
+    auto converged = [&](int l, int sweep) {
+        for (int q = 0; q <= sweep; ++q)
+            if (flags[(size_t)l * (kMaxSweepsCap + 1) + q] == 0) return true;
+        return false;
+    };
+    if (p.K_max <= 768) {
+        // block form on the matrix cores, layers in groups (contiguous layer ranges with about the
+        // same number of work-groups); wcross is layer-major, so a group is a slice of it
+        std::unique_lock<std::mutex> lock(g_side_mutex);
+        int ngroups = L < kMaxGroups ? L : kMaxGroups;
+        if (g_merge_groups >= 1 && g_merge_groups < ngroups) ngroups = g_merge_groups;
+        if (ngroups > 1 && !side_streams_ready()) ngroups = 1;
+        struct Group { int l0, l1, wg0, wg1, rounds; bool done; hipStream_t s; };
+        std::vector<Group> groups;
+        {
+            int l = 0, wg = 0;
+            for (int g = 0; g < ngroups; ++g) {
+                Group G{l, l, wg, wg, 0, false, g == 0 ? s : g_side.stream[g - 1]};
+                const int target = (int)((int64_t)p.n_wg_cross * (g + 1) / ngroups);
+                while (G.l1 < L && (G.wg1 < target || g == ngroups - 1)) {
+                    G.wg1 += p.pl[G.l1].nb / 2;
+                    if (p.pl[G.l1].nb - 1 > G.rounds) G.rounds = p.pl[G.l1].nb - 1;
+                    ++G.l1;
+                }
+                l = G.l1; wg = G.wg1;
+                if (G.l1 > G.l0) groups.push_back(G);
+            }
+        }
+        if (groups.size() > 1) {
+            ABT_TRY(hipEventRecord(g_side.fork, s));
+            for (size_t g = 1; g < groups.size(); ++g) ABT_TRY(hipStreamWaitEvent(groups[g].s, g_side.fork, 0));
+        }
+        // The host learns whether a group has converged from its per-sweep flags.  Waiting for them
+        // after every sweep would leave the GPU idle until the next sweep is enqueued, so the host
+        // stays one sweep ahead: the flags of sweep s are copied to pinned memory behind that sweep,
+        // sweep s + 1 is enqueued, and only then the host waits for the copy of sweep s and decides
+        // about sweep s + 2.  (The launches of a sweep that turns out not to be needed exit at once.)
+        const bool pipelined = side_streams_ready() && pinned_flags_ready(flags.size());
+        hipError_t fail = hipSuccess;
+        auto examine = [&](Group& G, int gi, int sweep) {       // flags of `sweep` have been copied
+            if (G.done) return;
+            if (pipelined) {
+                fail = hipEventSynchronize(g_side.polled[gi][sweep & 1]);
+                if (fail != hipSuccess) return;
+            }
+            const int* src = pipelined ? g_side.flags_host : flags.data();
             bool all_done = true;
-            for (int l = 0; l < L && all_done; ++l) {
+            for (int l = G.l0; l < G.l1 && all_done; ++l) {
                 bool done = false;
-                for (int q = 0; q <= sweep; ++q) done |= flags[(size_t)l * (kMaxSweepsCap + 1) + q] == 0;
+                for (int q = 0; q <= sweep; ++q) done |= src[(size_t)l * (kMaxSweepsCap + 1) + q] == 0;
                 all_done = done;
             }
-            if (all_done) break;
+            G.done = all_done;
+        };
+        for (int sweep = 0; sweep < max_sweeps && fail == hipSuccess; ++sweep) {
+            bool any = false;
+            for (int round = 0; round < p.nb_max - 1 && fail == hipSuccess; ++round)
+                for (Group& G : groups) {
+                    if (G.done || round >= G.rounds) continue;
+                    any = true;
+                    fail = launch_jacobi_block_round(dl, cross + G.wg0, G.wg1 - G.wg0, p.K_max, sweep, round, G.s);
+                    if (fail != hipSuccess) break;
+                }
+            if (!any || fail != hipSuccess) break;
+            if (sweep + 1 >= max_sweeps) break;
+            for (size_t gi = 0; gi < groups.size() && fail == hipSuccess; ++gi) {
+                Group& G = groups[gi];
+                if (G.done) continue;
+                const size_t off = (size_t)G.l0 * (kMaxSweepsCap + 1);
+                int* dst = pipelined ? g_side.flags_host : flags.data();
+                fail = hipMemcpyAsync(dst + off, (const int*)(ws + p.off_rotated) + off,
+                                      sizeof(int) * (kMaxSweepsCap + 1) * (G.l1 - G.l0), hipMemcpyDeviceToHost, G.s);
+                if (fail == hipSuccess && pipelined) fail = hipEventRecord(g_side.polled[gi][sweep & 1], G.s);
+                if (fail == hipSuccess && !pipelined) fail = hipStreamSynchronize(G.s);
+            }
+            // not pipelined: decide now; pipelined: decide on the sweep before this one
+            const int look = pipelined ? sweep - 1 : sweep;
+            if (look >= 1)
+                for (size_t gi = 0; gi < groups.size() && fail == hipSuccess; ++gi) examine(groups[gi], (int)gi, look);
+        }
+        // join, also after an error: nothing of this call may stay behind on a side stream
+        for (size_t g = 1; g < groups.size(); ++g) {
+            hipError_t e2 = hipEventRecord(g_side.join[g - 1], groups[g].s);
+            if (e2 == hipSuccess) e2 = hipStreamWaitEvent(s, g_side.join[g - 1], 0);
+            if (e2 != hipSuccess) { hipStreamSynchronize(groups[g].s); if (fail == hipSuccess) fail = e2; }
+        }
+        if (fail != hipSuccess) return fail;
+    } else {
+        for (int sweep = 0; sweep < max_sweeps; ++sweep) {
+            if (nx <= 16) ABT_TRY(launch_jacobi_sweep<16>(p, dl, cross, intra, sweep, s));
+            else ABT_TRY(launch_jacobi_sweep<32>(p, dl, cross, intra, sweep, s));
+            // A sweep is some hundred launches; once every layer has converged the remaining ones
+            // would all exit at once.  Poll the per-sweep flags (a few KB) instead of issuing them.
+            if (sweep >= 2 && sweep + 1 < max_sweeps) {
+                ABT_TRY(hipMemcpyAsync(flags.data(), ws + p.off_rotated, sizeof(int) * flags.size(),
+                                       hipMemcpyDeviceToHost, s));
+                ABT_TRY(hipStreamSynchronize(s));
+                bool all_done = true;
+                for (int l = 0; l < L && all_done; ++l) all_done = converged(l, sweep);
+                if (all_done) break;
+            }
         }
     }
     int n2 = 1;
