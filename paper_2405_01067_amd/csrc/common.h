@@ -19,6 +19,19 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kWave = 64;
 
+// Loads and stores through a pointer known to point into device memory.  A pointer read from a table
+// is generic to the compiler, which then emits FLAT instructions; those count in the LDS counter as
+// well as in the memory counter, so every wait for an LDS read would also wait for all global loads
+// in flight (prefetches included).  These helpers emit GLOBAL instructions.
+template <typename T>
+__device__ __forceinline__ T gload(const T* p) {
+    return *(const __attribute__((address_space(1))) T*)(p);
+}
+template <typename T>
+__device__ __forceinline__ void gstore(T* p, const T& v) {
+    *(__attribute__((address_space(1))) T*)(p) = v;
+}
+
 // Two fp32 -> packed bf16 (low half = lo), round-to-nearest-even: one v_cvt_pk_bf16_f32 on gfx950.
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;

@@ -24,21 +24,29 @@ struct GemmF32Dev {
     int tiles_q;
 };
 
-__device__ __forceinline__ float fetch(const float* base, int row, int col, int ld, int rows, int cols) {
-    return (row < rows && col < cols) ? base[(int64_t)row * ld + col] : 0.0f;
+// Unpredicated load (indices clamped into the matrix; `ok` tells whether the element exists): a
+// predicated one would have to be waited for before the next load is issued.
+__device__ __forceinline__ float fetch(const float* base, int row, int col, int ld, int rows, int cols, bool& ok) {
+    ok = row < rows && col < cols;
+    const int r = row < rows ? row : rows - 1, c = col < cols ? col : cols - 1;
+    return gload(base + (int64_t)r * ld + c);
 }
 
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmF32Dev* __restrict__ descs, int ndesc,
-                                                       GemmF32Dev single, int use_single) {
-    __shared__ float As[SLAB * PITCH];
-    __shared__ float Bs[SLAB * PITCH];
+                                                       GemmF32Dev single, int use_single, int ntiles) {
+    __shared__ float As2[2][SLAB * PITCH];
+    __shared__ float Bs2[2][SLAB * PITCH];
 
+    // Tiles are numbered problem by problem; block b works on tile (b % 8) * (grid / 8) + b / 8, so each
+    // XCD (block index modulo 8) gets a contiguous eighth of the list and the tiles of one problem
+    // share their operand panels through one L2.  The grid is the tile count rounded up to 8.
+    const int tile = (int)(blockIdx.x & 7) * (int)(gridDim.x >> 3) + (int)(blockIdx.x >> 3);
+    if (tile >= ntiles) return;
     GemmF32Dev g;
     if (use_single) {
         g = single;
     } else {
         int lo = 0, hi = ndesc - 1;
-        const int tile = blockIdx.x;
         while (lo < hi) {  // last descriptor whose tile_begin <= tile
             int mid = (lo + hi + 1) >> 1;
             if (descs[mid].tile_begin <= tile) lo = mid; else hi = mid - 1;
@@ -46,7 +54,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmF32Dev* __restr
         g = descs[lo];
     }
     const GemmF32& d = g.d;
-    const int local = blockIdx.x - g.tile_begin;
+    const int local = tile - g.tile_begin;
     const int i0 = (local / g.tiles_q) * TILE;
     const int j0 = (local % g.tiles_q) * TILE;
 
@@ -68,43 +76,56 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmF32Dev* __restr
 
     if (!dead) {
         float ra[8], rb[8];
+        bool oka[8], okb[8];
         auto load_slab = [&](int k0) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int lin = e * 256 + t;
                 if (d.transA) {  // A stored [K, P]
                     const int k = lin >> 7, i = lin & 127;
-                    ra[e] = fetch(d.A, k0 + k, i0 + i, d.lda, d.K, d.P);
+                    ra[e] = fetch(d.A, k0 + k, i0 + i, d.lda, d.K, d.P, oka[e]);
                 } else {         // A stored [P, K]
                     const int i = lin >> 4, k = lin & 15;
-                    ra[e] = fetch(d.A, i0 + i, k0 + k, d.lda, d.P, d.K);
+                    ra[e] = fetch(d.A, i0 + i, k0 + k, d.lda, d.P, d.K, oka[e]);
                 }
                 if (d.transB) {  // B stored [Q, K]
                     const int j = lin >> 4, k = lin & 15;
-                    rb[e] = fetch(d.B, j0 + j, k0 + k, d.ldb, d.Q, d.K);
+                    rb[e] = fetch(d.B, j0 + j, k0 + k, d.ldb, d.Q, d.K, okb[e]);
                 } else {         // B stored [K, Q]
                     const int k = lin >> 7, j = lin & 127;
-                    rb[e] = fetch(d.B, k0 + k, j0 + j, d.ldb, d.K, d.Q);
+                    rb[e] = fetch(d.B, k0 + k, j0 + j, d.ldb, d.K, d.Q, okb[e]);
                 }
             }
         };
-        auto store_slab = [&]() {
+        auto store_slab = [&](int buf) {
+            float* As = As2[buf];
+            float* Bs = Bs2[buf];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int lin = e * 256 + t;
-                if (d.transA) As[(lin >> 7) * PITCH + (lin & 127)] = ra[e];
-                else          As[(lin & 15) * PITCH + (lin >> 4)] = ra[e];
-                if (d.transB) Bs[(lin & 15) * PITCH + (lin >> 4)] = rb[e];
-                else          Bs[(lin >> 7) * PITCH + (lin & 127)] = rb[e];
+                const float va = oka[e] ? ra[e] : 0.0f, vb = okb[e] ? rb[e] : 0.0f;
+                if (d.transA) As[(lin >> 7) * PITCH + (lin & 127)] = va;
+                else          As[(lin & 15) * PITCH + (lin >> 4)] = va;
+                if (d.transB) Bs[(lin & 15) * PITCH + (lin >> 4)] = vb;
+                else          Bs[(lin >> 7) * PITCH + (lin & 127)] = vb;
             }
         };
 
+        // two LDS buffers, one barrier per slab: while slab s is multiplied out of buffer s % 2, slab
+        // s + 1 (in registers since the iteration before) goes to the other buffer and the loads of
+        // slab s + 2 are issued, so a load has two slabs of products to arrive
         const int nslab = (d.K + SLAB - 1) / SLAB;
         load_slab(0);
+        store_slab(0);
+        if (nslab > 1) load_slab(SLAB);
+        __syncthreads();
         for (int s = 0; s < nslab; ++s) {
-            store_slab();
-            __syncthreads();
-            if (s + 1 < nslab) load_slab((s + 1) * SLAB);
+            const float* As = As2[s & 1];
+            const float* Bs = Bs2[s & 1];
+            if (s + 1 < nslab) {
+                store_slab((s & 1) ^ 1);                  // everybody left that buffer before the last barrier
+                if (s + 2 < nslab) load_slab((s + 2) * SLAB);
+            }
             const int li = lane & 31, lk = lane >> 5;
 #pragma unroll
             for (int kk = 0; kk < SLAB; kk += 2) {
@@ -149,7 +170,7 @@ hipError_t launch_gemm_f32_one(const GemmF32& d, hipStream_t s) {
     g.tiles_q = (d.Q + TILE - 1) / TILE;
     const int tiles = ((d.P + TILE - 1) / TILE) * g.tiles_q;
     if (tiles <= 0) return hipSuccess;
-    hipLaunchKernelGGL(gemm_f32_kernel, dim3(tiles), dim3(256), 0, s, nullptr, 0, g, 1);
+    hipLaunchKernelGGL(gemm_f32_kernel, dim3((tiles + 7) / 8 * 8), dim3(256), 0, s, nullptr, 0, g, 1, tiles);
     return hipGetLastError();
 }
 
@@ -173,8 +194,8 @@ int gemm_f32_build_table(const GemmF32* descs_host, int n, void* host_image) {
 hipError_t launch_gemm_f32_table(const void* dev_image, int n, int tiles, hipStream_t s) {
     if (n <= 0 || tiles <= 0) return hipSuccess;
     GemmF32Dev none{};
-    hipLaunchKernelGGL(gemm_f32_kernel, dim3(tiles), dim3(256), 0, s,
-                       (const GemmF32Dev*)dev_image, n, none, 0);
+    hipLaunchKernelGGL(gemm_f32_kernel, dim3((tiles + 7) / 8 * 8), dim3(256), 0, s,
+                       (const GemmF32Dev*)dev_image, n, none, 0, tiles);
     return hipGetLastError();
 }
 

@@ -15,6 +15,7 @@
 //
 // mode 1 (mean of reconstructions) uses the same pipeline on the concatenations
 // Abar = [A_1 .. A_G] / G (m x Gk) and Bbar = [B_1; ..; B_G] (Gk x n).
+#include <algorithm>
 #include <atomic>
 #include <mutex>
 #include <vector>
@@ -36,122 +37,6 @@ __global__ void fill_i32_kernel(int* p, int64_t n, int v) {
 __global__ void identity_f32_kernel(float* p, int K) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < (int64_t)K * K) p[i] = (i / K == i % K) ? 1.0f : 0.0f;
-}
-
-// ------------------------------------------------------------------------------------------
-// Stage 1: average (mode 0) or concatenate (mode 1) the G copies.  Pure streaming.
-// ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void mean_kernel(const LayerDev* __restrict__ layers) {
-    const LayerDev& L = layers[blockIdx.y];
-    const int G = L.G;
-    const float inv = 1.0f / (float)G;
-    const int64_t nA = (int64_t)L.m * L.k, nB = (int64_t)L.k * L.n;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x * 4;
-    const int64_t start = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-    if (L.mode == 0) {
-        for (int64_t i = start; i < nA + nB; i += stride) {
-            const bool isA = i < nA;                      // nA, nB are multiples of 4 (k % 32 == 0)
-            const int64_t off = isA ? i : i - nA;
-            const float* const* ptrs = isA ? L.A_ptrs : L.B_ptrs;
-            f32x4 acc = *reinterpret_cast<const f32x4*>(ptrs[0] + off);
-            for (int g = 1; g < G; ++g) acc += *reinterpret_cast<const f32x4*>(ptrs[g] + off);
-            acc *= inv;
-            *reinterpret_cast<f32x4*>((isA ? L.Abar : L.Bbar) + off) = acc;
-        }
-    } else {
-        const int K = L.K;
-        for (int64_t i = start; i < (nA + nB) * G; i += stride) {
-            const int64_t per = nA + nB;
-            const int g = (int)(i / per);
-            const int64_t j = i - (int64_t)g * per;
-            if (j < nA) {         // Abar[row][g*k + c] = A_g[row][c] / G
-                const int64_t row = j / L.k, c = j % L.k;
-                f32x4 v = *reinterpret_cast<const f32x4*>(L.A_ptrs[g] + j);
-                v *= inv;
-                *reinterpret_cast<f32x4*>(L.Abar + row * K + (int64_t)g * L.k + c) = v;
-            } else {              // Bbar[g*k + c][:] = B_g[c][:]
-                const int64_t off = j - nA;
-                const f32x4 v = *reinterpret_cast<const f32x4*>(L.B_ptrs[g] + off);
-                *reinterpret_cast<f32x4*>(L.Bbar + (int64_t)g * nB + off) = v;
-            }
-        }
-    }
-}
-
-// ------------------------------------------------------------------------------------------
-// Stage 2: Gram matrices in fp64 from fp32 data.  One work-group owns one 64 x 64 tile of the
-// lower triangle and walks the whole contraction length, so the sums have a fixed order.
-//   which = 0: G_A = Abar^T Abar (contraction over the m rows; stored into LA)
-//   which = 1: G_B = Bbar Bbar^T (contraction over the n columns; stored into GB and LB)
-// ------------------------------------------------------------------------------------------
-struct GramTile { int layer, which, ti, tj; };
-
-__global__ __launch_bounds__(256) void gram_kernel(const LayerDev* __restrict__ layers,
-                                                   const GramTile* __restrict__ tiles) {
-    __shared__ float As[16][68];
-    __shared__ float Bs[16][68];
-    const GramTile gt = tiles[blockIdx.x];
-    const LayerDev& L = layers[gt.layer];
-    const int K = L.K;
-    const int i0 = gt.ti * 64, j0 = gt.tj * 64;
-    const int len = gt.which == 0 ? L.m : L.n;
-    const float* src = gt.which == 0 ? L.Abar : L.Bbar;
-    const int t = threadIdx.x;
-    const int tx = t & 15, ty = t >> 4;
-
-    double acc[4][4];
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
-
-    for (int c0 = 0; c0 < len; c0 += 16) {
-        // slab element (kk, x): which == 0 -> Abar[c0+kk][i0+x]; which == 1 -> Bbar[i0+x][c0+kk]
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int lin = e * 256 + t;
-            int kk, x;
-            if (gt.which == 0) { kk = lin >> 6; x = lin & 63; } else { x = lin >> 4; kk = lin & 15; }
-            const int c = c0 + kk;
-            float va = 0.0f, vb = 0.0f;
-            if (c < len) {
-                if (gt.which == 0) {
-                    if (i0 + x < K) va = src[(int64_t)c * K + i0 + x];
-                    if (j0 + x < K) vb = src[(int64_t)c * K + j0 + x];
-                } else {
-                    if (i0 + x < K) va = src[(int64_t)(i0 + x) * len + c];
-                    if (j0 + x < K) vb = src[(int64_t)(j0 + x) * len + c];
-                }
-            }
-            As[kk][x] = va;
-            Bs[kk][x] = vb;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int kk = 0; kk < 16; ++kk) {
-            double a[4], b[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) { a[u] = (double)As[kk][ty * 4 + u]; b[u] = (double)Bs[kk][tx * 4 + u]; }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) acc[u][v] = fma(a[u], b[v], acc[u][v]);
-        }
-        __syncthreads();
-    }
-    double* out0 = gt.which == 0 ? L.LA : L.GB;
-    double* out1 = gt.which == 0 ? nullptr : L.LB;
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int i = i0 + ty * 4 + u, j = j0 + tx * 4 + v;
-            if (i < K && j < K) {
-                out0[(int64_t)i * K + j] = acc[u][v];
-                out0[(int64_t)j * K + i] = acc[u][v];
-                if (out1) { out1[(int64_t)i * K + j] = acc[u][v]; out1[(int64_t)j * K + i] = acc[u][v]; }
-            }
-        }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -272,9 +157,185 @@ __global__ __launch_bounds__(256) void cholesky_kernel(const LayerDev* __restric
 }
 
 // ------------------------------------------------------------------------------------------
+// Stage 3 for K <= kCholMaxK: the same factorisation, right-looking, with the panel in LDS and the
+// trailing update on the fp64 matrix cores.  One work-group per matrix.  Per block column j0:
+//   load the 32 x 32 diagonal block and the (K - j0 - 32) x 32 panel below it into LDS,
+//   factor the diagonal block (one wave, 32 dependent steps), X = panel L_jj^(-T) (a thread per row),
+//   write L's block column, and subtract X X^T from the lower triangle of the trailing matrix:
+//   16 x 16 tiles, C tile from / to memory (L2), operands of v_mfma_f64_16x16x4 from the LDS panel.
+// ------------------------------------------------------------------------------------------
+constexpr int kCholMaxK = 544;     // (K - 32) x 34 doubles of panel: 136 KB
+constexpr int kCholPitch = 34;     // doubles per panel row: 16 rows x 2 column groups of an operand read cover all banks
+
+constexpr int kCholThreads = 256;  // (512 threads measured the same: the serial diagonal-block and row-solve phases dominate)
+
+__global__ __launch_bounds__(kCholThreads) void cholesky_mfma_kernel(const LayerDev* __restrict__ layers) {
+    constexpr int NT = kCholThreads;
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const LayerDev& L = layers[blockIdx.x >> 1];
+    double* Gm = (blockIdx.x & 1) ? L.LB : L.LA;
+    const int K = L.K;
+    if (K > kCholMaxK) return;
+    double* Xp = reinterpret_cast<double*>(lds_raw);                 // [K - 32][kCholPitch]
+    double (*Ljj)[33] = reinterpret_cast<double (*)[33]>(Xp + (size_t)(K > 32 ? K - 32 : 0) * kCholPitch);
+    double* invp = &Ljj[0][0] + 32 * 33;                             // [32] reciprocal pivots (0: dropped column)
+    double* red = invp + 32;                                         // [NT]
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, n = lane & 15, kq = lane >> 4;
+
+    double mx = 0.0, tr = 0.0;
+    for (int i = t; i < K; i += NT) { const double d = gload(Gm + (int64_t)i * K + i); mx = fmax(mx, d); tr += d; }
+    red[t] = mx;
+    __syncthreads();
+    for (int s = NT / 2; s > 0; s >>= 1) {
+        if (t < s) red[t] = fmax(red[t], red[t + s]);
+        __syncthreads();
+    }
+    const double floor_piv = red[0] * 1e-14;
+    __syncthreads();
+    red[t] = tr;
+    __syncthreads();
+    for (int s = NT / 2; s > 0; s >>= 1) {
+        if (t < s) red[t] += red[t + s];
+        __syncthreads();
+    }
+    if (t == 0) L.trace[blockIdx.x & 1] = red[0];
+    __syncthreads();
+
+    for (int j0 = 0; j0 < K; j0 += 32) {
+        const int nr = K - j0 - 32;                  // rows below the diagonal block
+        // ---- (1) diagonal block and panel -> LDS (rows of 256 bytes, coalesced)
+        for (int e = t; e < 32 * 32; e += NT) Ljj[e >> 5][e & 31] = gload(Gm + (int64_t)(j0 + (e >> 5)) * K + j0 + (e & 31));
+        // (eight 16-byte loads in flight per thread: a load that is stored to LDS right away costs a full
+        // memory latency per loop trip)
+        for (int e0 = 0; e0 < nr * 16; e0 += 8 * NT) {
+            f64x2 buf[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = e0 + u * NT + t;
+                const int ec = e < nr * 16 ? e : nr * 16 - 1;
+                buf[u] = gload(reinterpret_cast<const f64x2*>(Gm + (int64_t)(j0 + 32 + (ec >> 4)) * K + j0 + 2 * (ec & 15)));
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = e0 + u * NT + t;
+                if (e < nr * 16) *reinterpret_cast<f64x2*>(Xp + (e >> 4) * kCholPitch + 2 * (e & 15)) = buf[u];
+            }
+        }
+        __syncthreads();
+        // ---- (2) factor the diagonal block: one wave, lane r holds row r in registers; step c takes the
+        // pivot and the finished column c from the other lanes with lane reads (no LDS, no waits)
+        if (wave == 0) {
+            const int r = lane & 31;
+            double row[32];
+#pragma unroll
+            for (int c = 0; c < 32; ++c) row[c] = Ljj[r][c];
+            auto lane_value = [](double v, int src) {
+                const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
+                const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+                return __hiloint2double(hi, lo);
+            };
+#pragma unroll
+            for (int c = 0; c < 32; ++c) {
+                const double d = lane_value(row[c], c);
+                const bool ok = d > floor_piv;
+                // 1 / sqrt(d): hardware estimate and two Newton steps (a square root and a division in
+                // fp64 would be several times the rest of the step); the pivot itself is d / sqrt(d)
+                const double dd = ok ? d : 1.0;
+                double y = __builtin_amdgcn_rsq(dd);
+                y = y * fma(-0.5 * dd, y * y, 1.5);
+                y = y * fma(-0.5 * dd, y * y, 1.5);
+                const double ip = ok ? y : 0.0;
+                const double piv = ok ? dd * y : 0.0;
+                const double v = (r == c) ? piv : (r > c ? row[c] * ip : 0.0);
+                row[c] = v;
+                if (lane == c) invp[c] = ip;
+#pragma unroll
+                for (int cc = c + 1; cc < 32; ++cc) row[cc] = fma(-v, lane_value(v, cc), row[cc]);
+            }
+            if (lane < 32) {
+#pragma unroll
+                for (int c = 0; c < 32; ++c) Ljj[r][c] = row[c];
+            }
+        }
+        __syncthreads();
+        // ---- (3) rows below: x = row L_jj^(-T), column by column so that the updates of a step are independent
+        for (int r = t; r < nr; r += NT) {
+            double x[32];
+#pragma unroll
+            for (int c = 0; c < 32; ++c) x[c] = Xp[r * kCholPitch + c];
+#pragma unroll
+            for (int c = 0; c < 32; ++c) {
+                x[c] *= invp[c];
+#pragma unroll
+                for (int c2 = c + 1; c2 < 32; ++c2) x[c2] = fma(-x[c], Ljj[c2][c], x[c2]);
+            }
+#pragma unroll
+            for (int c = 0; c < 32; ++c) Xp[r * kCholPitch + c] = x[c];
+        }
+        __syncthreads();
+        // ---- (4) L's block column to memory: diagonal block (upper part zero), panel, zeros to the right
+        for (int e = t; e < 32 * 32; e += NT) {
+            const int r = e >> 5, c = e & 31;
+            gstore(Gm + (int64_t)(j0 + r) * K + j0 + c, (c <= r) ? Ljj[r][c] : 0.0);
+        }
+        for (int e = t; e < nr * 16; e += NT)
+            gstore(reinterpret_cast<f64x2*>(Gm + (int64_t)(j0 + 32 + (e >> 4)) * K + j0 + 2 * (e & 15)),
+                   *reinterpret_cast<const f64x2*>(Xp + (e >> 4) * kCholPitch + 2 * (e & 15)));
+        for (int e = t; e < 32 * nr; e += NT) {
+            const int r = e / nr, c = e - r * nr;
+            gstore(Gm + (int64_t)(j0 + r) * K + j0 + 32 + c, 0.0);
+        }
+        // ---- (5) trailing matrix, lower triangle: C(ti, tj) -= X(ti) X(tj)^T.  Lane l holds X[16 ti + l % 16][l / 16 + 4 s]
+        // (s = 0..7) as A operand (negated) and the same of tile tj as B operand; the accumulator register v
+        // is C[l / 16 + 4 v][l % 16] of the tile.
+        const int T = nr >> 4;
+        for (int ti = T - 1 - wave; ti >= 0; ti -= NT / 64) {
+            double a[8];
+#pragma unroll
+            for (int s = 0; s < 8; ++s) a[s] = -Xp[(16 * ti + n) * kCholPitch + 4 * s + kq];
+            double* crow = Gm + (int64_t)(j0 + 32 + 16 * ti + kq) * K + j0 + 32 + n;
+            // C tiles travel in groups of four, the next group's loads issued before the products of this
+            // one: a load has 32 matrix instructions (about 2000 cycles) to come back from L2
+            f64x4 cur[4], nxt[4];
+            auto fetch4 = [&](f64x4 (&dst)[4], int base) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (base + u <= ti) {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) dst[u][v] = gload(crow + (int64_t)(4 * v) * K + 16 * (base + u));
+                    }
+            };
+            fetch4(cur, 0);
+            for (int g0 = 0; g0 <= ti; g0 += 4) {
+                if (g0 + 4 <= ti) fetch4(nxt, g0 + 4);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int tj = g0 + u;
+                    if (tj <= ti) {
+                        f64x4 acc = cur[u];
+#pragma unroll
+                        for (int s = 0; s < 8; ++s) {
+                            const double b = Xp[(16 * tj + n) * kCholPitch + 4 * s + kq];
+                            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[s], b, acc, 0, 0, 0);
+                        }
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) gstore(crow + (int64_t)(4 * v) * K + 16 * tj, acc[v]);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
+            }
+        }
+        __threadfence_block();
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // fp64 GEMM for the K x K stages (grouped):  C = op(A) . op(B) with optional row gather on
 // op(A), per-row / per-column scaling, fp64 and/or fp32 output.
-// Tile 64 x 64, 256 threads, 4 x 4 outputs per thread, vector fp64 FMA.
+// Tile 64 x 64, 256 threads = 4 waves of 32 x 32 (2 x 2 blocks of v_mfma_f64_16x16x4), slabs of 16
+// staged through LDS, the next slab's global loads in flight during the products.
 // ------------------------------------------------------------------------------------------
 struct GemmF64 {
     const double* A; const double* B;
@@ -289,11 +350,17 @@ struct GemmF64 {
     int tile_begin, tiles_q;
 };
 
-__global__ __launch_bounds__(256) void gemm_f64_kernel(const GemmF64* __restrict__ descs, int ndesc) {
-    __shared__ double As[16][68];
-    __shared__ double Bs[16][68];
+__global__ __launch_bounds__(256) void gemm_f64_kernel(const GemmF64* __restrict__ descs, int ndesc, int ntiles) {
+    // k-major slabs of 16; pitch 80 doubles: the four 16-lane rows of an operand read (k, k + 1, ...)
+    // start 160 words apart, i.e. in alternating halves of the 64 banks
+    __shared__ double As[2][16][80];
+    __shared__ double Bs[2][16][80];
+    // Tiles are numbered problem by problem; block b works on tile (b % 8) * (grid / 8) + b / 8, so each
+    // XCD (block index modulo 8) gets a contiguous eighth of the list: the tiles of one problem share
+    // their operand panels through one L2 instead of pulling them into all eight.
+    const int tile = (int)(blockIdx.x & 7) * (int)(gridDim.x >> 3) + (int)(blockIdx.x >> 3);
+    if (tile >= ntiles) return;
     int lo = 0, hi = ndesc - 1;
-    const int tile = blockIdx.x;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
         if (descs[mid].tile_begin <= tile) lo = mid; else hi = mid - 1;
@@ -301,72 +368,109 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(const GemmF64* __restrict
     const GemmF64 d = descs[lo];
     const int local = tile - d.tile_begin;
     const int i0 = (local / d.tiles_q) * 64, j0 = (local % d.tiles_q) * 64;
-    const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, n = lane & 15, kq = lane >> 4;
+    const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;      // this wave's 32 x 32 part of the tile
     const int lim = d.limit ? *d.limit : 0;
     const bool dead = d.limit && (d.limit_rows ? (i0 >= lim) : (j0 >= lim));
 
-    double acc[4][4];
+    // v_mfma_f64_16x16x4: A operand lane l = A[l % 16][l / 16], B operand = B[l / 16][l % 16],
+    // accumulator register v of lane l = C[l / 16 + 4 v][l % 16]
+    f64x4 acc[2][2];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
+        for (int b = 0; b < 2; ++b) acc[a][b] = f64x4{0.0, 0.0, 0.0, 0.0};
 
     if (!dead) {
-        for (int k0 = 0; k0 < d.K; k0 += 16) {
+        // loads carry no predicate (indices are clamped into the matrices) so that none of them has
+        // to be waited for before the next is issued; what was out of range is dropped when the slab
+        // goes to LDS
+        double ra[4], rb[4];
+        bool oka[4], okb[4];
+        // the rows of op(A) this thread fetches do not change from slab to slab: resolve the gather
+        // once (inside the slab loop every index load would have to be waited for, and with it all
+        // loads issued before)
+        int rowA[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int lin = e * 256 + t;
+            const int x = d.transA ? (lin & 63) : (lin >> 4);
+            const int xi = i0 + x < d.P ? i0 + x : d.P - 1;
+            rowA[e] = (!d.transA && d.row_gather) ? gload(d.row_gather + xi) : xi;
+        }
+        auto load_slab = [&](int k0) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int lin = e * 256 + t;
                 {
                     int kk, x;
                     if (d.transA) { kk = lin >> 6; x = lin & 63; } else { x = lin >> 4; kk = lin & 15; }
-                    double v = 0.0;
-                    if (i0 + x < d.P && k0 + kk < d.K) {
-                        if (d.transA) v = d.A[(int64_t)(k0 + kk) * d.lda + i0 + x];
-                        else {
-                            const int row = d.row_gather ? d.row_gather[i0 + x] : i0 + x;
-                            v = d.A[(int64_t)row * d.lda + k0 + kk];
-                        }
-                    }
-                    As[kk][x] = v;
+                    oka[e] = i0 + x < d.P && k0 + kk < d.K;
+                    const int ki = k0 + kk < d.K ? k0 + kk : d.K - 1;
+                    ra[e] = d.transA ? gload(d.A + (int64_t)ki * d.lda + rowA[e]) : gload(d.A + (int64_t)rowA[e] * d.lda + ki);
                 }
                 {
                     int kk, x;
                     if (d.transB) { x = lin >> 4; kk = lin & 15; } else { kk = lin >> 6; x = lin & 63; }
-                    double v = 0.0;
-                    if (j0 + x < d.Q && k0 + kk < d.K)
-                        v = d.transB ? d.B[(int64_t)(j0 + x) * d.ldb + k0 + kk] : d.B[(int64_t)(k0 + kk) * d.ldb + j0 + x];
-                    Bs[kk][x] = v;
+                    okb[e] = j0 + x < d.Q && k0 + kk < d.K;
+                    const int xj = j0 + x < d.Q ? j0 + x : d.Q - 1, ki = k0 + kk < d.K ? k0 + kk : d.K - 1;
+                    rb[e] = d.transB ? gload(d.B + (int64_t)xj * d.ldb + ki) : gload(d.B + (int64_t)ki * d.ldb + xj);
                 }
             }
-            __syncthreads();
+        };
+        auto store_slab = [&](int b) {
 #pragma unroll
-            for (int kk = 0; kk < 16; ++kk) {
-                double a[4], b[4];
+            for (int e = 0; e < 4; ++e) {
+                const int lin = e * 256 + t;
+                const double va = oka[e] ? ra[e] : 0.0, vb = okb[e] ? rb[e] : 0.0;
+                if (d.transA) As[b][lin >> 6][lin & 63] = va; else As[b][lin & 15][lin >> 4] = va;
+                if (d.transB) Bs[b][lin & 15][lin >> 4] = vb; else Bs[b][lin >> 6][lin & 63] = vb;
+            }
+        };
+        // two LDS buffers, one barrier per slab: while slab s is multiplied out of buffer s % 2, slab
+        // s + 1 (in registers since the iteration before) goes to the other buffer and the loads of
+        // slab s + 2 are issued, so a load has two slabs of products to arrive
+        const int nslab = (d.K + 15) / 16;
+        load_slab(0);
+        store_slab(0);
+        if (nslab > 1) load_slab(16);
+        __syncthreads();
+        for (int sl = 0; sl < nslab; ++sl) {
+            const int b = sl & 1;
+            if (sl + 1 < nslab) {
+                store_slab(b ^ 1);                       // everybody left buffer b ^ 1 before the last barrier
+                if (sl + 2 < nslab) load_slab((sl + 2) * 16);
+            }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) { a[u] = As[kk][ty * 4 + u]; b[u] = Bs[kk][tx * 4 + u]; }
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) acc[u][v] = fma(a[u], b[v], acc[u][v]);
+            for (int q = 0; q < 4; ++q) {
+                const double a0 = As[b][4 * q + kq][wi + n], a1 = As[b][4 * q + kq][wi + 16 + n];
+                const double b0 = Bs[b][4 * q + kq][wj + n], b1 = Bs[b][4 * q + kq][wj + 16 + n];
+                acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
+                acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
+                acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
+                acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
             }
             __syncthreads();
         }
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int i = i0 + ty * 4 + u, j = j0 + tx * 4 + v;
-            if (i < d.P && j < d.Q) {
-                if (d.C) d.C[(int64_t)i * d.ldc + j] = acc[u][v];
-                if (d.C32) {
-                    double val = acc[u][v];
-                    if (d.row_scale32) val *= d.row_scale32[i];
-                    if (d.col_scale32) val *= d.col_scale32[j];
-                    d.C32[(int64_t)i * d.ldc32 + j] = (float)val;
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = i0 + wi + 16 * a + kq + 4 * v, j = j0 + wj + 16 * b + n;
+                if (i < d.P && j < d.Q) {
+                    const double val0 = acc[a][b][v];
+                    if (d.C) d.C[(int64_t)i * d.ldc + j] = val0;
+                    if (d.C32) {
+                        double val = val0;
+                        if (d.row_scale32) val *= d.row_scale32[i];
+                        if (d.col_scale32) val *= d.col_scale32[j];
+                        d.C32[(int64_t)i * d.ldc32 + j] = (float)val;
+                    }
                 }
             }
-        }
 }
 
 // ||C||_F^2 per layer, the scale of the "numerically zero column" test: eight work-groups per
@@ -523,8 +627,22 @@ __global__ __launch_bounds__(512) void jacobi_intra_kernel(const LayerDev* __res
 
 // ------------------------------------------------------------------------------------------
 // Stage 6: singular values = column norms, sorted descending; rank rule; scale vectors.
-// One work-group per layer.
+// The squared norms come from a launch of their own that spreads the K x K reads over the chip
+// (one wave per column, four columns per work-group); the sort and the rank rule take one
+// work-group per layer.
 // ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void colnorm_kernel(const LayerDev* __restrict__ layers) {
+    const LayerDev& L = layers[blockIdx.y];
+    const int K = L.K, lane = threadIdx.x & 63;
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (c >= K) return;
+    const double* col = L.Ct + (int64_t)c * K;
+    double ss = 0.0;
+    for (int r = lane; r < K; r += 64) { const double v = gload(col + r); ss = fma(v, v, ss); }
+    ss = wave_sum(ss);
+    if (lane == 0) L.nrm[c] = ss;
+}
+
 __global__ __launch_bounds__(256) void finalize_kernel(const LayerDev* __restrict__ layers, int max_sweeps) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const LayerDev& L = layers[blockIdx.x];
@@ -533,17 +651,9 @@ __global__ __launch_bounds__(256) void finalize_kernel(const LayerDev* __restric
     while (n2 < K) n2 <<= 1;
     double* key = reinterpret_cast<double*>(lds_raw);      // [n2]
     int* idx = reinterpret_cast<int*>(key + n2);           // [n2]
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int t = threadIdx.x;
 
-    for (int c = wave; c < n2; c += 4) {
-        double ss = 0.0;
-        if (c < K) {
-            const double* col = L.Ct + (int64_t)c * K;
-            for (int r = lane; r < K; r += 64) ss = fma(col[r], col[r], ss);
-            ss = wave_sum(ss);
-        }
-        if (lane == 0) { key[c] = c < K ? sqrt(ss) : -1.0; idx[c] = c; }
-    }
+    for (int c = t; c < n2; c += 256) { key[c] = c < K ? sqrt(L.nrm[c]) : -1.0; idx[c] = c; }
     __syncthreads();
     // bitonic sort, descending by key (ties: lower original index first)
     for (int size = 2; size <= n2; size <<= 1) {
@@ -614,6 +724,51 @@ struct Plan {
 
 int jacobi_block(int K) { return K <= 768 ? 16 : (K <= 1024 ? 8 : 4); }
 
+// Job list of the averaging + Gram stage.  The (layer, side) pairs are taken longest contraction
+// first and dealt round-robin to the eight XCDs (block index modulo 8 picks the XCD); the tiles of
+// one pair take consecutive slots of its XCD, so they run at about the same time on one L2.
+// Returns the number of leading jobs that take the kernel with 16-byte loads; the rest (B sides with
+// n % 4 != 0) follow.
+int build_gram_jobs(const abt_merge_desc* layers, int L, std::vector<GramJob>& out) {
+    struct Pair { int layer, which; int64_t len; int T; };
+    std::vector<Pair> pairs;
+    pairs.reserve(2 * (size_t)L);
+    for (int l = 0; l < L; ++l) {
+        const abt_merge_desc& d = layers[l];
+        const int K = (int)(d.mode == 0 ? d.k : d.k * d.G);
+        const int T = (K + 127) / 128;
+        pairs.push_back(Pair{l, 0, d.m, T});
+        if (d.n % 4 == 0) pairs.push_back(Pair{l, 1, d.n, T});
+    }
+    std::stable_sort(pairs.begin(), pairs.end(), [](const Pair& a, const Pair& b) {
+        return a.len * a.T * (a.T + 1) > b.len * b.T * (b.T + 1);
+    });
+    std::vector<GramJob> per_xcd[8];
+    for (size_t q = 0; q < pairs.size(); ++q) {
+        // shortest list first keeps the XCDs level when the pairs differ in size
+        int x = 0;
+        for (int c = 1; c < 8; ++c) if (per_xcd[c].size() < per_xcd[x].size()) x = c;
+        const Pair& pr = pairs[q];
+        for (int ti = 0; ti < pr.T; ++ti)
+            for (int tj = 0; tj <= ti; ++tj) per_xcd[x].push_back(GramJob{pr.layer, pr.which, ti, tj});
+    }
+    size_t slots = 0;
+    for (int c = 0; c < 8; ++c) if (per_xcd[c].size() > slots) slots = per_xcd[c].size();
+    out.assign(slots * 8, GramJob{-1, 0, 0, 0});
+    for (int c = 0; c < 8; ++c)
+        for (size_t i = 0; i < per_xcd[c].size(); ++i) out[i * 8 + c] = per_xcd[c][i];
+    const int aligned = (int)out.size();
+    for (int l = 0; l < L; ++l) {
+        const abt_merge_desc& d = layers[l];
+        if (d.n % 4 == 0) continue;
+        const int K = (int)(d.mode == 0 ? d.k : d.k * d.G);
+        const int T = (K + 127) / 128;
+        for (int ti = 0; ti < T; ++ti)
+            for (int tj = 0; tj <= ti; ++tj) out.push_back(GramJob{l, 1, ti, tj});
+    }
+    return aligned;
+}
+
 Plan make_plan(const abt_merge_desc* layers, int L) {
     Plan p;
     p.L = L;
@@ -628,8 +783,6 @@ Plan make_plan(const abt_merge_desc* layers, int L) {
         Plan::PerLayer& q = p.pl[l];
         q.K = K; q.jb = jacobi_block(K); q.nb = K / q.jb;
         p.n_ptrs += 2 * d.G;
-        const int T = (K + 63) / 64;
-        p.n_gram_tiles += 2 * (T * (T + 1) / 2);
         p.n_wg_cross += q.nb / 2;
         p.n_wg_intra += q.nb;
         if (q.nb > p.nb_max) p.nb_max = q.nb;
@@ -639,8 +792,13 @@ Plan make_plan(const abt_merge_desc* layers, int L) {
         p.n_gemm64 += 1;                        // per stage: one problem per layer
         p.n_gemm32 += 2 + (d.W_out ? 1 : 0);
     }
+    {
+        std::vector<GramJob> jobs;
+        build_gram_jobs(layers, L, jobs);
+        p.n_gram_tiles = (int)jobs.size();
+    }
     p.off_ptrs = take(sizeof(void*) * p.n_ptrs);
-    p.off_gram_tiles = take(sizeof(GramTile) * p.n_gram_tiles);
+    p.off_gram_tiles = take(sizeof(GramJob) * p.n_gram_tiles);
     p.off_wg_cross = take(sizeof(int2) * p.n_wg_cross);
     p.off_wg_intra = take(sizeof(int2) * p.n_wg_intra);
     p.off_gemm64 = take(sizeof(GemmF64) * p.n_gemm64 * 3);   // three fp64 stages, staged up front
@@ -774,7 +932,8 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
     // ---- host images of the header tables
     std::vector<LayerDev> hl(L);
     std::vector<const float*> hptrs(p.n_ptrs);
-    std::vector<GramTile> gtiles; gtiles.reserve(p.n_gram_tiles);
+    std::vector<GramJob> gtiles;
+    const int gram_aligned = build_gram_jobs(layers, L, gtiles);
     std::vector<int2> wcross; wcross.reserve(p.n_wg_cross);
     std::vector<int2> wintra; wintra.reserve(p.n_wg_intra);
     std::vector<GemmF64> g64(p.n_gemm64 * 3);
@@ -807,10 +966,7 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
         v.info = (int*)(ws + p.off_info) + (size_t)l * kInfoInts;
         v.S_out = d.S_out; v.k_out = d.k_out;
 
-        const int K = q.K, T = (K + 63) / 64;
-        for (int which = 0; which < 2; ++which)
-            for (int ti = 0; ti < T; ++ti)
-                for (int tj = 0; tj <= ti; ++tj) gtiles.push_back(GramTile{l, which, ti, tj});
+        const int K = q.K;
         for (int sidx = 0; sidx < q.nb / 2; ++sidx) wcross.push_back(make_int2(l, sidx));
         for (int b = 0; b < q.nb; ++b) wintra.push_back(make_int2(l, b));
 
@@ -860,7 +1016,7 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
 #define ABT_TRY(x) do { e = (x); if (e != hipSuccess) return e; } while (0)
     ABT_TRY(hipMemcpyAsync(ws + p.off_layers, hl.data(), sizeof(LayerDev) * L, hipMemcpyHostToDevice, s));
     ABT_TRY(hipMemcpyAsync(ws + p.off_ptrs, hptrs.data(), sizeof(void*) * p.n_ptrs, hipMemcpyHostToDevice, s));
-    ABT_TRY(hipMemcpyAsync(ws + p.off_gram_tiles, gtiles.data(), sizeof(GramTile) * gtiles.size(), hipMemcpyHostToDevice, s));
+    ABT_TRY(hipMemcpyAsync(ws + p.off_gram_tiles, gtiles.data(), sizeof(GramJob) * gtiles.size(), hipMemcpyHostToDevice, s));
     ABT_TRY(hipMemcpyAsync(ws + p.off_wg_cross, wcross.data(), sizeof(int2) * wcross.size(), hipMemcpyHostToDevice, s));
     ABT_TRY(hipMemcpyAsync(ws + p.off_wg_intra, wintra.data(), sizeof(int2) * wintra.size(), hipMemcpyHostToDevice, s));
     ABT_TRY(hipMemcpyAsync(ws + p.off_gemm64, g64.data(), sizeof(GemmF64) * g64.size(), hipMemcpyHostToDevice, s));
@@ -878,12 +1034,21 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
         // sweeps never run count as "nothing rotated" only if an earlier sweep converged; mark the
         // slots past the cap as dirty so finalize reports non-convergence correctly
     }
-    hipLaunchKernelGGL(mean_kernel, dim3(64, L), dim3(256), 0, s, dl);
-    hipLaunchKernelGGL(gram_kernel, dim3(p.n_gram_tiles), dim3(256), 0, s, dl,
-                       (const GramTile*)(ws + p.off_gram_tiles));
-    hipLaunchKernelGGL(cholesky_kernel, dim3(2 * L), dim3(256), 0, s, dl);
+    ABT_TRY(launch_mean_gram(dl, (const GramJob*)(ws + p.off_gram_tiles), gram_aligned, p.n_gram_tiles - gram_aligned, s));
+    if (p.K_max <= kCholMaxK) {
+        const size_t lds = sizeof(double) * ((size_t)(p.K_max > 32 ? p.K_max - 32 : 0) * kCholPitch + 32 * 33 + 32 + kCholThreads);
+        static std::atomic<size_t> chol_attr{0};
+        if (lds > chol_attr.load()) {
+            ABT_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&cholesky_mfma_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            chol_attr.store(lds);
+        }
+        hipLaunchKernelGGL(cholesky_mfma_kernel, dim3(2 * L), dim3(kCholThreads), lds, s, dl);
+    } else {
+        hipLaunchKernelGGL(cholesky_kernel, dim3(2 * L), dim3(256), 0, s, dl);
+    }
     const GemmF64* d64 = (const GemmF64*)(ws + p.off_gemm64);
-    hipLaunchKernelGGL(gemm_f64_kernel, dim3(tb0), dim3(256), 0, s, d64, p.n_gemm64);
+    hipLaunchKernelGGL(gemm_f64_kernel, dim3(align_up(tb0, 8)), dim3(256), 0, s, d64, p.n_gemm64, tb0);
     hipLaunchKernelGGL(frob2_kernel, dim3(8, L), dim3(256), 0, s, dl);
     ABT_TRY(hipGetLastError());
 
@@ -996,9 +1161,10 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
     }
     int n2 = 1;
     while (n2 < p.K_max) n2 <<= 1;
+    hipLaunchKernelGGL(colnorm_kernel, dim3((p.K_max + 3) / 4, L), dim3(256), 0, s, dl);
     hipLaunchKernelGGL(finalize_kernel, dim3(L), dim3(256), (sizeof(double) + sizeof(int)) * n2, s, dl, max_sweeps);
-    if (tb1 > 0) hipLaunchKernelGGL(gemm_f64_kernel, dim3(tb1), dim3(256), 0, s, d64 + p.n_gemm64, p.n_gemm64);
-    if (tb2 > 0) hipLaunchKernelGGL(gemm_f64_kernel, dim3(tb2), dim3(256), 0, s, d64 + 2 * p.n_gemm64, p.n_gemm64);
+    if (tb1 > 0) hipLaunchKernelGGL(gemm_f64_kernel, dim3(align_up(tb1, 8)), dim3(256), 0, s, d64 + p.n_gemm64, p.n_gemm64, tb1);
+    if (tb2 > 0) hipLaunchKernelGGL(gemm_f64_kernel, dim3(align_up(tb2, 8)), dim3(256), 0, s, d64 + 2 * p.n_gemm64, p.n_gemm64, tb2);
     ABT_TRY(hipGetLastError());
     ABT_TRY(launch_gemm_f32_table(ws + p.off_gemm32, (int)g32.size(), tiles32, s));
 #undef ABT_TRY

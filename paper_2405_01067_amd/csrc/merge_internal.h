@@ -32,7 +32,7 @@ struct LayerDev {
     double* LA; double* GB; double* LB; double* Ct; double* Yt;
     double* sigma; double* s3; double* s5;
     double* trace;         // [10]: trace(G_A), trace(G_B), then eight partial sums of ||C||_F^2
-    double* nrm;           // [K]: squared column norms of C, refreshed every sweep, updated by rotations
+    double* nrm;           // [K]: squared column norms of the rotated core (colnorm_kernel -> finalize_kernel)
     int* perm;
     float* PA; float* PB;
     int* rotated;          // [kMaxSweepsCap + 1]
@@ -84,6 +84,14 @@ __device__ __forceinline__ bool jacobi_rotation(double alpha, double beta, doubl
     if (tangent) *tangent = tn;
     return true;
 }
+
+// Average of the copies + Gram matrices (merge_gram.hip): one work-group per job; layer < 0 marks
+// an empty slot; (ti, tj), ti >= tj, is a 128 x 128 tile of the lower triangle; which = 0: G_A
+// (stored into LA), 1: G_B (stored into GB and LB).  The diagonal tiles also write Abar / Bbar.
+struct GramJob { int layer, which, ti, tj; };
+// `jobs` holds njobs entries for the kernel with 16-byte loads, then njobs_unaligned entries (B sides
+// whose row length n is not a multiple of four) for the element-wise one.
+hipError_t launch_mean_gram(const LayerDev* layers, const GramJob* jobs, int njobs, int njobs_unaligned, hipStream_t s);
 
 // One round of the block Jacobi iteration for cores with K <= 768 (every layer of the batch):
 // `n_wg` work-groups, wg_map[i] = (layer, pair slot).  Round 0 of a sweep also orthogonalises the

@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256, (NT <= 6 ? 3 : 1)) void jacobi_block_kernel(co
         for (int s = 0; s < 8; ++s) {
             const int col = (s < 4 ? bI * 16 + kq + 4 * s : bJ * 16 + kq + 4 * (s - 4));
             f64x2 v = {0.0, 0.0};
-            if (row0 < K) v = *reinterpret_cast<const f64x2*>(L.Ct + (int64_t)col * K + row0);
+            if (row0 < K) v = gload(reinterpret_cast<const f64x2*>(L.Ct + (int64_t)col * K + row0));
             D[2 * tt][s] = v[0];
             D[2 * tt + 1][s] = v[1];
         }
@@ -312,7 +312,7 @@ __global__ __launch_bounds__(256, (NT <= 6 ? 3 : 1)) void jacobi_block_kernel(co
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
                 const int col = (s < 4 ? bI * 16 + kq + 4 * s : bJ * 16 + kq + 4 * (s - 4));
-                *reinterpret_cast<f64x2*>(L.Ct + (int64_t)col * K + row0) = f64x2{D[2 * tt][s], D[2 * tt + 1][s]};
+                gstore(reinterpret_cast<f64x2*>(L.Ct + (int64_t)col * K + row0), f64x2{D[2 * tt][s], D[2 * tt + 1][s]});
             }
         }
     }
