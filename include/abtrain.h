@@ -17,10 +17,16 @@
  *     caller; the library never allocates, frees or retains caller memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  lr_linear_fwd,
  *     lr_linear_bwd, lr_conv_fwd, lr_conv_bwd, ab_adamw_step and ab_reconstruct enqueue work on it
- *     and return without synchronising the host.  ab_merge and
- *     ab_merge_batched wait for the stream a few times (after uploading their layer table, and
- *     between Jacobi sweeps to see whether every layer has converged); the back-projection
- *     they enqueue last may still be running when they return.
+ *     and return without synchronising the host.  Calls that DO block the host:
+ *       ab_merge, ab_merge_batched, ab_factorize, ab_factorize_batched: once after uploading
+ *         their layer tables, and from the third Jacobi sweep on once per sweep, for the copy of
+ *         the convergence flags of the sweep BEFORE the one just enqueued (the host stays one
+ *         sweep ahead, so the GPU does not idle meanwhile).  With more than one layer they also
+ *         run layer groups on up to three streams of the library's own (default priority),
+ *         forked from and joined back into `stream` inside the call.  The stages they enqueue
+ *         last (back-projection) may still be running when they return.  Not capturable in a
+ *         HIP graph.
+ *       ab_merge_info: waits for `stream`.
  *   - `workspace` is caller-owned device scratch of at least the size the matching
  *     *_workspace_bytes() query returns, 256-byte aligned; its contents are undefined
  *     afterwards.  Calls that share a workspace must be stream-ordered.
@@ -46,7 +52,8 @@ typedef enum {
     ABT_EWORKSPACE = -4, /* workspace NULL or smaller than *_workspace_bytes() */
     ABT_EDTYPE = -5,     /* unknown abt_dtype */
     ABT_ENOCONV = -6,    /* reported by ab_merge_info: the Jacobi sweep cap was hit */
-    ABT_EHIP = -7        /* a HIP runtime call failed (launch error, copy error) */
+    ABT_EHIP = -7,       /* a HIP runtime call failed (launch error, copy error) */
+    ABT_ENOMEM = -8      /* a host-side table of the call could not be allocated */
 } abt_status;
 
 typedef enum {
@@ -159,7 +166,8 @@ size_t ab_merge_batched_workspace_bytes(const abt_merge_desc* layers, int L);
 /* After the stream work of ab_merge / ab_merge_batched on `workspace` has been enqueued:
  * waits for `stream`, then reports for layer `layer` (0 for ab_merge) the Jacobi sweeps used
  * and the number of singular values computed.  Returns ABT_OK, or ABT_ENOCONV when that
- * layer hit the sweep cap (results were still written). sweeps / n_sigma: HOST, may be NULL. */
+ * layer hit the sweep cap (results were still written), ABT_EINVAL when `layer` is not a layer
+ * of the last merge that ran on this workspace.  sweeps / n_sigma: HOST, may be NULL. */
 int ab_merge_info(const void* workspace, int layer, int32_t* sweeps, int32_t* n_sigma,
                   void* stream);
 

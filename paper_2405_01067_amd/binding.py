@@ -239,6 +239,12 @@ def lr_linear_bwd(dY, X, T, A, B, need_dX: bool = True, need_dA: bool = True, ne
     if T is not None and tuple(_dev_tensor(T, "T").shape) != (M, r):
         raise AbtError("T must be [M,r]")
     dt = _dt(X)
+    for t, nm in ((dY, "dY"), (A, "A"), (B, "B"), (T, "T")):
+        if t is not None and t.dtype != X.dtype:
+            raise AbtError(f"{nm} must have the dtype of X ({X.dtype}), got {t.dtype}")
+    for t, nm, want in ((dX, "dX", X.dtype), (dA, "dA", torch.float32), (dB, "dB", torch.float32)):
+        if t is not None and t.dtype != want:
+            raise AbtError(f"{nm} must be {want}, got {t.dtype}")
     if need_dX and dX is None:
         dX = torch.empty((M, n), dtype=X.dtype, device=X.device)
     if need_dA and dA is None:

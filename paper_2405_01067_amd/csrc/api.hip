@@ -1,6 +1,8 @@
 // C ABI of the library: argument validation, workspace carving and the launch sequences.
 // Every operation is documented in include/abtrain.h.
+#include <atomic>
 #include <cmath>
+#include <new>
 #include <vector>
 
 #include "common.h"
@@ -9,13 +11,13 @@ using namespace abt;
 
 namespace {
 
-int g_max_sweeps = 30;
+std::atomic<int> g_max_sweeps{30};
 
 // Chain kernel choice: for large batches the 128-row kernel where it supports the rank (32, 64, 96,
 // 128, 192); else the 64-row kernel with loader and MFMA waves wherever that supports the rank
 // (32, 64, 96, 128, 160, 192, 256, 320, 384), else the older kernel (224, 288, 352).
-int g_chain_rows = 0;    // 0: automatic; 64 or 128: force that work-group height where the rank allows it
-int g_chain_parts = 0;   // 0: automatic; n: force n column parts for 128-row work-groups
+std::atomic<int> g_chain_rows{0};    // 0: automatic; 64 or 128: force that work-group height where the rank allows it
+std::atomic<int> g_chain_parts{0};   // 0: automatic; n: force n column parts for 128-row work-groups
 
 // Launch shape of the chain kernel.  Measured on gfx950 (forward of configs 2 and 3 and four other
 // shapes): a 128-row work-group takes 1.58 times as long as a 64-row one on the same factors (its
@@ -25,15 +27,16 @@ int g_chain_parts = 0;   // 0: automatic; n: force n column parts for 128-row wo
 // block) never paid in those measurements and are only used when forced.
 struct ChainShape { int rows, parts; };
 
-ChainShape choose_chain_shape(int64_t M, int p, int q, int R, bool second_stage) {
+ChainShape choose_chain_shape(int64_t M, int p, int q, int R, bool second_stage, bool allow_parts) {
     const ChainShape small{64, 1};
-    if (g_chain_rows == 64 || !chain3_supports(R, p, q)) return small;
+    const int rows_forced = g_chain_rows.load(), parts_forced = g_chain_parts.load();
+    if (rows_forced == 64 || !chain2_tall_supports(R, p, q)) return small;
     int parts = 1;
-    if (second_stage && g_chain_parts > 1) {
+    if (allow_parts && second_stage && parts_forced > 1) {
         const int ntile = (int)ceil_div(q, 128);
-        parts = g_chain_parts < ntile ? g_chain_parts : ntile;
+        parts = parts_forced < ntile ? parts_forced : ntile;
     }
-    if (g_chain_rows == 128 || !chain2_supports(R, p, q)) return ChainShape{128, parts};
+    if (rows_forced == 128 || !chain2_supports(R, p, q)) return ChainShape{128, parts};
     const double cost64 = (double)ceil_div(ceil_div(M, 64), 256);
     const double cost128 = 1.58 * (double)ceil_div(ceil_div(M, 128) * parts, 256);
     return cost128 < cost64 ? ChainShape{128, parts} : small;
@@ -43,20 +46,37 @@ ChainShape choose_chain_shape(int64_t M, int p, int q, int R, bool second_stage)
 hipError_t chain_gather(const void* image, const PatchGeom& g, const void* P, const void* Q, void* Yout, void* Tout,
                         int t_pitch, int64_t M, int q, int R, hipStream_t s) {
     const int p = g.kh * g.kw * ((g.Cin + 63) / 64) * 64;
-    const int saved = g_chain_parts;
-    g_chain_parts = 0;
-    const ChainShape sh = choose_chain_shape(M, p, q, R, Yout != nullptr);
-    g_chain_parts = saved;
-    if (sh.rows == 128) return launch_chain3_gather_bf16(image, g, P, Q, Yout, Tout, t_pitch, M, q, R, s);
+    const ChainShape sh = choose_chain_shape(M, p, q, R, Yout != nullptr, false);
+    if (sh.rows == 128) {
+        // the tall launcher checks the image window of a 128-row block before it launches anything and
+        // reports an invalid value when it does not fit 32-bit offsets: take the 64-row kernel then
+        const hipError_t e = launch_chain2_tall_gather_bf16(image, g, P, Q, Yout, Tout, t_pitch, M, q, R, s);
+        if (e != hipErrorInvalidValue) return e;
+        (void)hipGetLastError();
+    }
     return launch_chain2_gather_bf16(image, g, P, Q, Yout, Tout, t_pitch, M, q, R, s);
 }
 
 hipError_t chain(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                  int64_t M, int p, int q, int R, hipStream_t s) {
-    const ChainShape sh = choose_chain_shape(M, p, q, R, Yout != nullptr);
-    if (sh.rows == 128) return launch_chain3_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, sh.parts, s);
+    const ChainShape sh = choose_chain_shape(M, p, q, R, Yout != nullptr, true);
+    if (sh.rows == 128) return launch_chain2_tall_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, sh.parts, s);
     if (chain2_supports(R, p, q)) return launch_chain2_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
     return launch_chain_bf16(Xin, P, Q, Yout, Tout, M, p, q, R, s);
+}
+
+// The entry points promise not to throw: what the host-side tables of a call may throw (allocation
+// failure of a std::vector) becomes a status.
+template <class F>
+int guarded(F&& f) {
+    try { return f(); }
+    catch (const std::bad_alloc&) { return ABT_ENOMEM; }
+    catch (...) { return ABT_EHIP; }
+}
+template <class F>
+size_t guarded_size(F&& f) {
+    try { return f(); }
+    catch (...) { return 0; }
 }
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -137,6 +157,7 @@ const char* abt_status_string(int status) {
         case ABT_EDTYPE: return "ABT_EDTYPE: unknown dtype";
         case ABT_ENOCONV: return "ABT_ENOCONV: Jacobi sweep cap reached";
         case ABT_EHIP: return "ABT_EHIP: HIP runtime error";
+        case ABT_ENOMEM: return "ABT_ENOMEM: host memory allocation failed";
         default: return "unknown abt_status";
     }
 }
@@ -275,6 +296,7 @@ int ab_adamw_step(const abt_adamw_tensor* tensors, int n, int64_t step,
     if (!std::isfinite(lr) || !std::isfinite(lr_scale) || !std::isfinite(eps) || !std::isfinite(weight_decay) ||
         !(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0) || eps < 0.0)
         return ABT_EINVAL;
+    return guarded([&]() -> int {
     std::vector<AdamwTensor> v;
     v.reserve((size_t)n);
     for (int i = 0; i < n; ++i) {
@@ -299,6 +321,7 @@ int ab_adamw_step(const abt_adamw_tensor* tensors, int n, int64_t step,
     h.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
     h.eps = (float)eps; h.eta = (float)(lr * lr_scale); h.weight_decay = (float)weight_decay;
     return launch_adamw(v.data(), (int)v.size(), h, (hipStream_t)stream) == hipSuccess ? ABT_OK : ABT_EHIP;
+    });
 }
 
 double ab_lr_rebound_scale(int64_t i, int64_t rebound_steps) {
@@ -318,21 +341,17 @@ int ab_reconstruct(const float* A, const float* B, float* W,
 }
 
 int abt_set_chain_rows(int rows) {
-    const int prev = g_chain_rows;
-    if (rows == 0 || rows == 64 || rows == 128) g_chain_rows = rows;
-    return prev;
+    if (rows == 0 || rows == 64 || rows == 128) return g_chain_rows.exchange(rows);
+    return g_chain_rows.load();
 }
 
 int abt_set_chain_parts(int parts) {
-    const int prev = g_chain_parts;
-    if (parts >= 0 && parts <= 8) g_chain_parts = parts;
-    return prev;
+    if (parts >= 0 && parts <= 8) return g_chain_parts.exchange(parts);
+    return g_chain_parts.load();
 }
 
 int abt_set_jacobi_max_sweeps(int max_sweeps) {
-    const int prev = g_max_sweeps;
-    g_max_sweeps = max_sweeps < 1 ? 1 : (max_sweeps > 64 ? 64 : max_sweeps);
-    return prev;
+    return g_max_sweeps.exchange(max_sweeps < 1 ? 1 : (max_sweeps > 64 ? 64 : max_sweeps));
 }
 
 int abt_set_merge_groups(int groups) { return merge_set_groups(groups); }
@@ -443,7 +462,7 @@ size_t ab_merge_batched_workspace_bytes(const abt_merge_desc* layers, int L) {
         if (layers[l].G < 1 || layers[l].m < 1 || layers[l].n < 1 || layers[l].k < 1 || layers[l].k_cap < 1 ||
             (layers[l].mode != 0 && layers[l].mode != 1))
             return 0;
-    return merge_workspace_bytes(layers, L);
+    return guarded_size([&] { return merge_workspace_bytes(layers, L); });
 }
 
 int ab_merge_batched(const abt_merge_desc* layers, int L, void* workspace, size_t workspace_bytes, void* stream) {
@@ -452,9 +471,11 @@ int ab_merge_batched(const abt_merge_desc* layers, int L, void* workspace, size_
         const int st = check_merge_layer(layers[l]);
         if (st != ABT_OK) return st;
     }
-    if (!workspace || workspace_bytes < merge_workspace_bytes(layers, L)) return ABT_EWORKSPACE;
-    if (!aligned(workspace, 256)) return ABT_EALIGN;
-    return merge_run(layers, L, workspace, g_max_sweeps, (hipStream_t)stream) == hipSuccess ? ABT_OK : ABT_EHIP;
+    return guarded([&]() -> int {
+        if (!workspace || workspace_bytes < merge_workspace_bytes(layers, L)) return ABT_EWORKSPACE;
+        if (!aligned(workspace, 256)) return ABT_EALIGN;
+        return merge_run(layers, L, workspace, g_max_sweeps, (hipStream_t)stream) == hipSuccess ? ABT_OK : ABT_EHIP;
+    });
 }
 
 size_t ab_merge_workspace_bytes(int G, int64_t m, int64_t n, int64_t k, int64_t k_cap, int mode) {
@@ -520,12 +541,15 @@ FactorizePlan plan_factorize(const abt_factorize_desc* layers, int L) {
 extern "C" {
 
 size_t ab_factorize_batched_workspace_bytes(const abt_factorize_desc* layers, int L) {
-    const FactorizePlan p = plan_factorize(layers, L);
-    return p.status == ABT_OK ? p.total : 0;
+    return guarded_size([&]() -> size_t {
+        const FactorizePlan p = plan_factorize(layers, L);
+        return p.status == ABT_OK ? p.total : 0;
+    });
 }
 
 int ab_factorize_batched(const abt_factorize_desc* layers, int L, void* workspace, size_t workspace_bytes,
                          void* stream) {
+    return guarded([&]() -> int {
     FactorizePlan p = plan_factorize(layers, L);
     if (p.status != ABT_OK) return p.status;
     for (int l = 0; l < L; ++l) {
@@ -550,6 +574,7 @@ int ab_factorize_batched(const abt_factorize_desc* layers, int L, void* workspac
         if (launch_identity_f32((float*)((char*)workspace + p.eye_off[i]), (int)p.Ks[i], (hipStream_t)stream) != hipSuccess)
             return ABT_EHIP;
     return merge_run(p.merge.data(), L, workspace, g_max_sweeps, (hipStream_t)stream) == hipSuccess ? ABT_OK : ABT_EHIP;
+    });
 }
 
 size_t ab_factorize_workspace_bytes(int64_t m, int64_t n, int64_t k_cap) {
@@ -570,7 +595,9 @@ int ab_factorize(const float* W, int64_t m, int64_t n, float tau, int64_t k_fixe
 int ab_merge_info(const void* workspace, int layer, int32_t* sweeps, int32_t* n_sigma, void* stream) {
     if (!workspace || layer < 0) return ABT_EINVAL;
     int32_t info[4] = {0, 0, 0, 0};
-    if (merge_read_info(workspace, layer, info, (hipStream_t)stream) != hipSuccess) return ABT_EHIP;
+    const hipError_t e = merge_read_info(workspace, layer, info, (hipStream_t)stream);
+    if (e == hipErrorInvalidValue) return ABT_EINVAL;       // not a merge workspace, or no such layer in it
+    if (e != hipSuccess) return ABT_EHIP;
     if (sweeps) *sweeps = info[0];
     if (n_sigma) *n_sigma = info[1];
     return info[2] ? ABT_OK : ABT_ENOCONV;

@@ -78,8 +78,8 @@ hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, voi
 // waves): every slab of a factor serves twice the rows.  R in {32, 64, 96, 128, 192}.  With
 // parts > 1 the grid gets that many work-groups per row block, each doing its share of the output
 // tiles of stage 2 after repeating stage 1 (for batches too small to fill the chip otherwise).
-bool chain3_supports(int R, int p, int q);
-hipError_t launch_chain3_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
+bool chain2_tall_supports(int R, int p, int q);
+hipError_t launch_chain2_tall_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                               int64_t M, int p, int q, int R, int parts, hipStream_t s);
 // The same chain with the first operand gathered from a channels-last image [M / (H W), H, W, Cin]
 // instead of read from a matrix: row i of the virtual operand is the kh x kw patch around pixel i
@@ -90,7 +90,7 @@ hipError_t launch_chain3_bf16(const void* Xin, const void* P, const void* Q, voi
 struct PatchGeom { int H, W, Cin, kh, kw, sign; };
 hipError_t launch_chain2_gather_bf16(const void* image, const PatchGeom& g, const void* P, const void* Q,
                                      void* Yout, void* Tout, int t_pitch, int64_t M, int q, int R, hipStream_t s);
-hipError_t launch_chain3_gather_bf16(const void* image, const PatchGeom& g, const void* P, const void* Q,
+hipError_t launch_chain2_tall_gather_bf16(const void* image, const PatchGeom& g, const void* P, const void* Q,
                                      void* Yout, void* Tout, int t_pitch, int64_t M, int q, int R, hipStream_t s);
 // dst[c, r] = src[r, c] for a bf16 matrix of `rows` x `cols`.
 struct TransposeJob { const void* src; void* dst; int rows, cols; };   // dst[cols, rows] = src[rows, cols]^T

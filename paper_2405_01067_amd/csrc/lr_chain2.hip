@@ -44,21 +44,9 @@
 // often needs fewer rounds.  Twelve waves leave 168 registers per lane, so the register rings are
 // shallower and a stage-2 slab holds at most 96 contraction columns (two slabs per output tile for
 // R = 192), which also keeps four staging tiles plus two slab slots inside the 160 KB of LDS.
-#include "common.h"
+#include <atomic>
 
-// Phase timing for tuning, compiled out of the library: with -DABT_TIMING, wave 0 (role 0, an MFMA
-// wave) and the first loader wave (role 1) of work-group 5 record the cycle counter at the marked
-// points into abt_tbuf (once per launch) and abt_tl (per slab of stage 2); a test program that
-// includes this file reads them back with hipMemcpyFromSymbol.
-#ifdef ABT_TIMING
-__device__ long long abt_tbuf[2][64];
-#define TMARK(role, i) do { if (blockIdx.x == 5 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? ABT_LOADER_WAVE : 0)) abt_tbuf[role][i] = __builtin_readcyclecounter(); } while (0)
-__device__ long long abt_tl[2][4][32];
-#define TSTAMP(role, k, it) do { if (blockIdx.x == 5 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? ABT_LOADER_WAVE : 0) && (it) < 32) abt_tl[role][k][it] = __builtin_readcyclecounter(); } while (0)
-#else
-#define TMARK(role, i) do {} while (0)
-#define TSTAMP(role, k, it) do {} while (0)
-#endif
+#include "common.h"
 
 namespace abt {
 
@@ -308,7 +296,6 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
             for (int d = 0; d < D1; ++d) load(ring[d], d);
             store(ring[0], 0);
             load(ring[0], D1);
-            TMARK(1, 0);
             wg_barrier();                                   // slab 0 is in slot 0
             for (int s0 = 0; s0 < n1p; s0 += D1) {
 #pragma unroll
@@ -317,7 +304,6 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
                     wg_barrier();
                 }
             }
-            TMARK(1, 1);
         }
         // stage-2 ring: D2 slabs of Q in flight.  The descriptor is rebuilt per slab (scalar work) to
         // cover exactly the tile's rows: the wave-uniform offset of a buffer access is not range
@@ -420,10 +406,8 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
             for (int d = 0; d < D2; ++d) {
                 const int s = s0 + d;
                 const bool flush = s > 0 && s % KSL == 0 && flushed < ntile;
-                TSTAMP(1, 0, s);
                 step2(ring2[(d + 1) % D2], s, flush, flushed);
                 if (flush) ++flushed;
-                TSTAMP(1, 3, s);
                 wg_barrier();
             }
         }
@@ -432,7 +416,6 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
 #pragma unroll
             for (int e = 0; e < NY; ++e) flush_store(flushed, e);
         }
-        TMARK(1, 2);
         return;
     }
 
@@ -451,10 +434,7 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
         for (int b = 0; b < CB; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc1[a][b][v] = 0.0f;
-
-    TMARK(0, 0);
     wg_barrier();                                       // slab 0 is in slot 0
-    TMARK(0, 1);
     for (int s = 0; s < n1p; ++s) {
         if (s < ns1) {
             const unsigned char* base = lds + (s & 1) * L::slab1;
@@ -481,8 +461,6 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
         }
         wg_barrier();
     }
-
-    TMARK(0, 2);
     // ------------------------------------------------------------------ sum over the KS groups, T tile (bf16) to LDS
     // lane holds T[32(rs RA + a) + lj][32(cs CB + b) + 8g + 4 lh + (0..3)] in acc1[a][b][4g .. 4g+3]
     auto emit_T = [&](const f32x16 (&blk)[CB], int a) {
@@ -518,7 +496,6 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
                     keep[b][4 * g] += v[0]; keep[b][4 * g + 1] += v[1];
                     keep[b][4 * g + 2] += v[2]; keep[b][4 * g + 3] += v[3];
                 }
-            TMARK(0, 3);
             emit_T(keep, a_keep);
         };
         if (ks == 0) swap_and_emit(acc1[1], acc1[0], 0);
@@ -558,7 +535,6 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
                 if (half > 1) wg_barrier();             // the next round overwrites what was just read
             }
         }
-        TMARK(0, 3);
         if (ks == 0) {
 #pragma unroll
             for (int a = 0; a < RA; ++a) emit_T(acc1[a], a);
@@ -577,10 +553,7 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
         for (int kb = 0; kb < KB; ++kb)
             tf[a][kb] = *reinterpret_cast<const u32x4*>(ttile_g + (32 * a + lj) * L::tpitch + (16 * kb + 8 * lh) * 2);
     wg_barrier();                                       // T tile consumed; stage 2 takes over the LDS
-    TMARK(0, 4);
     wg_barrier();                                       // Q slab 0 is in slot 0
-    TMARK(0, 5);
-
     // ------------------------------------------------------------------ stage 2
     f32x16 acc2[2];
     for (int s0 = 0; s0 < n2p; s0 += KSL) {
@@ -592,7 +565,6 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
             for (int v = 0; v < 16; ++v) acc2[a][v] = 0.0f;
 #pragma unroll
         for (int kslab = 0; kslab < KSL; ++kslab) {
-            TSTAMP(0, 0, s0 + kslab);
             if (live) {
                 const unsigned char* base = lds + ((s0 + kslab) & 1) * L::slab2;
                 const int row = 32 * w4 + lj;
@@ -617,11 +589,9 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
                         }
                 }
             }
-            TSTAMP(0, 1, s0 + kslab);
             wg_barrier();
         }
     }
-    TMARK(0, 6);
 }
 
 #undef ABT_LOADER_WAVE
@@ -635,12 +605,13 @@ hipError_t launch_chain_r(const void* Xin, const void* P, const void* Q, void* Y
     // column parts: each does its share of the 128-column output tiles (and repeats stage 1)
     if (parts < 1 || parts > 64 || (Yout != nullptr && parts > (q + 127) / 128) || (Yout == nullptr && parts != 1))
         return hipErrorInvalidValue;
-    static bool attr_set = false;
-    if (!attr_set) {
+    // (setting the attribute twice from two host threads is harmless; the flag only saves the call)
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chain2_bf16_kernel<R, RG, GATHER>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((chain2_bf16_kernel<R, RG, GATHER>), dim3((unsigned)ceil_div(M, L::ROWS), (unsigned)parts),
                        dim3(64 * (NMW_ * RG + NLW)), lds_bytes, s,
@@ -692,7 +663,7 @@ bool chain2_supports(int R, int p, int q) {
 
 // Ranks whose two reduction scratches, T tiles and staging tiles fit the LDS and whose T operands
 // fit the 168 registers twelve waves leave (R = 384 would need 192 for them alone).
-bool chain3_supports(int R, int p, int q) {
+bool chain2_tall_supports(int R, int p, int q) {
     if (p % 64 != 0 || p > (1 << 20) || q > (1 << 20)) return false;
     switch (R) {
         case 32: case 64: case 96: case 128: case 192: return true;
@@ -705,7 +676,7 @@ hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, voi
     return launch_chain_64<false>(Xin, P, Q, Yout, Tout, M, p, q, R, R, Ch2Gather{}, s);
 }
 
-hipError_t launch_chain3_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
+hipError_t launch_chain2_tall_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                               int64_t M, int p, int q, int R, int parts, hipStream_t s) {
     return launch_chain_128<false>(Xin, P, Q, Yout, Tout, M, p, q, R, R, Ch2Gather{}, parts, s);
 }
@@ -719,11 +690,11 @@ hipError_t launch_chain2_gather_bf16(const void* image, const PatchGeom& g, cons
     return launch_chain_64<true>(image, P, Q, Yout, Tout, M, (int)p, q, R, t_pitch, gg, s);
 }
 
-hipError_t launch_chain3_gather_bf16(const void* image, const PatchGeom& g, const void* P, const void* Q,
+hipError_t launch_chain2_tall_gather_bf16(const void* image, const PatchGeom& g, const void* P, const void* Q,
                                      void* Yout, void* Tout, int t_pitch, int64_t M, int q, int R, hipStream_t s) {
     const int cpb = (g.Cin + 63) / 64;
     const int64_t p = (int64_t)g.kh * g.kw * cpb * 64;
-    if (!gather_ok(g, M, p, t_pitch, R, 128) || !chain3_supports(R, (int)p, q)) return hipErrorInvalidValue;
+    if (!gather_ok(g, M, p, t_pitch, R, 128) || !chain2_tall_supports(R, (int)p, q)) return hipErrorInvalidValue;
     const Ch2Gather gg{g.H, g.W, g.Cin, cpb, g.kh, g.kw, g.sign};
     return launch_chain_128<true>(image, P, Q, Yout, Tout, M, (int)p, q, R, t_pitch, gg, 1, s);
 }

@@ -15,14 +15,6 @@
 // ds_read_b64_tr_b16 instead was limited by the rate of those 8-byte reads.)
 #include "common.h"
 
-// Per-slab timing for tuning, compiled out of the library (see the same switch in lr_chain2.hip).
-#ifdef ABT_TIMING
-__device__ long long abt_tn_tl[2][2][64];
-#define TN_STAMP(role, k, it) do { if (blockIdx.x == 26 && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == ((role) ? 4 : 0) && (it) < 64) abt_tn_tl[role][k][it] = __builtin_readcyclecounter(); } while (0)
-#else
-#define TN_STAMP(role, k, it) do {} while (0)
-#endif
-
 namespace abt {
 
 namespace {
@@ -230,7 +222,6 @@ __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int co
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             const int s = s0 + d;
-            TN_STAMP(1, 0, s);
             unsigned char* base = lds + ((s + 1) & 1) * slab_bytes;    // slab s+1; slot s&1 is being read
             const rsrc_t res = descriptor(s + 1 + D);
 #pragma unroll
@@ -239,7 +230,6 @@ __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int co
                 fetch(ring[(d + 1) % D][b], res, s + 1 + D, b);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            TN_STAMP(1, 1, s);
             ring_barrier();
         }
     }
@@ -309,7 +299,6 @@ __global__ __launch_bounds__(Tn2<R>::NT) void tn2_bf16_kernel(Tn2Args args) {
 
     ring_barrier();                                      // slab 0 is in slot 0
     for (int s = 0; s < np; ++s) {
-        TN_STAMP(0, 0, s);
         if (s < nslab) {
             const unsigned char* base = lds + (s & 1) * C::slab;
 #pragma unroll
@@ -327,7 +316,6 @@ __global__ __launch_bounds__(Tn2<R>::NT) void tn2_bf16_kernel(Tn2Args args) {
                 }
             }
         }
-        TN_STAMP(0, 1, s);
         ring_barrier();
     }
 

@@ -710,7 +710,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(const LayerDev* __restric
 // ------------------------------------------------------------------------------------------
 struct Plan {
     int L = 0;
-    size_t off_info = 0, off_layers = 0, off_ptrs = 0, off_gram_tiles = 0, off_wg_cross = 0,
+    size_t off_header = 0, off_info = 0, off_layers = 0, off_ptrs = 0, off_gram_tiles = 0, off_wg_cross = 0,
            off_wg_intra = 0, off_gemm64 = 0, off_gemm32 = 0, off_rotated = 0, off_data = 0, total = 0;
     int n_gram_tiles = 0, n_wg_cross = 0, n_wg_intra = 0, n_gemm64 = 0, n_gemm32 = 0, n_ptrs = 0;
     int nb_max = 0, K_max = 0, jb_max = 0;
@@ -775,6 +775,7 @@ Plan make_plan(const abt_merge_desc* layers, int L) {
     p.pl.resize(L);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    p.off_header = take(sizeof(int) * 4);                      // magic, L (merge_read_info bounds `layer` with it)
     p.off_info = take(sizeof(int) * kInfoInts * L);
     p.off_layers = take(sizeof(LayerDev) * L);
     for (int l = 0; l < L; ++l) {
@@ -916,10 +917,17 @@ hipError_t launch_identity_f32(float* dst, int K, hipStream_t s) {
     return hipGetLastError();
 }
 
+constexpr int kWorkspaceMagic = 0x41425431;
+
 hipError_t merge_read_info(const void* workspace, int layer, int32_t out[4], hipStream_t s) {
     hipError_t e = hipStreamSynchronize(s);
     if (e != hipSuccess) return e;
-    return hipMemcpy(out, (const char*)workspace + sizeof(int) * kInfoInts * layer,
+    int hdr[4] = {0, 0, 0, 0};
+    e = hipMemcpy(hdr, workspace, sizeof(hdr), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return e;
+    if (hdr[0] != kWorkspaceMagic || layer < 0 || layer >= hdr[1]) return hipErrorInvalidValue;
+    // the info table follows the 256-byte header slot (see make_plan)
+    return hipMemcpy(out, (const char*)workspace + 256 + sizeof(int) * kInfoInts * layer,
                      sizeof(int) * kInfoInts, hipMemcpyDeviceToHost);
 }
 
@@ -1014,6 +1022,8 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
     // ---- upload the tables (pageable sources: staged by the runtime before each call returns)
     hipError_t e;
 #define ABT_TRY(x) do { e = (x); if (e != hipSuccess) return e; } while (0)
+    const int header[4] = {kWorkspaceMagic, L, 0, 0};
+    ABT_TRY(hipMemcpyAsync(ws + p.off_header, header, sizeof(header), hipMemcpyHostToDevice, s));
     ABT_TRY(hipMemcpyAsync(ws + p.off_layers, hl.data(), sizeof(LayerDev) * L, hipMemcpyHostToDevice, s));
     ABT_TRY(hipMemcpyAsync(ws + p.off_ptrs, hptrs.data(), sizeof(void*) * p.n_ptrs, hipMemcpyHostToDevice, s));
     ABT_TRY(hipMemcpyAsync(ws + p.off_gram_tiles, gtiles.data(), sizeof(GramJob) * gtiles.size(), hipMemcpyHostToDevice, s));
@@ -1031,8 +1041,6 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
         const int64_t n = (int64_t)(kMaxSweepsCap + 1) * L;
         hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s,
                            (int*)(ws + p.off_rotated), n, 0);
-        // sweeps never run count as "nothing rotated" only if an earlier sweep converged; mark the
-        // slots past the cap as dirty so finalize reports non-convergence correctly
     }
     ABT_TRY(launch_mean_gram(dl, (const GramJob*)(ws + p.off_gram_tiles), gram_aligned, p.n_gram_tiles - gram_aligned, s));
     if (p.K_max <= kCholMaxK) {

@@ -1,9 +1,12 @@
 """Seeded synthetic inputs shared by the CPU oracle's tests and the HIP path's tests/bench.
 
-This module only draws random numbers and lays them out; it holds none of the method's
-arithmetic (no factored products, no SVD, no rank rule).  The one linear-algebra routine it
-calls, a QR of a Gaussian matrix, is used purely to draw random orthonormal frames for planted
-test matrices.  Everything is NumPy on the host; callers upload the arrays they need.
+This module only draws random numbers and lays them out: no factored products, no SVD, no rank
+rule, nothing the oracle or the kernels compute.  The one linear-algebra routine it calls, a QR
+of a Gaussian matrix, draws random orthonormal frames; `planted_factor_pair` scales such frames
+by the square roots of a chosen spectrum, because the workloads prescribe inputs of that form
+(factor copies that look like the output of a decomposition with a known spectrum).  Neither the
+oracle nor the library calls it to do their own arithmetic.  Everything is NumPy on the host;
+callers upload the arrays they need.
 
 The workloads mirror the layer shapes of the paper's experiments (ViT-B/16 and ResNet-50 at
 local batch 64/256, Sec. "Experiments"); the paper's datasets and trained weights are replaced

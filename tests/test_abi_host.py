@@ -37,7 +37,7 @@ def test_header_functions_are_exported(lib):
 
 def test_status_strings(lib):
     assert abt.status_string(0) == "ABT_OK"
-    for code in range(-7, 0):
+    for code in range(-8, 0):
         s = abt.status_string(code)
         assert s.startswith("ABT_E"), s
     assert "unknown" in abt.status_string(-99)
@@ -231,3 +231,9 @@ def test_sweep_cap_setter(lib):
     prev = abt.set_jacobi_max_sweeps(5)
     assert abt.set_jacobi_max_sweeps(1000) == 5
     assert abt.set_jacobi_max_sweeps(prev) == 64
+
+
+def test_merge_group_setter(lib):
+    prev = abt.set_merge_groups(2)
+    assert abt.set_merge_groups(-5) == 2          # negative: back to "as many as allowed"
+    assert abt.set_merge_groups(prev) == 0
