@@ -16,7 +16,7 @@
  *   - Unless a parameter is documented as a HOST pointer it is a DEVICE pointer owned by the
  *     caller; the library never allocates, frees or retains caller memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  lr_linear_fwd,
- *     lr_linear_bwd, lr_conv_fwd, lr_conv_bwd, ab_adamw_step and ab_reconstruct enqueue work on it
+ *     lr_linear_bwd, lr_linear_bwd_static, lr_conv_fwd, lr_conv_bwd, ab_adamw_step and ab_reconstruct enqueue work on it
  *     and return without synchronising the host.  Calls that DO block the host:
  *       ab_merge, ab_merge_batched, ab_factorize, ab_factorize_batched: once after uploading
  *         their layer tables, and from the third Jacobi sweep on once per sweep, for the copy of
@@ -53,7 +53,8 @@ typedef enum {
     ABT_EDTYPE = -5,     /* unknown abt_dtype */
     ABT_ENOCONV = -6,    /* reported by ab_merge_info: the Jacobi sweep cap was hit */
     ABT_EHIP = -7,       /* a HIP runtime call failed (launch error, copy error) */
-    ABT_ENOMEM = -8      /* a host-side table of the call could not be allocated */
+    ABT_ENOMEM = -8,     /* a host-side table of the call could not be allocated */
+    ABT_ETOOLARGE = -9   /* lr_linear_bwd_static: the shape needs more than ABT_STATIC_SCRATCH_BYTES */
 } abt_status;
 
 typedef enum {
@@ -103,6 +104,26 @@ int lr_linear_bwd(const void* dY, const void* X, const void* T, const void* A, c
                   void* workspace, size_t workspace_bytes, void* stream);
 
 size_t lr_linear_bwd_workspace_bytes(int64_t M, int64_t m, int64_t n, int64_t r, int dt);
+
+/* ---------------------------------------------------------------------------------------
+ * lr_linear_bwd for callers that cannot allocate device memory and have no workspace to hand
+ * over: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results and kernels as lr_linear_bwd, but the workspace is an
+ * array of ABT_STATIC_SCRATCH_BYTES inside the library's device code (each GPU the library
+ * runs on holds its own copy until the process ends).  The call allocates nothing, on the
+ * host or on the device, and frees nothing.
+ * A shape for which lr_linear_bwd_workspace_bytes() exceeds ABT_STATIC_SCRATCH_BYTES is
+ * rejected with ABT_ETOOLARGE before anything is enqueued.
+ * All calls on one GPU share that GPU's array: two calls whose kernels may overlap (different
+ * streams, different host threads) race on it and give undefined gradients; calls on one
+ * stream are safe back to back.  Nothing in the array has to start at zero, and nothing a
+ * call leaves there is read by a later one.
+ * ------------------------------------------------------------------------------------- */
+#define ABT_STATIC_SCRATCH_BYTES (64u << 20)
+int lr_linear_bwd_static(const void* dY, const void* X, const void* T, const void* A, const void* B,
+                         void* dX, float* dA, float* dB,
+                         int64_t M, int64_t m, int64_t n, int64_t r, int dt, int accumulate,
+                         void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * Merge of G group copies of one layer's factors (Algorithm 1: A <- allReduce(A/worldSize),

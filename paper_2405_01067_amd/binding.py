@@ -11,6 +11,7 @@ from typing import List, Optional, Sequence
 
 ABT_F32, ABT_BF16 = 0, 1
 ABT_ENOCONV = -6
+ABT_ETOOLARGE = -9
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libabtrain.so")
 _lib = None
@@ -18,7 +19,7 @@ _lib = None
 EXPORTS = (
     "abt_status_string", "abt_set_jacobi_max_sweeps", "abt_set_merge_groups", "abt_set_chain_rows", "abt_set_chain_parts",
     "lr_linear_fwd", "lr_linear_fwd_workspace_bytes",
-    "lr_linear_bwd", "lr_linear_bwd_workspace_bytes",
+    "lr_linear_bwd", "lr_linear_bwd_workspace_bytes", "lr_linear_bwd_static",
     "ab_merge", "ab_merge_workspace_bytes",
     "ab_merge_batched", "ab_merge_batched_workspace_bytes", "ab_merge_info",
     "ab_factorize", "ab_factorize_workspace_bytes",
@@ -95,6 +96,8 @@ def load():
     lib.lr_linear_bwd.restype = ci
     lib.lr_linear_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, vp, sz, vp]
     lib.lr_linear_bwd_workspace_bytes.restype = sz
+    lib.lr_linear_bwd_static.restype = ci
+    lib.lr_linear_bwd_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, vp]
     lib.lr_linear_bwd_workspace_bytes.argtypes = [i64, i64, i64, i64, ci]
     pvp = ctypes.POINTER(ctypes.c_void_p)
     lib.ab_merge.restype = ci
@@ -262,6 +265,33 @@ def lr_linear_bwd(dY, X, T, A, B, need_dX: bool = True, need_dA: bool = True, ne
                              _ptr(dB if need_dB else None), M, m, n, r, dt, int(bool(accumulate)),
                              _ptr(ws), ws.numel(), _stream()), "lr_linear_bwd")
     return (dX if need_dX else None), (dA if need_dA else None), (dB if need_dB else None)
+
+
+STATIC_SCRATCH_BYTES = 64 << 20   # ABT_STATIC_SCRATCH_BYTES of the header
+
+
+def lr_linear_bwd_static(dY, X, T, A, B, dX=None, dA=None, dB=None, accumulate: bool = False):
+    """lr_linear_bwd through the entry point that allocates nothing: the caller passes every output
+    it wants (None skips that gradient) and the library uses its own static scratch array.
+    Returns (dX, dA, dB) as passed."""
+    torch = _torch()
+    lib = load()
+    dY, X, A, B = (_dev_tensor(t, nm) for t, nm in ((dY, "dY"), (X, "X"), (A, "A"), (B, "B")))
+    M, n = X.shape
+    m, r = A.shape
+    if tuple(dY.shape) != (M, m) or tuple(B.shape) != (r, n):
+        raise AbtError("shape mismatch: dY [M,m], X [M,n], A [m,r], B [r,n]")
+    for t, nm, shape, want in ((T, "T", (M, r), X.dtype), (dY, "dY", (M, m), X.dtype), (A, "A", (m, r), X.dtype),
+                               (B, "B", (r, n), X.dtype), (dX, "dX", (M, n), X.dtype),
+                               (dA, "dA", (m, r), torch.float32), (dB, "dB", (r, n), torch.float32)):
+        if t is None:
+            continue
+        _dev_tensor(t, nm)
+        if tuple(t.shape) != shape or t.dtype != want:
+            raise AbtError(f"{nm} must be {shape} of {want}, got {tuple(t.shape)} of {t.dtype}")
+    _check(lib.lr_linear_bwd_static(_ptr(dY), _ptr(X), _ptr(T), _ptr(A), _ptr(B), _ptr(dX), _ptr(dA), _ptr(dB),
+                                    M, m, n, r, _dt(X), int(bool(accumulate)), _stream()), "lr_linear_bwd_static")
+    return dX, dA, dB
 
 
 def _conv_geom(act, B, kh, kw):

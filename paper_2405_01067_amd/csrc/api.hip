@@ -158,6 +158,7 @@ const char* abt_status_string(int status) {
         case ABT_ENOCONV: return "ABT_ENOCONV: Jacobi sweep cap reached";
         case ABT_EHIP: return "ABT_EHIP: HIP runtime error";
         case ABT_ENOMEM: return "ABT_ENOMEM: host memory allocation failed";
+        case ABT_ETOOLARGE: return "ABT_ETOOLARGE: shape needs more than the static scratch array";
         default: return "unknown abt_status";
     }
 }
@@ -454,6 +455,43 @@ int lr_linear_bwd(const void* dY, const void* X, const void* T, const void* A, c
         if (e != hipSuccess) return ABT_EHIP;
     }
     return ABT_OK;
+}
+
+// ------------------------------------------------------------------ backward without allocation
+// The scratch of lr_linear_bwd_static: one array per GPU, held from the moment the library's code is
+// loaded on that GPU until the process ends.  In host code the name below is only a handle; the
+// array's device address comes from hipGetSymbolAddress, once per device, and only that address is
+// ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[ABT_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ABT_EHIP;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ABT_EHIP;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);   // every thread gets the same address
+    }
+    *out = p;
+    return ABT_OK;
+}
+}  // namespace
+
+int lr_linear_bwd_static(const void* dY, const void* X, const void* T, const void* A, const void* B,
+                         void* dX, float* dA, float* dB,
+                         int64_t M, int64_t m, int64_t n, int64_t r, int dt, int accumulate, void* stream) {
+    const int st = check_lr_shapes(M, m, n, r, dt);
+    if (st != ABT_OK) return st;
+    if (lr_linear_bwd_workspace_bytes(M, m, n, r, dt) > (size_t)ABT_STATIC_SCRATCH_BYTES) return ABT_ETOOLARGE;
+    void* ws = nullptr;
+    const int sp = static_scratch(&ws);
+    if (sp != ABT_OK) return sp;
+    return lr_linear_bwd(dY, X, T, A, B, dX, dA, dB, M, m, n, r, dt, accumulate, ws,
+                         (size_t)ABT_STATIC_SCRATCH_BYTES, stream);
 }
 
 size_t ab_merge_batched_workspace_bytes(const abt_merge_desc* layers, int L) {
