@@ -334,6 +334,19 @@ int abt_set_jacobi_max_sweeps(int max_sweeps);
  * switch; returns the previous setting. */
 int abt_set_merge_groups(int groups);
 
+/* Stage timers of ab_merge_batched / ab_factorize_batched (a measurement switch, off by default;
+ * returns the previous setting).  While on, a call records HIP events on the caller's stream at
+ * its stage boundaries, and ab_merge_stage_ms waits for the last call to finish and writes the
+ * elapsed milliseconds of its ABT_MERGE_STAGES stages to the HOST array `ms`, in the order of
+ * Algorithm 1's merge followed by Eq. 3:
+ *   0 average of the copies + Gram matrices      1 Cholesky factors of the Gram matrices
+ *   2 K x K core product                         3 Jacobi sweeps of the core (all layer groups)
+ *   4 singular values, rank rule, projectors     5 back-projection A', B' (and W when asked for)
+ * Returns ABT_EINVAL if ms is NULL and ABT_EHIP if no timed call has completed. */
+#define ABT_MERGE_STAGES 6
+int abt_set_merge_stage_timing(int on);
+int ab_merge_stage_ms(float* ms);
+
 #ifdef __cplusplus
 }
 #endif

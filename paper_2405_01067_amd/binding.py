@@ -17,7 +17,8 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "lib
 _lib = None
 
 EXPORTS = (
-    "abt_status_string", "abt_set_jacobi_max_sweeps", "abt_set_merge_groups", "abt_set_chain_rows", "abt_set_chain_parts",
+    "abt_status_string", "abt_set_jacobi_max_sweeps", "abt_set_merge_groups", "abt_set_merge_stage_timing",
+    "ab_merge_stage_ms", "abt_set_chain_rows", "abt_set_chain_parts",
     "lr_linear_fwd", "lr_linear_fwd_workspace_bytes",
     "lr_linear_bwd", "lr_linear_bwd_workspace_bytes", "lr_linear_bwd_static",
     "ab_merge", "ab_merge_workspace_bytes",
@@ -89,6 +90,10 @@ def load():
     lib.abt_set_jacobi_max_sweeps.argtypes = [ci]
     lib.abt_set_merge_groups.restype = ci
     lib.abt_set_merge_groups.argtypes = [ci]
+    lib.abt_set_merge_stage_timing.restype = ci
+    lib.abt_set_merge_stage_timing.argtypes = [ci]
+    lib.ab_merge_stage_ms.restype = ci
+    lib.ab_merge_stage_ms.argtypes = [ctypes.POINTER(ctypes.c_float)]
     lib.lr_linear_fwd.restype = ci
     lib.lr_linear_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, vp, sz, vp]
     lib.lr_linear_fwd_workspace_bytes.restype = sz
@@ -162,6 +167,21 @@ def set_jacobi_max_sweeps(n: int) -> int:
 
 def set_merge_groups(n: int) -> int:
     return load().abt_set_merge_groups(int(n))
+
+
+MERGE_STAGES = ("mean_gram", "cholesky", "core_product", "jacobi", "rank_and_projectors", "back_projection")
+
+
+def set_merge_stage_timing(on: bool) -> int:
+    return load().abt_set_merge_stage_timing(int(bool(on)))
+
+
+def merge_stage_ms() -> dict:
+    """Elapsed milliseconds of the stages of the last batched merge / factorisation that ran with
+    the stage timers on (waits for it)."""
+    buf = (ctypes.c_float * len(MERGE_STAGES))()
+    _check(load().ab_merge_stage_ms(buf), "ab_merge_stage_ms")
+    return dict(zip(MERGE_STAGES, (float(x) for x in buf)))
 
 
 # --------------------------------------------------------------------------------------

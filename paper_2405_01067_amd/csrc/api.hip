@@ -357,6 +357,13 @@ int abt_set_jacobi_max_sweeps(int max_sweeps) {
 
 int abt_set_merge_groups(int groups) { return merge_set_groups(groups); }
 
+int abt_set_merge_stage_timing(int on) { return merge_set_stage_timing(on); }
+
+int ab_merge_stage_ms(float* ms) {
+    if (!ms) return ABT_EINVAL;
+    return merge_stage_ms(ms) == hipSuccess ? ABT_OK : ABT_EHIP;
+}
+
 size_t lr_linear_fwd_workspace_bytes(int64_t M, int64_t m, int64_t n, int64_t r, int dt) {
     if (check_lr_shapes(M, m, n, r, dt) != ABT_OK) return 0;
     return dt == ABT_F32 ? align_up((size_t)M * r * 4, 256) : 0;

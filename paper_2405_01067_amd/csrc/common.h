@@ -143,6 +143,11 @@ size_t merge_workspace_bytes(const abt_merge_desc* layers, int L);
 hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int max_sweeps, hipStream_t s);
 hipError_t merge_read_info(const void* workspace, int layer, int32_t out[4], hipStream_t s);
 hipError_t launch_identity_f32(float* dst, int K, hipStream_t s);   // dst[K, K] = I
+// Stage timers of the batched merge: with the switch on, merge_run records events on the caller's
+// stream at its stage boundaries and merge_stage_ms waits for the last and returns the elapsed
+// milliseconds of the ABT_MERGE_STAGES stages (hipErrorNotReady if no timed merge has run).
+int merge_set_stage_timing(int on);
+hipError_t merge_stage_ms(float out[ABT_MERGE_STAGES]);
 int merge_set_groups(int n);   // upper bound on the layer groups (streams) of the Jacobi stage; returns the previous one
 
 // ------------------------------------------------------------------ optimiser step

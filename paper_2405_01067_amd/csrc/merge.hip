@@ -875,6 +875,26 @@ struct SideStreams {
 std::mutex g_side_mutex;     // one batched merge at a time uses the side streams
 SideStreams g_side;
 
+// Stage timers (a measurement switch, off by default): events on the caller's stream at the stage
+// boundaries of the last merge_run, read by merge_stage_ms.
+constexpr int kStageMarks = ABT_MERGE_STAGES + 1;
+std::atomic<int> g_stage_timing{0};
+std::mutex g_stage_mutex;
+hipEvent_t g_stage_event[kStageMarks] = {};
+int g_stage_device = -1;
+int g_stage_recorded = 0;        // marks recorded by the last timed merge_run
+
+bool stage_events_ready() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    if (g_stage_device == dev) return true;
+    if (g_stage_device >= 0) return false;      // created on another device
+    for (int i = 0; i < kStageMarks; ++i)
+        if (hipEventCreate(&g_stage_event[i]) != hipSuccess) return false;
+    g_stage_device = dev;
+    return true;
+}
+
 bool pinned_flags_ready(size_t ints) {
     if (g_side.flags_cap >= ints) return true;
     if (g_side.flags_host) { (void)hipHostFree(g_side.flags_host); g_side.flags_host = nullptr; g_side.flags_cap = 0; }
@@ -910,6 +930,17 @@ bool side_streams_ready() {
 size_t merge_workspace_bytes(const abt_merge_desc* layers, int L) { return make_plan(layers, L).total; }
 
 int merge_set_groups(int n) { return g_merge_groups.exchange(n < 0 ? 0 : n); }
+
+int merge_set_stage_timing(int on) { return g_stage_timing.exchange(on ? 1 : 0); }
+
+hipError_t merge_stage_ms(float out[ABT_MERGE_STAGES]) {
+    std::lock_guard<std::mutex> lock(g_stage_mutex);
+    if (g_stage_recorded != kStageMarks) return hipErrorNotReady;
+    hipError_t e = hipEventSynchronize(g_stage_event[kStageMarks - 1]);
+    for (int i = 0; i < ABT_MERGE_STAGES && e == hipSuccess; ++i)
+        e = hipEventElapsedTime(&out[i], g_stage_event[i], g_stage_event[i + 1]);
+    return e;
+}
 
 hipError_t launch_identity_f32(float* dst, int K, hipStream_t s) {
     const int64_t n = (int64_t)K * K;
@@ -1036,13 +1067,28 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
     // the uploads must have left the host vectors before they are destroyed
     ABT_TRY(hipStreamSynchronize(s));
 
+    std::unique_lock<std::mutex> stage_lock(g_stage_mutex, std::defer_lock);
+    bool timed = false;
+    if (g_stage_timing.load()) {
+        stage_lock.lock();
+        timed = stage_events_ready();
+        g_stage_recorded = 0;
+        if (!timed) stage_lock.unlock();
+    }
+    auto mark = [&](int i) -> hipError_t {
+        if (!timed) return hipSuccess;
+        g_stage_recorded = i + 1;
+        return hipEventRecord(g_stage_event[i], s);
+    };
     const LayerDev* dl = (const LayerDev*)(ws + p.off_layers);
+    ABT_TRY(mark(0));
     {
         const int64_t n = (int64_t)(kMaxSweepsCap + 1) * L;
         hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s,
                            (int*)(ws + p.off_rotated), n, 0);
     }
     ABT_TRY(launch_mean_gram(dl, (const GramJob*)(ws + p.off_gram_tiles), gram_aligned, p.n_gram_tiles - gram_aligned, s));
+    ABT_TRY(mark(1));
     if (p.K_max <= kCholMaxK) {
         const size_t lds = sizeof(double) * ((size_t)(p.K_max > 32 ? p.K_max - 32 : 0) * kCholPitch + 32 * 33 + 32 + kCholThreads);
         static std::atomic<size_t> chol_attr{0};
@@ -1055,10 +1101,12 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
     } else {
         hipLaunchKernelGGL(cholesky_kernel, dim3(2 * L), dim3(256), 0, s, dl);
     }
+    ABT_TRY(mark(2));
     const GemmF64* d64 = (const GemmF64*)(ws + p.off_gemm64);
     hipLaunchKernelGGL(gemm_f64_kernel, dim3(align_up(tb0, 8)), dim3(256), 0, s, d64, p.n_gemm64, tb0);
     hipLaunchKernelGGL(frob2_kernel, dim3(8, L), dim3(256), 0, s, dl);
     ABT_TRY(hipGetLastError());
+    ABT_TRY(mark(3));
 
     const int2* cross = (const int2*)(ws + p.off_wg_cross);
     const int2* intra = (const int2*)(ws + p.off_wg_intra);
@@ -1167,6 +1215,7 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
             }
         }
     }
+    ABT_TRY(mark(4));
     int n2 = 1;
     while (n2 < p.K_max) n2 <<= 1;
     hipLaunchKernelGGL(colnorm_kernel, dim3((p.K_max + 3) / 4, L), dim3(256), 0, s, dl);
@@ -1174,7 +1223,9 @@ hipError_t merge_run(const abt_merge_desc* layers, int L, void* workspace, int m
     if (tb1 > 0) hipLaunchKernelGGL(gemm_f64_kernel, dim3(align_up(tb1, 8)), dim3(256), 0, s, d64 + p.n_gemm64, p.n_gemm64, tb1);
     if (tb2 > 0) hipLaunchKernelGGL(gemm_f64_kernel, dim3(align_up(tb2, 8)), dim3(256), 0, s, d64 + 2 * p.n_gemm64, p.n_gemm64, tb2);
     ABT_TRY(hipGetLastError());
+    ABT_TRY(mark(5));
     ABT_TRY(launch_gemm_f32_table(ws + p.off_gemm32, (int)g32.size(), tiles32, s));
+    ABT_TRY(mark(6));
 #undef ABT_TRY
     return hipSuccess;
 }
