@@ -22,7 +22,11 @@
 //            MFMA wave loads all of it as MFMA operands: T stays in registers for all of stage 2.
 //   stage 2: a slab is 128 rows of Q (all R columns while that fits, else half) and yields a
 //            64 x 128 output tile, 32 columns per MFMA wave; the tile is staged in LDS (two
-//            buffers) and leaves one slab later as full 256-byte row segments.
+//            buffers) and leaves two slabs later as full 256-byte row segments.
+//   In both stages an MFMA wave keeps several operand reads in flight ahead of the MFMAs that use
+//   them and holds the last step of a slab back across the barrier (a lone MFMA wave per SIMD has
+//   nobody to hide its LDS latency behind: with reads issued step by step the loop time was about
+//   three times the MFMA time).
 // (The direct-to-LDS loads of gfx950 were measured at about half the rate of register-staged
 // loads per wave and are not used.)
 //
@@ -45,6 +49,7 @@
 // shallower and a stage-2 slab holds at most 96 contraction columns (two slabs per output tile for
 // R = 192), which also keeps four staging tiles plus two slab slots inside the 160 KB of LDS.
 #include <atomic>
+#include <type_traits>
 
 #include "common.h"
 
@@ -95,6 +100,7 @@ constexpr int BK1 = 64, CPR1 = BK1 / 8;         // stage-1 slab: 64 contraction 
 constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v / 2); }
 constexpr int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 constexpr int gcdi(int a, int b) { return b == 0 ? a : gcdi(b, a % b); }
+constexpr int largest_divisor(int n, int most) { return most <= 1 ? 1 : (n % most == 0 ? most : largest_divisor(n, most - 1)); }
 
 template <int R, int RG>
 struct Ch2Cfg {
@@ -117,6 +123,8 @@ struct Ch2Cfg {
     static constexpr int NCHQ = 128 * CPR2 / NLT;             // chunks per loader thread = BK2 / 16
     static constexpr int D2 = RG == 1 ? clampi(36 / NCHQ, 2, 6) : clampi(20 / NCHQ, 2, 4);   // stage-2 slabs in flight
     static constexpr int U2 = D2 * KSL / gcdi(D2, KSL);       // stage-2 trip count is padded to a multiple of this
+    // operand buffers of an MFMA wave in stage 2 (registers: T takes R / 2 of them, twelve waves leave 168)
+    static constexpr int NB2 = RG == 1 ? (R > 320 ? 2 : 6) : (R > 128 ? 3 : 6);
     static constexpr int ypitch = 128 * 2 + 16;
     static constexpr int ytile = 64 * ypitch;
     static constexpr int red = (C::KS / 2) * C::CS * C::RS * RA * CB * 4096;   // first (largest) round of the tree
@@ -405,13 +413,16 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
 #pragma unroll
             for (int d = 0; d < D2; ++d) {
                 const int s = s0 + d;
-                const bool flush = s > 0 && s % KSL == 0 && flushed < ntile;
+                // tile t is staged by the MFMA waves during slab (t + 1) KSL (they finish a slab's last
+                // step one barrier late) and leaves during the slab after that
+                const bool flush = s > KSL && (s - 1) % KSL == 0 && flushed < ntile;
                 step2(ring2[(d + 1) % D2], s, flush, flushed);
                 if (flush) ++flushed;
                 wg_barrier();
             }
         }
-        if (flushed < ntile) {
+        wg_barrier();                                    // the last tile is staged
+        for (; flushed < ntile; ++flushed) {             // at most the last two tiles, one per staging buffer
             flush_read(flushed);
 #pragma unroll
             for (int e = 0; e < NY; ++e) flush_store(flushed, e);
@@ -434,33 +445,60 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
         for (int b = 0; b < CB; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc1[a][b][v] = 0.0f;
-    wg_barrier();                                       // slab 0 is in slot 0
-    for (int s = 0; s < n1p; ++s) {
-        if (s < ns1) {
-            const unsigned char* base = lds + (s & 1) * L::slab1;
+    // One k16 step's operands.  The steps run as a software pipeline: the operands of step g + 1
+    // are requested before the MFMAs of step g are issued, and the last step of a slab is held back
+    // across the barrier, so that its MFMAs cover the latency of the next slab's first reads (a
+    // slab's data may only be read after the barrier that publishes it).  Operand sets alternate
+    // between two register buffers by the parity of the running step number.
+    struct Ops1 { u32x4 xf[RA]; u32x4 pf[CB]; };
+    Ops1 ob[2];
+    auto read1 = [&](Ops1& o, int s, int j) {
+        const unsigned char* base = lds + (s & 1) * L::slab1;
+        const int kk = ks * SPW + j;                    // k16 step inside the slab
+        const int qc = 2 * kk + lh;                     // logical chunk of this lane's 8 values
 #pragma unroll
-            for (int j = 0; j < SPW; ++j) {
-                const int kk = ks * SPW + j;            // k16 step inside the slab
-                const int qc = 2 * kk + lh;             // logical chunk of this lane's 8 values
-                u32x4 xf[RA], pf[CB];
+        for (int a = 0; a < RA; ++a) {
+            const int row = 64 * grp + 32 * (rs * RA + a) + lj;
+            o.xf[a] = *reinterpret_cast<const u32x4*>(base + row * (BK1 * 2) + swz<CPR1>(qc, row) * 16);
+        }
 #pragma unroll
-                for (int a = 0; a < RA; ++a) {
-                    const int row = 64 * grp + 32 * (rs * RA + a) + lj;
-                    xf[a] = *reinterpret_cast<const u32x4*>(base + row * (BK1 * 2) + swz<CPR1>(qc, row) * 16);
-                }
+        for (int b = 0; b < CB; ++b) {
+            const int row = ROWS + (cs * CB + b) * 32 + lj;
+            o.pf[b] = *reinterpret_cast<const u32x4*>(base + row * (BK1 * 2) + swz<CPR1>(qc, row) * 16);
+        }
+    };
+    auto mma1 = [&](const Ops1& o) {
 #pragma unroll
-                for (int b = 0; b < CB; ++b) {
-                    const int row = ROWS + (cs * CB + b) * 32 + lj;
-                    pf[b] = *reinterpret_cast<const u32x4*>(base + row * (BK1 * 2) + swz<CPR1>(qc, row) * 16);
-                }
+        for (int a = 0; a < RA; ++a)
 #pragma unroll
-                for (int a = 0; a < RA; ++a)
+            for (int b = 0; b < CB; ++b) acc1[a][b] = mfma16(o.pf[b], o.xf[a], acc1[a][b]);
+    };
+    // slab s: the held step of slab s - 1 sits in ob[1] (every slab has an even number of steps, or
+    // a single one that is moved there)
+    auto slab1 = [&](int s) {
+        read1(ob[0], s, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (s > 0) mma1(ob[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (SPW == 1) {
+            ob[1] = ob[0];
+        } else {
 #pragma unroll
-                    for (int b = 0; b < CB; ++b) acc1[a][b] = mfma16(pf[b], xf[a], acc1[a][b]);
+            for (int j = 0; j + 1 < SPW; ++j) {
+                read1(ob[(j + 1) & 1], s, j + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                mma1(ob[j & 1]);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+    };
+    static_assert(SPW == 1 || SPW % 2 == 0, "step parity");
+    wg_barrier();                                       // slab 0 is in slot 0
+    for (int s = 0; s < n1p; ++s) {
+        if (s < ns1) slab1(s);
         wg_barrier();
     }
+    mma1(ob[1]);                                        // the held last step (read before the last barrier)
     // ------------------------------------------------------------------ sum over the KS groups, T tile (bf16) to LDS
     // lane holds T[32(rs RA + a) + lj][32(cs CB + b) + 8g + 4 lh + (0..3)] in acc1[a][b][4g .. 4g+3]
     auto emit_T = [&](const f32x16 (&blk)[CB], int a) {
@@ -555,43 +593,87 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
     wg_barrier();                                       // T tile consumed; stage 2 takes over the LDS
     wg_barrier();                                       // Q slab 0 is in slot 0
     // ------------------------------------------------------------------ stage 2
+    // Software pipeline as in stage 1: a ring of NB operand buffers is refilled as soon as a step's
+    // MFMAs are issued (NB - 1 reads stay in flight), and the last step of a slab is held back across
+    // the barrier.  A tile's accumulators are therefore complete, and staged, one barrier later than
+    // its last slab.
+    constexpr int NS = BK2 / 16;                        // k16 steps per slab
+    constexpr int NB = largest_divisor(NS, L::NB2);     // divides NS: the held step always sits in ring[NB - 1]
+    // The swizzle XORs the low XB bits of the chunk index 2 kk + lh with row bits, and a row starts
+    // at a multiple of 16 << XB bytes (BK2 is a multiple of 8 << XB elements), so the address
+    // of step kk is that of step 0 with (kk mod PER) << 5 XORed in, plus a constant for kk / PER:
+    // one lane address serves all steps.
+    constexpr int XB = CPR2 % 16 == 0 ? 4 : (CPR2 % 8 == 0 ? 3 : 2);
+    constexpr int PER = (1 << XB) / 2;
+    static_assert((BK2 * 2) % (16 << XB) == 0, "row pitch and swizzle width");
+    const int qaddr0 = (32 * w4 + lj) * (BK2 * 2) + swz<CPR2>(lh, 32 * w4 + lj) * 16;
+    auto read2 = [&](u32x4& dst, int s, int kk) {
+        dst = *reinterpret_cast<const u32x4*>(lds + (s & 1) * L::slab2 + (qaddr0 ^ ((kk % PER) << 5)) + (kk / PER) * (16 << XB));
+    };
     f32x16 acc2[2];
-    for (int s0 = 0; s0 < n2p; s0 += KSL) {
-        const int t = s0 / KSL;
-        const bool live = s0 < ns2;                     // padded trips only keep the barrier count
+    u32x4 ring[NB];
+    auto mma2 = [&](const u32x4& qf, int kb) {
+        acc2[0] = mfma16(qf, tf[0][kb], acc2[0]);
+        acc2[1] = mfma16(qf, tf[1][kb], acc2[1]);
+    };
+    auto stage_out = [&](int t) {
+        // lane holds Y[32a + lj][32 wave + 8g + 4 lh + (0..3)] of this 64 x 128 tile
+        unsigned char* yt = ytile + (grp * 2 + (t & 1)) * L::ytile;
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                u32x2 o = {pack2_bf16(acc2[a][4 * g + 0], acc2[a][4 * g + 1]),
+                           pack2_bf16(acc2[a][4 * g + 2], acc2[a][4 * g + 3])};
+                *reinterpret_cast<u32x2*>(yt + (32 * a + lj) * L::ypitch + (32 * w4 + 8 * g + 4 * lh) * 2) = o;
+            }
+    };
+    auto clear2 = [&]() {
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc2[a][v] = 0.0f;
+    };
+    clear2();
+    for (int s0 = 0; s0 < n2p; s0 += KSL) {
+        const int t = s0 / KSL;
 #pragma unroll
         for (int kslab = 0; kslab < KSL; ++kslab) {
+            const int s = s0 + kslab;
+            const bool live = s < ns2;                  // padded trips only keep the barrier count
             if (live) {
-                const unsigned char* base = lds + ((s0 + kslab) & 1) * L::slab2;
-                const int row = 32 * w4 + lj;
 #pragma unroll
-                for (int kk = 0; kk < BK2 / 16; ++kk) {
-                    const u32x4 qf = *reinterpret_cast<const u32x4*>(
-                        base + row * (BK2 * 2) + swz<CPR2>(2 * kk + lh, row) * 16);
-                    const int kb = kslab * (BK2 / 16) + kk;
-                    acc2[0] = mfma16(qf, tf[0][kb], acc2[0]);
-                    acc2[1] = mfma16(qf, tf[1][kb], acc2[1]);
+                for (int i = 0; i + 1 < NB; ++i) read2(ring[i], s, i);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (s > 0 && s - 1 < ns2) {
+                // last step of the slab before this one
+                mma2(ring[NB - 1], ((kslab + KSL - 1) % KSL) * NS + NS - 1);
+                if (kslab == 0) {
+                    stage_out(t - 1);
+                    clear2();
                 }
-                if (kslab == KSL - 1) {
-                    // lane holds Y[32a + lj][32 wave + 8g + 4 lh + (0..3)] of this 64 x 128 tile
-                    unsigned char* yt = ytile + (grp * 2 + (t & 1)) * L::ytile;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (live) {
+                read2(ring[NB - 1], s, NB - 1);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int a = 0; a < 2; ++a)
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            u32x2 o = {pack2_bf16(acc2[a][4 * g + 0], acc2[a][4 * g + 1]),
-                                       pack2_bf16(acc2[a][4 * g + 2], acc2[a][4 * g + 3])};
-                            *reinterpret_cast<u32x2*>(yt + (32 * a + lj) * L::ypitch + (32 * w4 + 8 * g + 4 * lh) * 2) = o;
-                        }
+                for (int kk = 0; kk + 1 < NS; ++kk) {
+                    mma2(ring[kk % NB], kslab * NS + kk);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (kk + NB < NS) read2(ring[kk % NB], s, kk + NB);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
             wg_barrier();
         }
     }
+    if (n2p == ns2) {                                   // no padded trip has finished the last slab
+        mma2(ring[NB - 1], (KSL - 1) * NS + NS - 1);
+        stage_out(ntile - 1);
+    }
+    wg_barrier();                                       // the last tile is staged
 }
 
 #undef ABT_LOADER_WAVE
