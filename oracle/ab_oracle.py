@@ -203,6 +203,69 @@ def reconstruct(A, B):
     return _f64(A) @ _f64(B)
 
 
+def ab_schedule(total_steps):
+    """Phase lengths of Algorithm 1 for a run of `total_steps` steps with the fractions of Sec.
+    "Hyperparameter considerations": warmupSteps 20 %, numABSteps 3.33 % (1/30),
+    fullRankReboundSteps 0.25 numABSteps, learning-rate rebound 0.5 numABSteps.  Reading: each is
+    rounded to the nearest whole step (halves up) and is at least one step.
+    Returns (warmup, num_ab, full_rank_rebound, lr_rebound)."""
+    def whole(x):
+        return max(1, int(np.floor(x + 0.5)))
+    warm = whole(0.2 * total_steps)
+    num_ab = whole(total_steps / 30.0)
+    return warm, num_ab, whole(0.25 * num_ab), whole(0.5 * num_ab)
+
+
+def ab_training_run(weights, groups, tau, lr, batch, loss_grad, full_rank_step, total_steps, **hyper):
+    """Algorithm 1 for a chain of linear layers (the output of layer l feeds layer l + 1, no
+    activations) and `groups` emulated workers, composed of the functions above, in fp64.
+
+    The first half of the groups trains A, the second half B (odd counts: the extra group trains
+    A); the other factor is frozen.  The optimiser state of the trained factors starts at zero in
+    every group-training phase and its step counter at 1 (the parameters have changed shape; the
+    learning-rate rebound is the paper's answer to exactly that).  batch(g, step) gives the input
+    of group g, loss_grad(Y, g, step) the gradient at the last layer's output, and
+    full_rank_step(weights, phase, i, lr_scale) trains the dense weights in place: those three
+    belong to the model, not to the method.  Returns (weights, history): history has one entry
+    per synchronisation, (step, ranks selected at the decomposition, copies of the weights)."""
+    W = [_f64(w).copy() for w in weights]
+    warm, num_ab, reb, lr_reb = ab_schedule(total_steps)
+    step, history = 0, []
+    for i in range(min(warm, total_steps)):
+        full_rank_step(W, "warmup", i, 1.0)
+        step += 1
+    while step < total_steps:
+        factors = [ab_decomposition(w, tau=tau) for w in W]
+        ranks = [f[3] for f in factors]
+        A = [[f[0].copy() for f in factors] for _ in range(groups)]
+        B = [[f[1].copy() for f in factors] for _ in range(groups)]
+        targets = ["A" if g < (groups + 1) // 2 else "B" for g in range(groups)]
+        state = [[(np.zeros_like(A[g][l] if targets[g] == "A" else B[g][l]),) * 2 for l in range(len(W))]
+                 for g in range(groups)]
+        n_ab = min(num_ab, total_steps - step)
+        for i in range(n_ab):
+            scale = lr_rebound_scale(i, lr_reb)
+            for g in range(groups):
+                acts = [_f64(batch(g, step))]
+                for l in range(len(W)):
+                    acts.append(lr_linear_fwd(acts[-1], A[g][l], B[g][l])[0])
+                dY = _f64(loss_grad(acts[-1], g, step))
+                for l in reversed(range(len(W))):
+                    out = group_train_step(acts[l], dY, A[g][l], B[g][l], targets[g], state[g][l], i + 1, lr,
+                                           lr_scale=scale, **hyper)
+                    dY = out["dX"]
+                    A[g][l], B[g][l], state[g][l] = out["A"], out["B"], out["state"]
+            step += 1
+        for l in range(len(W)):
+            # A <- allReduce(A / worldSize), B <- allReduce(B / worldSize), W <- A B
+            W[l] = merged_matrix([A[g][l] for g in range(groups)], [B[g][l] for g in range(groups)], mode=0)
+        history.append((step, ranks, [w.copy() for w in W]))
+        for i in range(min(reb, total_steps - step)):
+            full_rank_step(W, "rebound", i, lr_rebound_scale(i, lr_reb))
+            step += 1
+    return W, history
+
+
 # --------------------------------------------------------------------------------------
 # convolutional layer carried as factors (Sec. "Methodology": a weight with more than two
 # dimensions is flattened over its trailing dimensions to give the matrix W of Eq. 3)

@@ -20,6 +20,7 @@ import torch
 
 from oracle import ab_oracle as orc
 from paper_2405_01067_amd import binding as abt
+from paper_2405_01067_amd import driver as drv
 from paper_2405_01067_amd import inputs as gen
 
 pytestmark = pytest.mark.gpu
@@ -114,3 +115,125 @@ def test_low_rank_phase_two_groups():
     W_start = A0h @ B0h
     assert rel(host(Wn) - W_start, Wo - W_start) < 1e-2
     assert rel(Wo, W_start) > 1e-4
+
+
+# ------------------------------------------------------------------ the whole of Algorithm 1
+
+def planted(rng, m, n, gap):
+    sigma = gen.power_law_spectrum(min(m, n), gap_at=gap)
+    Lf, Rf, _, _ = gen.planted_factor_pair(rng, m, n, sigma)
+    return (Lf @ Rf).astype(np.float32), float(math.sqrt(sigma[gap - 1] * sigma[gap]) / sigma[0])
+
+
+class ToyModel:
+    """What Algorithm 1 leaves to the model, written once for both sides: per-group batches, the
+    gradient of a least-squares loss at the last layer, and a stand-in for full-rank training (a
+    small seeded drift of the dense weights, scaled by the learning-rate factor of the rebound).
+    The two sides get the same numbers in their own precision."""
+
+    def __init__(self, rng, groups, M, n0, m_last, layers):
+        self.X = [gen.gaussian(rng, (M, n0)) for _ in range(groups)]
+        self.Yt = [gen.gaussian(rng, (M, m_last)) for _ in range(groups)]
+        self.drift = {(ph, i, l): gen.gaussian(rng, shape, std=2e-3)
+                      for ph, cnt in (("warmup", 40), ("rebound", 4)) for i in range(cnt) for l, shape in enumerate(layers)}
+        self.Xd = [dev(x) for x in self.X]
+        self.Ytd = [dev(y) for y in self.Yt]
+        self.driftd = {k: dev(v) for k, v in self.drift.items()}
+
+    # GPU side (torch tensors)
+    def batch_gpu(self, g, step): return self.Xd[g]
+    def loss_grad_gpu(self, Y, g, step): return Y - self.Ytd[g]
+    def full_rank_gpu(self, W, phase, i, scale):
+        for l, w in enumerate(W):
+            w.add_(self.driftd[(phase, i, l)], alpha=scale)
+
+    # oracle side (fp64 arrays)
+    def batch_cpu(self, g, step): return self.X[g]
+    def loss_grad_cpu(self, Y, g, step): return Y - self.Yt[g].astype(np.float64)
+    def full_rank_cpu(self, W, phase, i, scale):
+        for l in range(len(W)):
+            W[l] += scale * self.drift[(phase, i, l)].astype(np.float64)
+
+
+def test_algorithm1_driver_against_the_oracle_composition():
+    """120 steps of Algorithm 1 on a chain of two layers with four groups (two train A, two train B):
+    warm-up, then cycles of decomposition, group training under the learning-rate rebound,
+    synchronisation with W <- A B and full-rank rebound.  The driver (library calls only) and the
+    oracle's composition each decompose their own weights; after every synchronisation the ranks
+    must be equal and the dense weights agree, and what the low-rank phases changed must agree too.
+    The learning rate is small against gradient / curvature: Adam's first steps after every reset of
+    its state move each element by the full rate in the direction of the gradient's sign, a map
+    that magnifies differences between two runs once the rate times the curvature exceeds the
+    gradients (at lr = 2e-3 the fp32 and fp64 runs drift apart eightfold per cycle, at 1e-4 they
+    stay within the sum of the per-cycle tolerances)."""
+    rng = np.random.default_rng(77)
+    shapes = [(96, 64), (64, 96)]                     # W_0 [96, 64], W_1 [64, 96]
+    gaps = [16, 12]
+    W0, taus = zip(*(planted(rng, m, n, gap) for (m, n), gap in zip(shapes, gaps)))
+    tau = max(taus)                                   # one cut-off for the model: both gaps lie below it
+    for w, gap in zip(W0, gaps):
+        assert orc.ab_decomposition(w.astype(np.float64), tau=tau)[3] == gap
+    G, M, total, lr = 4, 160, 120, 1e-4
+    model = ToyModel(rng, G, M, shapes[0][1], shapes[-1][0], shapes)
+
+    Wd = [dev(w) for w in W0]
+    d = drv.ABDriver(Wd, groups=G, tau=tau, lr=lr, batch=model.batch_gpu, loss_grad=model.loss_grad_gpu,
+                     full_rank_step=model.full_rank_gpu, **HYPER)
+    snaps = []
+    d.on_synchronize = lambda dr: snaps.append((dr.step, list(dr.ranks), [host(w) for w in dr.W]))
+    sched = d.run(total)
+    torch.cuda.synchronize()
+    assert (sched.warmup_steps, sched.ab_steps, sched.rebound_steps, sched.lr_rebound_steps) == orc.ab_schedule(total) == (24, 4, 1, 2)
+    assert d.step == total
+
+    Wo, history = orc.ab_training_run([w.astype(np.float64) for w in W0], G, tau, lr, model.batch_cpu, model.loss_grad_cpu,
+                                      model.full_rank_cpu, total, **HYPER)
+    assert len(snaps) == len(history) == (total - 24 + 4) // 5
+    # Every cycle is a sequence of fp32-path operations, each within 1e-4 of the oracle's, and starts
+    # from weights that already differ by what the cycles before left: the bound grows by 1e-4 per cycle.
+    errs = []
+    for c, ((s_gpu, k_gpu, W_gpu), (s_cpu, k_cpu, W_cpu)) in enumerate(zip(snaps, history)):
+        assert s_gpu == s_cpu and k_gpu == k_cpu, (s_gpu, s_cpu, k_gpu, k_cpu)
+        errs.append(max(rel(W_gpu[l], W_cpu[l]) for l in range(len(shapes))))
+        assert errs[-1] < 1e-4 * (c + 1), (c, s_gpu, errs)
+    print("driver vs oracle after each synchronisation:", ["%.1e" % e for e in errs])
+    for l in range(len(shapes)):
+        assert rel(host(d.W[l]), Wo[l]) < 1e-4 * (len(history) + 1)
+        # the run changed the weights by far more than the two sides differ, and the change agrees
+        start = W0[l].astype(np.float64)
+        assert rel(Wo[l], start) > 1e-2
+        assert rel(host(d.W[l]) - start, Wo[l] - start) < 1e-2
+    # the phases were walked in Algorithm 1's order
+    kinds = [k for k, _, _ in d.log]
+    assert kinds[:5] == ["warmup", "decompose", "group", "synchronize", "rebound"]
+    assert kinds.count("group") == len(history)
+
+
+def test_algorithm1_driver_bf16_path_runs_and_keeps_padding_inert():
+    """Ranks are padded to a multiple of 32 with the zero columns the decomposition leaves; after
+    group training the padding must still be zero, in the fp32 and in the bf16 compute path, and the
+    bf16 path's merged weight must be finite and close to the fp32 path's (bf16 tolerance)."""
+    rng = np.random.default_rng(78)
+    shapes = [(128, 64), (64, 128)]
+    W0, taus = zip(*(planted(rng, m, n, 20) for m, n in shapes))
+    tau = max(taus)
+    G, M = 2, 256
+    model = ToyModel(rng, G, M, shapes[0][1], shapes[-1][0], shapes)
+    results = {}
+    for dtype in (torch.float32, torch.bfloat16):
+        Wd = [dev(w) for w in W0]
+        d = drv.ABDriver(Wd, groups=G, tau=tau, lr=1e-3, dtype=dtype,
+                         batch=lambda g, s: model.Xd[g].to(dtype), loss_grad=lambda Y, g, s: (Y.float() - model.Ytd[g]).to(dtype),
+                         **HYPER)
+        assert d.decompose() == [20, 20]
+        assert d.widths == [32, 32]
+        d.group_phase(3, 2)
+        for l in range(2):
+            for g in range(G):
+                assert not d.A[l][g][:, 20:].any() and not d.B[l][g][20:, :].any()
+        d.synchronize()
+        torch.cuda.synchronize()
+        results[dtype] = [host(w) for w in d.W]
+    for l in range(2):
+        assert np.isfinite(results[torch.bfloat16][l]).all()
+        assert rel(results[torch.bfloat16][l], results[torch.float32][l]) < 1e-2

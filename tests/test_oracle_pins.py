@@ -511,3 +511,64 @@ def test_conv_bwd_matches_central_finite_differences():
             hi[which][idx] += eps; lo[which][idx] -= eps
             fd = (loss(*hi) - loss(*lo)) / (2 * eps)
             assert fd == pytest.approx(grad[idx], rel=1e-6, abs=1e-8)
+
+
+# ------------------------------------------------------------------ Algorithm 1 as a whole
+
+def test_schedule_fractions_and_the_driver_agree():
+    """The oracle's phase lengths (floating-point fractions of Sec. "Hyperparameter considerations")
+    and the driver's integer arithmetic give the same whole steps for every run length."""
+    from paper_2405_01067_amd import driver as drv
+    assert orc.ab_schedule(3000) == (600, 100, 25, 50)        # 20 %, 3.33 %, a quarter, a half
+    for n in range(1, 3001):
+        s = drv.schedule(n)
+        assert (s.warmup_steps, s.ab_steps, s.rebound_steps, s.lr_rebound_steps) == orc.ab_schedule(n), n
+    assert [drv.group_target(g, 4) for g in range(4)] == ["A", "A", "B", "B"]
+    assert [drv.group_target(g, 3) for g in range(3)] == ["A", "A", "B"]
+
+
+def test_training_run_with_zero_learning_rate_is_eckart_young_truncation():
+    """With a learning rate of zero the group phase leaves the factors alone, so one cycle of
+    Algorithm 1 must map W to its best rank-k approximation (k from the cut-off rule), whatever the
+    number of groups, and a cut-off of zero must give W back."""
+    rng = np.random.default_rng(5)
+    W = [rng.standard_normal((12, 9)), rng.standard_normal((7, 12))]
+    X = rng.standard_normal((20, 9))
+    calls = []
+    def full_rank(Wl, phase, i, scale):
+        calls.append((phase, i, scale))
+    for groups in (1, 3):
+        calls.clear()
+        out, hist = orc.ab_training_run(W, groups, 0.3, 0.0, lambda g, s: X, lambda Y, g, s: Y, full_rank, 7)
+        # 7 steps: warm-up 1, then decomposition, 1 group step, synchronisation, 1 rebound step, ...
+        assert orc.ab_schedule(7) == (1, 1, 1, 1)
+        assert [c[0] for c in calls] == ["warmup", "rebound", "rebound", "rebound"]
+        assert len(hist) == 3 and hist[0][0] == 2
+        for l, w in enumerate(W):
+            u, s, vt = np.linalg.svd(w)
+            k = int(np.sum(s >= 0.3 * s[0]))
+            assert hist[0][1][l] == k
+            best = (u[:, :k] * s[:k]) @ vt[:k]
+            assert np.allclose(out[l], best, atol=1e-12)
+    out, _ = orc.ab_training_run(W, 2, 0.0, 0.0, lambda g, s: X, lambda Y, g, s: Y, full_rank, 4)
+    for l in range(2):
+        assert np.allclose(out[l], W[l], atol=1e-12)
+
+
+def test_training_run_one_group_one_step_is_one_adamw_step_on_A():
+    """One group (it trains A), one layer, a single group step: the synchronised weight is
+    (A - step) B with the AdamW step of the oracle's own optimiser on the gradient dY^T T."""
+    rng = np.random.default_rng(6)
+    W = rng.standard_normal((8, 6))
+    X = rng.standard_normal((15, 6))
+    Yt = rng.standard_normal((15, 8))
+    hyper = dict(beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+    # 4 steps: warm-up 1, then one cycle of 1 group step + 1 rebound step, then another group step
+    out, hist = orc.ab_training_run([W], 1, 0.0, 1e-2, lambda g, s: X, lambda Y, g, s: Y - Yt,
+                                    lambda Wl, ph, i, sc: None, 3, **hyper)
+    A, B, _, k = orc.ab_decomposition(W, tau=0.0)
+    T = X @ B.T
+    dA = (T @ A.T - Yt).T @ T
+    # first AdamW step: bias-corrected moments give g / (|g| + eps) elementwise
+    A1 = A - 1e-2 * (dA / (np.abs(dA) + 1e-8) + 0.01 * A)
+    assert np.allclose(hist[0][2][0], A1 @ B, atol=1e-10)
