@@ -49,6 +49,11 @@ def main():
                     help="profiling aid: run nothing but --steps forward launches of this config-3 case "
                          "(e.g. fc1_r384; config2 for the batch-64 layer) after --warmup, so that a kernel trace of the command holds "
                          "exactly that launch; prints its HIP-event timing")
+    ap.add_argument("--only-step", metavar="CASE", default=None,
+                    help="profiling aid: like --only-launch, but whole steps (forward + backward) of the case")
+    ap.add_argument("--only-merge", action="store_true",
+                    help="profiling aid: run nothing but the merge of the ViT-B/16 layer set (warm-up merges, "
+                         "then --merge-iters timed ones)")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="also run one plain 256 MiB device copy: the reference dispatch that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command")
@@ -192,103 +197,114 @@ def main():
         cpu["cases"].append(name)
 
     # ------------------------------------------------------------------ profiling aid: one launch only
-    if args.only_launch:
-        case = [cs for cs in gen.config3_cases() if cs[0] == args.only_launch]
-        if args.only_launch == "config2":
-            c = gen.config2()
-            name, M, m, n, r = "config2", c["M"], c["m"], c["n"], c["r"]
-        elif case:
-            name, M, m, n, r, seed = case[0]
-            c = gen.lr_case(M, m, n, r, seed)
-        else:
-            print(f"bench.py: no config-3 case named {args.only_launch} (or config2)", file=sys.stderr)
-            sys.exit(2)
-        st = Step(c, sets_for(2.0 * (2 * M * n + 2 * M * m + M * r)))
-        avg, med, mn = event_ms(st.fwd, iters=args.steps, warmup=args.warmup)
-        print(json.dumps({"only_launch": name, "avg_ms": avg, "median_ms": med, "min_ms": mn,
-                          "launches": args.warmup + max(3, args.steps // 10) * 10}))
-        return
-
-    # ------------------------------------------------------------------ headline: config 3
-    steps3 = []
-    for name, M, m, n, r, seed in gen.config3_cases():
-        c = gen.lr_case(M, m, n, r, seed)
-        st = Step(c, sets_for(2.0 * (2 * M * n + 2 * M * m + M * r)))
-        steps3.append((name, st))
-        if not args.no_cpu:
-            cpu_oracle_step(name, c, st.flops)
-        del c
-        gc.collect()
-    note(f"config 3: {len(steps3)} cases resident, {torch.cuda.memory_allocated() / 2**30:.1f} GiB")
-    total_flops = sum(st.flops for _, st in steps3)
-
-    def whole_step(i):
-        for _, st in steps3:
-            st.run(i)
-
-    for i in range(args.warmup):
-        whole_step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        whole_step(args.warmup + i)
-    torch.cuda.synchronize()
-    sec = (time.perf_counter() - t0) / args.steps
-    tflops = total_flops / sec / 1e12
-    note(f"config 3: {sec * 1e3:.3f} ms per step, {tflops:.1f} TFLOP/s")
-
-    cases = [case_report(name, st) for name, st in steps3]
-    summed_ms = sum(cs["ms"] for cs in cases)
-
-    # dominant kernel of a step: the fused chain kernel at R = 384 on the widest layer (fc1: the
-    # forward launch T = X B^T, Y = T A^T; the backward runs the same kernel for dT, dX).  The case
-    # is MFMA-bound (474 flop per algorithmic byte against a ridge of 312).
-    dom_name = "fc1_r384"
-    dom = dict(steps3)[dom_name]
-    dom_avg = event_ms(dom.fwd)[0]
-    dom_flops = 2.0 * dom.M * dom.r * (dom.m + dom.n)
-    achieved = dom_flops / (dom_avg * 1e-3) / 1e12
-    roofline = {
-        "kernel": "chain2_bf16_kernel<384, 1, false> (lr_linear_fwd of fc1 at r = 384, M = 50432: "
-                  "T = X B^T and Y = T A^T fused, one launch per call)",
-        "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-        "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
-        "algorithmic_flops_per_launch": dom_flops, "algorithmic_bytes_per_launch": dom.bytes_fwd,
-        "avg_launch_ms": round(dom_avg, 5),
-        "hbm_frac": round(dom.bytes_fwd / (dom_avg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-        "profile": "profiles/chain2_r384_cfg3_fc1_kernel_trace.txt",
-    }
-
-    out = {
-        "metric": METRIC, "value": round(tflops, 2), "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(sec * 1e3, 5), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[2]: all four ViT-B/16 linear shapes (qkv 2304x768, proj 768x768, "
-                               "fc1 3072x768, fc2 768x3072) factored at r in {96, 192, 384}, X 50432 rows "
-                               "(batch 256 x 197 tokens), bf16 in / fp32 accumulate, fwd+bwd of all twelve "
-                               "cases = one step",
-                   "cases": len(steps3), "flops_per_step": total_flops,
-                   "buffer_sets_per_case": "2 or more, alternated (rotated working set > 2 x 256 MB)"},
-        "pct_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
-        "config3_sum_of_case_medians_ms": round(summed_ms, 4),
-        "config3_tflops_from_case_medians": round(total_flops / summed_ms / 1e9, 1),
-        "roofline": roofline,
-        "cases": cases,
-    }
-    for _, st in steps3:
-        del st
-    del steps3, dom
-    gc.collect()
-    torch.cuda.empty_cache()
-
-    if args.pmc_copy:
+    def pmc_copy():
         src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
         dst.copy_(src)          # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
+
+    if args.only_launch or args.only_step:
+        which = args.only_launch or args.only_step
+        case = [cs for cs in gen.config3_cases() if cs[0] == which]
+        if which == "config2":
+            c = gen.config2()
+            name, M, m, n, r = "config2", c["M"], c["m"], c["n"], c["r"]
+        elif case:
+            name, M, m, n, r, seed = case[0]
+            c = gen.lr_case(M, m, n, r, seed)
+        else:
+            print(f"bench.py: no config-3 case named {which} (or config2)", file=sys.stderr)
+            sys.exit(2)
+        st = Step(c, sets_for(2.0 * (2 * M * n + 2 * M * m + M * r)))
+        avg, med, mn = event_ms(st.fwd if args.only_launch else st.run, iters=args.steps, warmup=args.warmup)
+        if args.pmc_copy:
+            pmc_copy()
+        print(json.dumps({"only_launch" if args.only_launch else "only_step": name, "avg_ms": avg, "median_ms": med,
+                          "min_ms": mn, "calls": args.warmup + max(3, args.steps // 10) * 10}))
+        return
+
+    if args.only_merge:
+        out = {"only_merge": True}
+        args.no_extra, args.no_cpu, args.no_merge = True, True, False
+        cases = []
+    if not args.only_merge:
+        # ------------------------------------------------------------------ headline: config 3
+        steps3 = []
+        for name, M, m, n, r, seed in gen.config3_cases():
+            c = gen.lr_case(M, m, n, r, seed)
+            st = Step(c, sets_for(2.0 * (2 * M * n + 2 * M * m + M * r)))
+            steps3.append((name, st))
+            if not args.no_cpu:
+                cpu_oracle_step(name, c, st.flops)
+            del c
+            gc.collect()
+        note(f"config 3: {len(steps3)} cases resident, {torch.cuda.memory_allocated() / 2**30:.1f} GiB")
+        total_flops = sum(st.flops for _, st in steps3)
+
+        def whole_step(i):
+            for _, st in steps3:
+                st.run(i)
+
+        for i in range(args.warmup):
+            whole_step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            whole_step(args.warmup + i)
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / args.steps
+        tflops = total_flops / sec / 1e12
+        note(f"config 3: {sec * 1e3:.3f} ms per step, {tflops:.1f} TFLOP/s")
+
+        cases = [case_report(name, st) for name, st in steps3]
+        summed_ms = sum(cs["ms"] for cs in cases)
+
+        # dominant kernel of a step: the fused chain kernel at R = 384 on the widest layer (fc1: the
+        # forward launch T = X B^T, Y = T A^T; the backward runs the same kernel for dT, dX).  The case
+        # is MFMA-bound (474 flop per algorithmic byte against a ridge of 312).
+        dom_name = "fc1_r384"
+        dom = dict(steps3)[dom_name]
+        dom_avg = event_ms(dom.fwd)[0]
+        dom_flops = 2.0 * dom.M * dom.r * (dom.m + dom.n)
+        achieved = dom_flops / (dom_avg * 1e-3) / 1e12
+        roofline = {
+            "kernel": "chain2_bf16_kernel<384, 1, false> (lr_linear_fwd of fc1 at r = 384, M = 50432: "
+                      "T = X B^T and Y = T A^T fused, one launch per call)",
+            "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+            "algorithmic_flops_per_launch": dom_flops, "algorithmic_bytes_per_launch": dom.bytes_fwd,
+            "avg_launch_ms": round(dom_avg, 5),
+            "hbm_frac": round(dom.bytes_fwd / (dom_avg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+            "profile": "profiles/chain2_r384_cfg3_fc1_kernel_trace.txt",
+        }
+
+        out = {
+            "metric": METRIC, "value": round(tflops, 2), "unit": "TFLOP/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": round(sec * 1e3, 5), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "configs[2]: all four ViT-B/16 linear shapes (qkv 2304x768, proj 768x768, "
+                                   "fc1 3072x768, fc2 768x3072) factored at r in {96, 192, 384}, X 50432 rows "
+                                   "(batch 256 x 197 tokens), bf16 in / fp32 accumulate, fwd+bwd of all twelve "
+                                   "cases = one step",
+                       "cases": len(steps3), "flops_per_step": total_flops,
+                       "buffer_sets_per_case": "2 or more, alternated (rotated working set > 2 x 256 MB)"},
+            "pct_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+            "config3_sum_of_case_medians_ms": round(summed_ms, 4),
+            "config3_tflops_from_case_medians": round(total_flops / summed_ms / 1e9, 1),
+            "roofline": roofline,
+            "cases": cases,
+        }
+        for _, st in steps3:
+            del st
+        del steps3, dom
+        gc.collect()
+        torch.cuda.empty_cache()
+
+    if args.pmc_copy:
+        pmc_copy()
 
     # ------------------------------------------------------------------ config 2 (batch 64 fc1, r = 192)
     step2 = None
@@ -483,6 +499,7 @@ def main():
         gc.collect()
         torch.cuda.empty_cache()
 
+    if not args.no_merge and not args.only_merge:
         # -------------------------------------------------------------- ab_factorize: dense ViT-B/16 weights
         rng = np.random.default_rng(7)
         dense = []
