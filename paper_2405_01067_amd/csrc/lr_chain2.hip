@@ -151,7 +151,8 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
                                                          const uint16_t* __restrict__ Qm,
                                                          uint16_t* __restrict__ Yout,
                                                          uint16_t* __restrict__ Tout,
-                                                         int64_t M, int p, int q, int t_pitch, Ch2Gather gg) {
+                                                         int64_t M, int p, int q, int t_pitch, Ch2Gather gg,
+                                                         int full_blocks, int tail_parts) {
     extern __shared__ __align__(1024) unsigned char lds[];
     using C = Ch2<R>;
     using L = Ch2Cfg<R, RG>;
@@ -162,14 +163,25 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
     constexpr int D1 = L::D1, D2 = L::D2;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t row0 = (int64_t)blockIdx.x * ROWS;
+    // Work-groups [0, full_blocks) take one row block each and all of its output tiles; the row
+    // blocks after those are shared by tail_parts work-groups each, every one repeating stage 1 and
+    // doing its share of the stage-2 tiles (for a batch too small to fill the chip, and for the
+    // last, partly filled round of a large one).
+    int rb = (int)blockIdx.x, part = 0, nparts = 1;
+    if (rb >= full_blocks) {
+        const int t = rb - full_blocks;
+        rb = full_blocks + t / tail_parts;
+        part = t % tail_parts;
+        nparts = tail_parts;
+    }
+    const int64_t row0 = (int64_t)rb * ROWS;
     const int ns1 = p / BK1;
     const int n1p = (ns1 + D1 - 1) / D1 * D1;           // stage-1 trip count, padded to the loaders' ring
-    // stage-2 output tiles of 128 columns: work-group (x, y) of a grid with gridDim.y column parts
-    // does the tiles [tile0, tile0 + ntile) of the ntile_all; every part repeats stage 1 for its rows
+    // stage-2 output tiles of 128 columns: part `part` of `nparts` does the tiles
+    // [tile0, tile0 + ntile) of the ntile_all; every part repeats stage 1 for its rows
     const int ntile_all = (q + 127) / 128;
-    const int tile0 = (int)(blockIdx.y * (unsigned)ntile_all / gridDim.y);
-    const int ntile = (int)((blockIdx.y + 1) * (unsigned)ntile_all / gridDim.y) - tile0;
+    const int tile0 = (int)((unsigned)part * (unsigned)ntile_all / (unsigned)nparts);
+    const int ntile = (int)((unsigned)(part + 1) * (unsigned)ntile_all / (unsigned)nparts) - tile0;
     const int ns2 = ntile * KSL;
     const int n2p = (ns2 + L::U2 - 1) / L::U2 * L::U2;  // stage-2 trip count, padded likewise
     // per row group g: reduction scratch at g * red, T tile at RG * red + g * ttile (stage 1 and T phase);
@@ -179,8 +191,8 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
     // Work-groups walk the contraction slabs (stage 1) and the output tiles (stage 2) from
     // different starting points, so that at any instant they touch different columns of
     // Xin / Yout and different rows of the factors.
-    const int rot1 = (int)(blockIdx.x % (unsigned)ns1);
-    const int rot2 = (int)(blockIdx.x % (unsigned)ntile);
+    const int rot1 = (int)((unsigned)rb % (unsigned)ns1);
+    const int rot2 = (int)((unsigned)rb % (unsigned)ntile);
     auto slab1_of = [&](int s) { if (s > ns1 - 1) s = ns1 - 1; s += rot1; return s >= ns1 ? s - ns1 : s; };
     auto tile_of = [&](int t) { if (t > ntile - 1) t = ntile - 1; t += rot2; return tile0 + (t >= ntile ? t - ntile : t); };
 
@@ -340,7 +352,7 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
             if (i < L::n_mid_barriers) wg_barrier();
         }
         // T tile is in LDS: store it (the MFMA waves load their operands from it meanwhile)
-        if (Tout != nullptr && blockIdx.y == 0) {
+        if (Tout != nullptr && part == 0) {
             // rows of Tout are t_pitch elements apart (R for a plain T; more when the tile is a
             // column block of a wider matrix); the descriptor ends with the last valid row
             const rsrc_t tres = make_rsrc(Tout + row0 * t_pitch, ((rows_valid - 1) * t_pitch + R) * 2);
@@ -695,10 +707,30 @@ hipError_t launch_chain_r(const void* Xin, const void* P, const void* Q, void* Y
         if (e != hipSuccess) return e;
         attr_set.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((chain2_bf16_kernel<R, RG, GATHER>), dim3((unsigned)ceil_div(M, L::ROWS), (unsigned)parts),
-                       dim3(64 * (NMW_ * RG + NLW)), lds_bytes, s,
+    const int64_t nblocks = ceil_div(M, L::ROWS);
+    int64_t full = 0;
+    int tail_parts = parts;
+    if (parts == 1) {
+        // A large batch ends with a partly filled round of the 256 compute units.  When that round is
+        // at most half full and stage 2 is the larger part of a work-group's slabs, its row blocks are
+        // split over the idle units by output tiles.
+        full = nblocks;
+        const int64_t tail = nblocks % 256;
+        const int ntile = (q + 127) / 128;
+        if (Yout != nullptr && nblocks > 256 && tail > 0 && 2 * tail <= 256) {
+            int tp = (int)(256 / tail);
+            if (tp > ntile) tp = ntile;
+            const int ns1 = p / BK1, whole = ns1 + ntile * L::KSL, shared = ns1 + (ntile + tp - 1) / tp * L::KSL;
+            if (tp >= 2 && 10 * shared <= 7 * whole) {
+                full = nblocks - tail;
+                tail_parts = tp;
+            }
+        }
+    }
+    const int64_t grid = full + (nblocks - full) * tail_parts;
+    hipLaunchKernelGGL((chain2_bf16_kernel<R, RG, GATHER>), dim3((unsigned)grid), dim3(64 * (NMW_ * RG + NLW)), lds_bytes, s,
                        (const uint16_t*)Xin, (const uint16_t*)P, (const uint16_t*)Q,
-                       (uint16_t*)Yout, (uint16_t*)Tout, M, p, q, t_pitch, gg);
+                       (uint16_t*)Yout, (uint16_t*)Tout, M, p, q, t_pitch, gg, (int)full, tail_parts);
     return hipGetLastError();
 }
 

@@ -326,6 +326,18 @@ def test_bf16_tall_work_groups_with_column_parts(tall_chain, M, r, parts):
         abt.set_chain_parts(prev)
 
 
+@pytest.mark.parametrize("M", [64 * 259, 64 * 258 + 17])
+def test_bf16_last_round_shared_by_output_tiles(M):
+    # more than one round of 64-row work-groups and a last round of three row blocks: those are
+    # split four ways by output tiles (m = 512: four tiles) and repeat the single stage-1 slab
+    prev = abt.set_chain_rows(64)
+    try:
+        c = gen.lr_case(M=M, m=512, n=64, r=32, seed=7300 + M % 97)
+        check_full(c, torch.bfloat16, TOL_BF16)
+    finally:
+        abt.set_chain_rows(prev)
+
+
 def test_bf16_tall_work_groups_chosen_for_large_batches():
     # above one round of 64-row work-groups the library picks the 128-row kernel by itself; the
     # result must agree with the 64-row kernel's up to summation order, and with the oracle on samples
