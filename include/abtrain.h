@@ -322,7 +322,7 @@ int abt_set_chain_rows(int rows);
 int abt_set_chain_parts(int parts);
 
 /* Sweep cap of the Jacobi SVD (default 30, clamped to [1, 64]; sweeps stop as soon as every layer
- * has converged: 8-9 for the 384-wide cores of config 5, about 15 for dense 768-wide weights);
+ * has converged: 8 for 384-wide cores with a power-law spectrum, 11 to 15 for 768-wide ones);
  * returns the previous value. */
 int abt_set_jacobi_max_sweeps(int max_sweeps);
 

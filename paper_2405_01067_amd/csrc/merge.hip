@@ -10,8 +10,10 @@
 // The new factors of Eq. 3 are back-projections of the averaged ones, without any inverse:
 //     A' = U Sigma^(1/2) = Abar P_A,   P_A = G_B Y diag(sigma^(-5/2))
 //     B' = Sigma^(1/2) V^T = P_B Bbar, P_B = diag(sigma^(-3/2)) Y^T,      Y = L_A (C V_c)
-// (from U_c Sigma = C V_c, V_c Sigma = C^T U_c and L L^T = G).  Everything K x K runs in fp64;
-// the streaming ends (mean, back-projection) are fp32.
+// (from U_c Sigma = C V_c, V_c Sigma = C^T U_c and L L^T = G).  Everything K x K runs in fp64; the
+// back-projection is fp32.  This file: the plan of a batched call (workspace layout, tables, stage
+// order, layer groups on side streams), Cholesky, the K x K products and the finalisation; the
+// average fused into the Gram kernel is in merge_gram.hip, the block Jacobi in merge_jacobi.hip.
 //
 // mode 1 (mean of reconstructions) uses the same pipeline on the concatenations
 // Abar = [A_1 .. A_G] / G (m x Gk) and Bbar = [B_1; ..; B_G] (Gk x n).
