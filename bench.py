@@ -545,6 +545,35 @@ def main():
 
         ga_ms = event_ms(step_A)[1]
         gb_ms = event_ms(step_B)[1]
+        # four groups (two train A, two train B), each with its own buffers: group by group, and in the
+        # grouped calls (one forward launch, four backward launches for all groups)
+        G4 = 4
+        base = step2.sets[0]
+        gsets = [dict(X=base["X"].clone(), dY=base["dY"].clone(), A=step2.A.clone(), B=step2.B.clone(),
+                      Y=torch.empty_like(base["Y"]), T=torch.empty_like(base["T"]), dX=torch.empty_like(base["dX"]),
+                      dA=torch.empty_like(step2.dA), dB=torch.empty_like(step2.dB)) for _ in range(G4)]
+        gws = torch.empty(lib.lr_linear_bwd_grouped_workspace_bytes(G4, step2.M, step2.m, step2.n, step2.r, abt.ABT_BF16),
+                          dtype=torch.uint8, device=dev)
+
+        def groups_one_by_one(i):
+            for g, b in enumerate(gsets):
+                abt.lr_linear_fwd(b["X"], b["A"], b["B"], save_T=True, Y=b["Y"], T=b["T"], workspace=step2.ws)
+                if g < G4 // 2:
+                    abt.lr_linear_bwd(b["dY"], b["X"], b["T"], b["A"], b["B"], dX=b["dX"], dA=b["dA"], need_dB=False, workspace=step2.ws)
+                else:
+                    abt.lr_linear_bwd(b["dY"], b["X"], b["T"], b["A"], b["B"], dX=b["dX"], dB=b["dB"], need_dA=False, workspace=step2.ws)
+
+        fwd_groups = [dict(X=b["X"], A=b["A"], B=b["B"], Y=b["Y"], T=b["T"]) for b in gsets]
+        bwd_groups = [dict(dY=b["dY"], X=b["X"], T=b["T"], A=b["A"], B=b["B"], dX=b["dX"],
+                           dA=b["dA"] if g < G4 // 2 else None, dB=None if g < G4 // 2 else b["dB"]) for g, b in enumerate(gsets)]
+
+        def groups_grouped(i):
+            abt.lr_linear_fwd_grouped(fwd_groups)
+            abt.lr_linear_bwd_grouped(bwd_groups, workspace=gws)
+
+        g1_ms = event_ms(groups_one_by_one, batch=4)[1]
+        gg_ms = event_ms(groups_grouped, batch=4)[1]
+        del gsets, gws, fwd_groups, bwd_groups
         tensors, elems = [], 0
         for blk in range(gen.VIT_B16_BLOCKS):
             for li, (name, m, n) in enumerate(gen.VIT_B16_LINEARS):
@@ -573,6 +602,8 @@ def main():
                              "A_group_ms": round(ga_ms, 4), "B_group_ms": round(gb_ms, 4),
                              "A_group_tflops": round(flops56 / (ga_ms * 1e-3) / 1e12, 1),
                              "B_group_tflops": round(flops56 / (gb_ms * 1e-3) / 1e12, 1),
+                             "four_groups_one_by_one_ms": round(g1_ms, 4), "four_groups_grouped_calls_ms": round(gg_ms, 4),
+                             "four_groups_grouped_tflops": round(4 * flops56 / (gg_ms * 1e-3) / 1e12, 1),
                              "adamw_ms": round(ad_ms, 4), "adamw_elements": elems,
                              "adamw_GBps": round(ad_bytes / (ad_ms * 1e-3) / 1e9, 1),
                              "adamw_hbm_frac": round(ad_bytes / (ad_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),

@@ -16,7 +16,7 @@
  *   - Unless a parameter is documented as a HOST pointer it is a DEVICE pointer owned by the
  *     caller; the library never allocates, frees or retains caller memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  lr_linear_fwd,
- *     lr_linear_bwd, lr_linear_bwd_static, lr_conv_fwd, lr_conv_bwd, ab_adamw_step and ab_reconstruct enqueue work on it
+ *     lr_linear_bwd, lr_linear_bwd_static, lr_linear_fwd_grouped, lr_linear_bwd_grouped, lr_conv_fwd, lr_conv_bwd, ab_adamw_step and ab_reconstruct enqueue work on it
  *     and return without synchronising the host.  Calls that DO block the host:
  *       ab_merge, ab_merge_batched, ab_factorize, ab_factorize_batched: once after uploading
  *         their layer tables, and from the third Jacobi sweep on once per sweep, for the copy of
@@ -124,6 +124,44 @@ int lr_linear_bwd_static(const void* dY, const void* X, const void* T, const voi
                          void* dX, float* dA, float* dB,
                          int64_t M, int64_t m, int64_t n, int64_t r, int dt, int accumulate,
                          void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * The factored layer for G emulated groups at once (Algorithm 1, group training: every group
+ * holds its own copy of A and B, sees its own batch and trains A or B; Sec. "Methodology").
+ * All groups share the shapes M, m, n, r and the type; `groups` is a HOST array of G <= 8 entries
+ * of device pointers with the meaning they have in lr_linear_fwd / lr_linear_bwd:
+ *   forward : X, A, B, Y required, T_save optional (all groups or none).
+ *   backward: dY, X, A, B required; T optional (NULL = recomputed); dX, dA, dB optional per group
+ *             (a group that trains A passes dB = NULL and the other way round).
+ * ABT_BF16: the forward is one launch for all groups; the backward is one launch each for the
+ * transposes, the dT/dX chain (two if only some groups ask for dX), the factor gradients of all
+ * groups and their split reduction.  ABT_F32: the single-group path, group by group.
+ * Results per group are those of the single-group calls up to the summation order of dA / dB
+ * (the row split depends on the number of tiles in the launch); two grouped calls on the same
+ * inputs give bit-identical results.  Workspace: lr_linear_bwd_grouped_workspace_bytes for the
+ * backward, lr_linear_fwd_workspace_bytes * G laid end to end for the ABT_F32 forward without T_save.
+ * ------------------------------------------------------------------------------------- */
+typedef struct abt_lr_group {
+    const void* X;      /* [M, n] */
+    const void* A;      /* [m, r] */
+    const void* B;      /* [r, n] */
+    void* Y;            /* forward out [M, m] */
+    void* T_save;       /* forward out [M, r], optional */
+    const void* dY;     /* backward in [M, m] */
+    const void* T;      /* backward in [M, r], optional */
+    void* dX;           /* backward out [M, n], optional */
+    float* dA;          /* backward out [m, r] fp32, optional */
+    float* dB;          /* backward out [r, n] fp32, optional */
+} abt_lr_group;
+#define ABT_MAX_GROUPS 8
+
+int lr_linear_fwd_grouped(const abt_lr_group* groups, int G,
+                          int64_t M, int64_t m, int64_t n, int64_t r, int dt,
+                          void* workspace, size_t workspace_bytes, void* stream);
+int lr_linear_bwd_grouped(const abt_lr_group* groups, int G,
+                          int64_t M, int64_t m, int64_t n, int64_t r, int dt, int accumulate,
+                          void* workspace, size_t workspace_bytes, void* stream);
+size_t lr_linear_bwd_grouped_workspace_bytes(int G, int64_t M, int64_t m, int64_t n, int64_t r, int dt);
 
 /* ---------------------------------------------------------------------------------------
  * Merge of G group copies of one layer's factors (Algorithm 1: A <- allReduce(A/worldSize),

@@ -21,6 +21,7 @@ EXPORTS = (
     "ab_merge_stage_ms", "abt_set_chain_rows", "abt_set_chain_parts",
     "lr_linear_fwd", "lr_linear_fwd_workspace_bytes",
     "lr_linear_bwd", "lr_linear_bwd_workspace_bytes", "lr_linear_bwd_static",
+    "lr_linear_fwd_grouped", "lr_linear_bwd_grouped", "lr_linear_bwd_grouped_workspace_bytes",
     "ab_merge", "ab_merge_workspace_bytes",
     "ab_merge_batched", "ab_merge_batched_workspace_bytes", "ab_merge_info",
     "ab_factorize", "ab_factorize_workspace_bytes",
@@ -49,6 +50,14 @@ class ConvGeom(ctypes.Structure):
 class AdamwTensor(ctypes.Structure):
     _fields_ = [("param", ctypes.c_void_p), ("grad", ctypes.c_void_p), ("exp_avg", ctypes.c_void_p),
                 ("exp_avg_sq", ctypes.c_void_p), ("param_bf16", ctypes.c_void_p), ("count", ctypes.c_int64)]
+
+
+class LrGroup(ctypes.Structure):
+    """abt_lr_group"""
+    _fields_ = [(name, ctypes.c_void_p) for name in ("X", "A", "B", "Y", "T_save", "dY", "T", "dX", "dA", "dB")]
+
+
+MAX_GROUPS = 8   # ABT_MAX_GROUPS
 
 
 class MergeDesc(ctypes.Structure):
@@ -101,6 +110,12 @@ def load():
     lib.lr_linear_bwd.restype = ci
     lib.lr_linear_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, vp, sz, vp]
     lib.lr_linear_bwd_workspace_bytes.restype = sz
+    lib.lr_linear_fwd_grouped.restype = ci
+    lib.lr_linear_fwd_grouped.argtypes = [ctypes.POINTER(LrGroup), ci, i64, i64, i64, i64, ci, vp, sz, vp]
+    lib.lr_linear_bwd_grouped.restype = ci
+    lib.lr_linear_bwd_grouped.argtypes = [ctypes.POINTER(LrGroup), ci, i64, i64, i64, i64, ci, ci, vp, sz, vp]
+    lib.lr_linear_bwd_grouped_workspace_bytes.restype = sz
+    lib.lr_linear_bwd_grouped_workspace_bytes.argtypes = [ci, i64, i64, i64, i64, ci]
     lib.lr_linear_bwd_static.restype = ci
     lib.lr_linear_bwd_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, vp]
     lib.lr_linear_bwd_workspace_bytes.argtypes = [i64, i64, i64, i64, ci]
@@ -285,6 +300,91 @@ def lr_linear_bwd(dY, X, T, A, B, need_dX: bool = True, need_dA: bool = True, ne
                              _ptr(dB if need_dB else None), M, m, n, r, dt, int(bool(accumulate)),
                              _ptr(ws), ws.numel(), _stream()), "lr_linear_bwd")
     return (dX if need_dX else None), (dA if need_dA else None), (dB if need_dB else None)
+
+
+def _group_shapes(groups, keys):
+    torch = _torch()
+    if not 1 <= len(groups) <= MAX_GROUPS:
+        raise AbtError(f"between 1 and {MAX_GROUPS} groups per call")
+    X0, A0 = groups[0]["X"], groups[0]["A"]
+    M, n = X0.shape
+    m, r = A0.shape
+    shapes = {"X": (M, n), "A": (m, r), "B": (r, n), "Y": (M, m), "T": (M, r), "dY": (M, m), "dX": (M, n)}
+    for g in groups:
+        for k in keys:
+            t = g.get(k)
+            if t is None:
+                continue
+            _dev_tensor(t, k)
+            if tuple(t.shape) != shapes[k] or t.dtype != X0.dtype:
+                raise AbtError(f"{k} of every group must be {shapes[k]} of {X0.dtype}")
+    return M, m, n, r, _dt(X0)
+
+
+def lr_linear_fwd_grouped(groups: List[dict], save_T: bool = True):
+    """lr_linear_fwd for up to 8 groups of one shape in one call.  Each dict: X, A, B (GPU tensors of one
+    dtype) and optionally preallocated Y, T.  Returns a list of (Y, T)."""
+    torch = _torch()
+    lib = load()
+    M, m, n, r, dt = _group_shapes(groups, ("X", "A", "B", "Y", "T"))
+    G = len(groups)
+    table = (LrGroup * G)()
+    outs = []
+    for i, g in enumerate(groups):
+        X = g["X"]
+        Y = g.get("Y")
+        if Y is None:
+            Y = torch.empty((M, m), dtype=X.dtype, device=X.device)
+        T = g.get("T") if save_T else None
+        if save_T and T is None:
+            T = torch.empty((M, r), dtype=X.dtype, device=X.device)
+        e = table[i]
+        e.X, e.A, e.B, e.Y, e.T_save = _ptr(X), _ptr(g["A"]), _ptr(g["B"]), _ptr(Y), _ptr(T)
+        outs.append((Y, T))
+    each = lib.lr_linear_fwd_workspace_bytes(M, m, n, r, dt) if not save_T else 0
+    ws = _workspace(each * G, groups[0]["X"].device, None)
+    _check(lib.lr_linear_fwd_grouped(table, G, M, m, n, r, dt, _ptr(ws), ws.numel(), _stream()), "lr_linear_fwd_grouped")
+    return outs
+
+
+def lr_linear_bwd_grouped(groups: List[dict], accumulate: bool = False, workspace=None):
+    """lr_linear_bwd for up to 8 groups of one shape in one call.  Each dict: dY, X, A, B, optionally T,
+    and the outputs wanted, preallocated or True to have them allocated: dX, dA, dB (absent, None or
+    False = skipped).  Returns a list of (dX, dA, dB)."""
+    torch = _torch()
+    lib = load()
+    M, m, n, r, dt = _group_shapes(groups, ("X", "A", "B", "dY", "T"))
+    G = len(groups)
+    table = (LrGroup * G)()
+    outs = []
+    dev = groups[0]["X"].device
+    for i, g in enumerate(groups):
+        def want(key, shape, dtype):
+            v = g.get(key)
+            if v is None or v is False:
+                return None
+            if v is True:
+                if accumulate and key != "dX":
+                    raise AbtError(f"accumulate needs an existing {key}")
+                return torch.empty(shape, dtype=dtype, device=dev)
+            _dev_tensor(v, key)
+            if tuple(v.shape) != shape or v.dtype != dtype:
+                raise AbtError(f"{key} must be {shape} of {dtype}")
+            return v
+        dX = want("dX", (M, n), g["X"].dtype)
+        dA = want("dA", (m, r), torch.float32)
+        dB = want("dB", (r, n), torch.float32)
+        e = table[i]
+        e.X, e.A, e.B, e.dY, e.T = _ptr(g["X"]), _ptr(g["A"]), _ptr(g["B"]), _ptr(g["dY"]), _ptr(g.get("T"))
+        e.dX, e.dA, e.dB = _ptr(dX), _ptr(dA), _ptr(dB)
+        outs.append((dX, dA, dB))
+    nbytes = lib.lr_linear_bwd_grouped_workspace_bytes(G, M, m, n, r, dt)
+    if nbytes == 0:
+        raise AbtError("lr_linear_bwd_grouped: unsupported shape")
+    ws = _workspace(nbytes, dev, workspace)
+    _check(lib.lr_linear_bwd_grouped(table, G, M, m, n, r, dt, int(bool(accumulate)), _ptr(ws), ws.numel(), _stream()),
+           "lr_linear_bwd_grouped")
+    return outs
 
 
 STATIC_SCRATCH_BYTES = 64 << 20   # ABT_STATIC_SCRATCH_BYTES of the header

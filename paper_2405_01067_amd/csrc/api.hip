@@ -464,6 +464,169 @@ int lr_linear_bwd(const void* dY, const void* X, const void* T, const void* A, c
     return ABT_OK;
 }
 
+// ------------------------------------------------------------------ G emulated groups per launch
+namespace {
+struct GroupedLayout { size_t At, Bt, dT, T, per_group, partials, total; };
+
+GroupedLayout grouped_layout_bf16(int G, int64_t M, int64_t m, int64_t n, int64_t r) {
+    GroupedLayout w{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    w.At = take((size_t)r * m * 2);
+    w.Bt = take((size_t)n * r * 2);
+    w.dT = take((size_t)M * r * 2);
+    w.T = take((size_t)M * r * 2);
+    w.per_group = off;
+    w.partials = (size_t)G * w.per_group;
+    // Partials of any subset of the 2 G jobs: elements x splits with splits <= max(1, 256 / tiles) and
+    // elements <= tiles x 128 x r, hence at most max(all elements, 256 x 128 x r) floats.
+    const size_t all = (size_t)G * (size_t)(m + n) * r, cap = (size_t)256 * 128 * r;
+    w.total = w.partials + align_up((all > cap ? all : cap) * sizeof(float), 256);
+    return w;
+}
+
+int chain_rows_for_groups(int G, int64_t M, int p, int q, int R) {
+    const int forced = g_chain_rows.load();
+    if (forced == 64 || !chain2_tall_supports(R, p, q)) return 64;
+    if (forced == 128 || !chain2_supports(R, p, q)) return 128;
+    const double cost64 = (double)ceil_div(G * ceil_div(M, 64), 256);
+    const double cost128 = 1.58 * (double)ceil_div(G * ceil_div(M, 128), 256);
+    return cost128 < cost64 ? 128 : 64;
+}
+
+// one launch for the problems with a second stage and one for those without
+hipError_t chain_grouped(const ChainProblem* pr, int G, int64_t M, int p, int q, int R, hipStream_t s) {
+    if (!chain2_supports(R, p, q) && !chain2_tall_supports(R, p, q)) {
+        for (int g = 0; g < G; ++g) {
+            if (!pr[g].Yout && !pr[g].Tout) continue;
+            const hipError_t e = chain(pr[g].Xin, pr[g].P, pr[g].Q, pr[g].Yout, pr[g].Tout, M, p, q, R, s);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    for (int second = 1; second >= 0; --second) {
+        ChainProblem sel[kChainMaxGroups];
+        int n = 0;
+        for (int g = 0; g < G; ++g) {
+            const bool has2 = pr[g].Yout != nullptr;
+            if ((has2 && second) || (!has2 && !second && pr[g].Tout)) sel[n++] = pr[g];
+        }
+        if (n == 0) continue;
+        const hipError_t e = launch_chain2_grouped_bf16(sel, n, M, p, q, R, chain_rows_for_groups(n, M, p, q, R), 1, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+}  // namespace
+
+size_t lr_linear_bwd_grouped_workspace_bytes(int G, int64_t M, int64_t m, int64_t n, int64_t r, int dt) {
+    if (G < 1 || G > ABT_MAX_GROUPS || check_lr_shapes(M, m, n, r, dt) != ABT_OK) return 0;
+    if (dt == ABT_F32) return (size_t)G * lr_linear_bwd_workspace_bytes(M, m, n, r, dt);
+    return grouped_layout_bf16(G, M, m, n, r).total;
+}
+
+int lr_linear_fwd_grouped(const abt_lr_group* groups, int G,
+                          int64_t M, int64_t m, int64_t n, int64_t r, int dt,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+    const int st = check_lr_shapes(M, m, n, r, dt);
+    if (st != ABT_OK) return st;
+    if (!groups || G < 1 || G > ABT_MAX_GROUPS) return ABT_EINVAL;
+    for (int g = 0; g < G; ++g) {
+        const abt_lr_group& q = groups[g];
+        if (!q.X || !q.A || !q.B || !q.Y || ((q.T_save != nullptr) != (groups[0].T_save != nullptr))) return ABT_EINVAL;
+        if (!aligned(q.X, 16) || !aligned(q.A, 16) || !aligned(q.B, 16) || !aligned(q.Y, 16) || !aligned(q.T_save, 16))
+            return ABT_EALIGN;
+    }
+    if (dt == ABT_F32) {
+        const size_t each = lr_linear_fwd_workspace_bytes(M, m, n, r, dt);
+        if (!groups[0].T_save && (!workspace || workspace_bytes < each * G)) return ABT_EWORKSPACE;
+        for (int g = 0; g < G; ++g) {
+            const int e = lr_linear_fwd(groups[g].X, groups[g].A, groups[g].B, groups[g].Y, groups[g].T_save, M, m, n, r, dt,
+                                        workspace ? (char*)workspace + each * g : nullptr, each, stream);
+            if (e != ABT_OK) return e;
+        }
+        return ABT_OK;
+    }
+    ChainProblem pr[kChainMaxGroups];
+    for (int g = 0; g < G; ++g) pr[g] = ChainProblem{groups[g].X, groups[g].B, groups[g].A, groups[g].Y, groups[g].T_save};
+    return chain_grouped(pr, G, M, (int)n, (int)m, (int)r, (hipStream_t)stream) == hipSuccess ? ABT_OK : ABT_EHIP;
+}
+
+int lr_linear_bwd_grouped(const abt_lr_group* groups, int G,
+                          int64_t M, int64_t m, int64_t n, int64_t r, int dt, int accumulate,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+    const int st = check_lr_shapes(M, m, n, r, dt);
+    if (st != ABT_OK) return st;
+    if (!groups || G < 1 || G > ABT_MAX_GROUPS) return ABT_EINVAL;
+    for (int g = 0; g < G; ++g) {
+        const abt_lr_group& q = groups[g];
+        if (!q.dY || !q.X || !q.A || !q.B) return ABT_EINVAL;
+        if (!aligned(q.dY, 16) || !aligned(q.X, 16) || !aligned(q.T, 16) || !aligned(q.A, 16) || !aligned(q.B, 16) ||
+            !aligned(q.dX, 16) || !aligned(q.dA, 16) || !aligned(q.dB, 16))
+            return ABT_EALIGN;
+    }
+    if (!workspace || workspace_bytes < lr_linear_bwd_grouped_workspace_bytes(G, M, m, n, r, dt)) return ABT_EWORKSPACE;
+    if (!aligned(workspace, 256)) return ABT_EALIGN;
+    char* ws = (char*)workspace;
+    if (dt == ABT_F32) {
+        const size_t each = lr_linear_bwd_workspace_bytes(M, m, n, r, dt);
+        for (int g = 0; g < G; ++g) {
+            const abt_lr_group& q = groups[g];
+            const int e = lr_linear_bwd(q.dY, q.X, q.T, q.A, q.B, q.dX, q.dA, q.dB, M, m, n, r, dt, accumulate,
+                                        ws + each * g, each, stream);
+            if (e != ABT_OK) return e;
+        }
+        return ABT_OK;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const GroupedLayout w = grouped_layout_bf16(G, M, m, n, r);
+    auto at = [&](int g, size_t off) { return ws + (size_t)g * w.per_group + off; };
+    // T = X B^T again for the groups that did not keep it and need it for dA
+    ChainProblem pr[kChainMaxGroups];
+    const void* Tp[kChainMaxGroups];
+    bool any = false;
+    for (int g = 0; g < G; ++g) {
+        const abt_lr_group& q = groups[g];
+        Tp[g] = q.T;
+        pr[g] = ChainProblem{};
+        if (!q.T && q.dA) {
+            pr[g] = ChainProblem{q.X, q.B, nullptr, nullptr, at(g, w.T)};
+            Tp[g] = at(g, w.T);
+            any = true;
+        }
+    }
+    if (any && chain_grouped(pr, G, M, (int)n, (int)m, (int)r, s) != hipSuccess) return ABT_EHIP;
+    // dT = dY (A^T)^T, dX = dT (B^T)^T: the forward chain on the transposed factors of every group
+    TransposeJob tj[kTransposeMaxJobs];
+    int ntj = 0;
+    any = false;
+    for (int g = 0; g < G; ++g) {
+        const abt_lr_group& q = groups[g];
+        pr[g] = ChainProblem{};
+        if (!q.dX && !q.dB) continue;
+        tj[ntj++] = TransposeJob{q.A, at(g, w.At), (int)m, (int)r};
+        if (q.dX) tj[ntj++] = TransposeJob{q.B, at(g, w.Bt), (int)r, (int)n};
+        pr[g] = ChainProblem{q.dY, at(g, w.At), q.dX ? at(g, w.Bt) : nullptr, q.dX, at(g, w.dT)};
+        any = true;
+    }
+    if (any) {
+        if (launch_transpose_bf16(tj, ntj, s) != hipSuccess) return ABT_EHIP;
+        if (chain_grouped(pr, G, M, (int)m, (int)n, (int)r, s) != hipSuccess) return ABT_EHIP;
+    }
+    // factor gradients of all groups in one launch (and one split reduction)
+    TnJob jobs[kTnMaxJobs];
+    int nj = 0;
+    for (int g = 0; g < G; ++g) {
+        const abt_lr_group& q = groups[g];
+        if (q.dA) jobs[nj++] = TnJob{q.dY, Tp[g], q.dA, (int)m, 0};
+        if (q.dB) jobs[nj++] = TnJob{q.X, at(g, w.dT), q.dB, (int)n, 1};
+    }
+    if (nj && tn_partials_bytes(M, jobs, nj, (int)r) > w.total - w.partials) return ABT_EWORKSPACE;   // cannot happen: see the layout
+    if (nj && launch_tn_bf16(jobs, nj, M, (int)r, accumulate ? 1 : 0, (float*)(ws + w.partials), s) != hipSuccess)
+        return ABT_EHIP;
+    return ABT_OK;
+}
+
 // ------------------------------------------------------------------ backward without allocation
 // The scratch of lr_linear_bwd_static: one array per GPU, held from the moment the library's code is
 // loaded on that GPU until the process ends.  In host code the name below is only a handle; the

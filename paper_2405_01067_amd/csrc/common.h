@@ -81,6 +81,13 @@ hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, voi
 bool chain2_tall_supports(int R, int p, int q);
 hipError_t launch_chain2_tall_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                               int64_t M, int p, int q, int R, int parts, hipStream_t s);
+// Up to kChainMaxGroups problems of one shape in one launch (the emulated groups of a training step).
+// rows = 64 or 128 (work-group height; the caller has checked chain2_supports / chain2_tall_supports);
+// Yout must be NULL for all problems or for none; a problem with Yout == Tout == NULL is skipped.
+constexpr int kChainMaxGroups = 8;
+struct ChainProblem { const void* Xin; const void* P; const void* Q; void* Yout; void* Tout; };
+hipError_t launch_chain2_grouped_bf16(const ChainProblem* problems, int G, int64_t M, int p, int q, int R,
+                                      int rows, int parts, hipStream_t s);
 // The same chain with the first operand gathered from a channels-last image [M / (H W), H, W, Cin]
 // instead of read from a matrix: row i of the virtual operand is the kh x kw patch around pixel i
 // (zero outside the image), columns ordered (tap, channel) with every tap padded to a multiple of
@@ -94,6 +101,7 @@ hipError_t launch_chain2_tall_gather_bf16(const void* image, const PatchGeom& g,
                                      void* Yout, void* Tout, int t_pitch, int64_t M, int q, int R, hipStream_t s);
 // dst[c, r] = src[r, c] for a bf16 matrix of `rows` x `cols`.
 struct TransposeJob { const void* src; void* dst; int rows, cols; };   // dst[cols, rows] = src[rows, cols]^T
+constexpr int kTransposeMaxJobs = 16;   // per launch
 hipError_t launch_transpose_bf16(const TransposeJob* jobs, int njobs, hipStream_t s);
 // part[split][P,Q] = U[rows of split, P]^T . V[rows of split, Q]  (bf16 in, fp32 partials)
 // followed by out[P,Q] (+)= sum over splits, in fixed order.  One of P, Q equals R.
@@ -101,6 +109,7 @@ hipError_t launch_transpose_bf16(const TransposeJob* jobs, int njobs, hipStream_
 struct TnJob {
     const void* U; const void* V; float* out; int P; int transposed;
 };
+constexpr int kTnMaxJobs = 16;   // per launch (all with the same M and R)
 size_t tn_partials_bytes(int64_t M, const TnJob* jobs, int njobs, int R);
 hipError_t launch_tn_bf16(const TnJob* jobs, int njobs, int64_t M, int R, int accumulate,
                           float* partials, hipStream_t s);

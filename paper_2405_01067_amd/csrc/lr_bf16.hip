@@ -220,14 +220,16 @@ hipError_t launch_chain_r(const void* Xin, const void* P, const void* Q, void* Y
 // bf16 transpose (for A^T and B^T, which turn dT = dY A and dX = dT B into the same
 // "rows times rows" shape the chain kernel consumes).
 // =====================================================================================
-// One launch serves up to two matrices (rows and cols multiples of 8).  A work-group moves one
+// One launch serves up to kTransposeMaxJobs matrices (rows and cols multiples of 8).  A work-group moves one
 // 64 x 64 tile: 16-byte loads of row pieces into LDS, 16-byte stores of column pieces out of it.
 struct TrJob { const uint16_t* src; uint16_t* dst; int rows, cols, tiles_x, tile_begin; };
-struct TrArgs { TrJob job[2]; int njobs; };
+struct TrArgs { TrJob job[kTransposeMaxJobs]; int njobs; };
 
 __global__ __launch_bounds__(256) void transpose_bf16_kernel(TrArgs args) {
     __shared__ uint16_t tile[64][72];                  // pitch 144 B: 16-byte aligned rows
-    const int jid = (args.njobs > 1 && (int)blockIdx.x >= args.job[1].tile_begin) ? 1 : 0;
+    int jid = 0;
+    for (int i = 1; i < args.njobs; ++i)
+        if ((int)blockIdx.x >= args.job[i].tile_begin) jid = i;
     const TrJob j = args.job[jid];
     const int t = (int)blockIdx.x - j.tile_begin;
     const int r0 = (t / j.tiles_x) * 64, c0 = (t % j.tiles_x) * 64;
@@ -310,7 +312,7 @@ hipError_t launch_chain_bf16(const void* Xin, const void* P, const void* Q, void
 }
 
 hipError_t launch_transpose_bf16(const TransposeJob* jobs, int njobs, hipStream_t s) {
-    if (njobs < 1 || njobs > 2) return hipErrorInvalidValue;
+    if (njobs < 1 || njobs > kTransposeMaxJobs) return hipErrorInvalidValue;
     TrArgs args{};
     args.njobs = njobs;
     int tiles = 0;

@@ -145,15 +145,27 @@ struct Ch2Cfg {
 // channel block: 128 contiguous bytes per row, as in the plain case.  p = kh kw cpb 64.
 struct Ch2Gather { int H, W, Cin, cpb, kh, kw, sign; };
 
+// Operands of up to kChainMaxGroups problems of one shape (the emulated groups of a training step:
+// same M, p, q, R, each with its own activations and its own copy of the factors); blockIdx.y picks one.
+struct Ch2Ptrs {
+    const uint16_t* X[kChainMaxGroups];
+    const uint16_t* P[kChainMaxGroups];
+    const uint16_t* Q[kChainMaxGroups];
+    uint16_t* Y[kChainMaxGroups];
+    uint16_t* T[kChainMaxGroups];
+};
+
 template <int R, int RG, bool GATHER>
-__global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(const uint16_t* __restrict__ Xin,
-                                                         const uint16_t* __restrict__ Pm,
-                                                         const uint16_t* __restrict__ Qm,
-                                                         uint16_t* __restrict__ Yout,
-                                                         uint16_t* __restrict__ Tout,
+__global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(Ch2Ptrs ptrs,
                                                          int64_t M, int p, int q, int t_pitch, Ch2Gather gg,
                                                          int full_blocks, int tail_parts) {
     extern __shared__ __align__(1024) unsigned char lds[];
+    const uint16_t* __restrict__ const Xin = ptrs.X[blockIdx.y];
+    const uint16_t* __restrict__ const Pm = ptrs.P[blockIdx.y];
+    const uint16_t* __restrict__ const Qm = ptrs.Q[blockIdx.y];
+    uint16_t* __restrict__ const Yout = ptrs.Y[blockIdx.y];
+    uint16_t* __restrict__ const Tout = ptrs.T[blockIdx.y];
+    if (Yout == nullptr && Tout == nullptr) return;      // nothing asked of this group
     using C = Ch2<R>;
     using L = Ch2Cfg<R, RG>;
     constexpr int ROWS = L::ROWS, NMW = NMW_ * RG, NMT = 64 * NMW;
@@ -691,13 +703,14 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(con
 #undef ABT_LOADER_WAVE
 
 template <int R, int RG, bool GATHER>
-hipError_t launch_chain_r(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
+hipError_t launch_chain_r(const Ch2Ptrs& ptrs, int G, bool second_stage,
                           int64_t M, int p, int q, int t_pitch, const Ch2Gather& gg, int parts, hipStream_t s) {
     using L = Ch2Cfg<R, RG>;
     constexpr int lds_bytes = L::lds_bytes;
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
     // column parts: each does its share of the 128-column output tiles (and repeats stage 1)
-    if (parts < 1 || parts > 64 || (Yout != nullptr && parts > (q + 127) / 128) || (Yout == nullptr && parts != 1))
+    if (G < 1 || G > kChainMaxGroups || parts < 1 || parts > 64 || (second_stage && parts > (q + 127) / 128) ||
+        (!second_stage && parts != 1))
         return hipErrorInvalidValue;
     // (setting the attribute twice from two host threads is harmless; the flag only saves the call)
     static std::atomic<bool> attr_set{false};
@@ -713,11 +726,11 @@ hipError_t launch_chain_r(const void* Xin, const void* P, const void* Q, void* Y
     if (parts == 1) {
         // A large batch ends with a partly filled round of the 256 compute units.  When that round is
         // at most half full and stage 2 is the larger part of a work-group's slabs, its row blocks are
-        // split over the idle units by output tiles.
+        // split over the idle units by output tiles (one problem per launch only).
         full = nblocks;
         const int64_t tail = nblocks % 256;
         const int ntile = (q + 127) / 128;
-        if (Yout != nullptr && nblocks > 256 && tail > 0 && 2 * tail <= 256) {
+        if (G == 1 && second_stage && nblocks > 256 && tail > 0 && 2 * tail <= 256) {
             int tp = (int)(256 / tail);
             if (tp > ntile) tp = ntile;
             const int ns1 = p / BK1, whole = ns1 + ntile * L::KSL, shared = ns1 + (ntile + tp - 1) / tp * L::KSL;
@@ -728,17 +741,16 @@ hipError_t launch_chain_r(const void* Xin, const void* P, const void* Q, void* Y
         }
     }
     const int64_t grid = full + (nblocks - full) * tail_parts;
-    hipLaunchKernelGGL((chain2_bf16_kernel<R, RG, GATHER>), dim3((unsigned)grid), dim3(64 * (NMW_ * RG + NLW)), lds_bytes, s,
-                       (const uint16_t*)Xin, (const uint16_t*)P, (const uint16_t*)Q,
-                       (uint16_t*)Yout, (uint16_t*)Tout, M, p, q, t_pitch, gg, (int)full, tail_parts);
+    hipLaunchKernelGGL((chain2_bf16_kernel<R, RG, GATHER>), dim3((unsigned)grid, (unsigned)G), dim3(64 * (NMW_ * RG + NLW)),
+                       lds_bytes, s, ptrs, M, p, q, t_pitch, gg, (int)full, tail_parts);
     return hipGetLastError();
 }
 
 template <bool GATHER>
-hipError_t launch_chain_64(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
+hipError_t launch_chain_64(const Ch2Ptrs& ptrs, int G, bool second_stage,
                            int64_t M, int p, int q, int R, int t_pitch, const Ch2Gather& gg, hipStream_t s) {
     switch (R) {
-#define ABT_CASE(RR) case RR: return launch_chain_r<RR, 1, GATHER>(Xin, P, Q, Yout, Tout, M, p, q, t_pitch, gg, 1, s);
+#define ABT_CASE(RR) case RR: return launch_chain_r<RR, 1, GATHER>(ptrs, G, second_stage, M, p, q, t_pitch, gg, 1, s);
         ABT_CASE(32) ABT_CASE(64) ABT_CASE(96) ABT_CASE(128) ABT_CASE(160) ABT_CASE(192)
         ABT_CASE(256) ABT_CASE(320) ABT_CASE(384)
 #undef ABT_CASE
@@ -747,14 +759,21 @@ hipError_t launch_chain_64(const void* Xin, const void* P, const void* Q, void* 
 }
 
 template <bool GATHER>
-hipError_t launch_chain_128(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
+hipError_t launch_chain_128(const Ch2Ptrs& ptrs, int G, bool second_stage,
                             int64_t M, int p, int q, int R, int t_pitch, const Ch2Gather& gg, int parts, hipStream_t s) {
     switch (R) {
-#define ABT_CASE(RR) case RR: return launch_chain_r<RR, 2, GATHER>(Xin, P, Q, Yout, Tout, M, p, q, t_pitch, gg, parts, s);
+#define ABT_CASE(RR) case RR: return launch_chain_r<RR, 2, GATHER>(ptrs, G, second_stage, M, p, q, t_pitch, gg, parts, s);
         ABT_CASE(32) ABT_CASE(64) ABT_CASE(96) ABT_CASE(128) ABT_CASE(192)
 #undef ABT_CASE
         default: return hipErrorInvalidValue;
     }
+}
+
+Ch2Ptrs one_problem(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout) {
+    Ch2Ptrs t{};
+    t.X[0] = (const uint16_t*)Xin; t.P[0] = (const uint16_t*)P; t.Q[0] = (const uint16_t*)Q;
+    t.Y[0] = (uint16_t*)Yout; t.T[0] = (uint16_t*)Tout;
+    return t;
 }
 
 // checks shared by the two gathered launchers; rows = work-group height
@@ -787,12 +806,12 @@ bool chain2_tall_supports(int R, int p, int q) {
 
 hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                               int64_t M, int p, int q, int R, hipStream_t s) {
-    return launch_chain_64<false>(Xin, P, Q, Yout, Tout, M, p, q, R, R, Ch2Gather{}, s);
+    return launch_chain_64<false>(one_problem(Xin, P, Q, Yout, Tout), 1, Yout != nullptr, M, p, q, R, R, Ch2Gather{}, s);
 }
 
 hipError_t launch_chain2_tall_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                               int64_t M, int p, int q, int R, int parts, hipStream_t s) {
-    return launch_chain_128<false>(Xin, P, Q, Yout, Tout, M, p, q, R, R, Ch2Gather{}, parts, s);
+    return launch_chain_128<false>(one_problem(Xin, P, Q, Yout, Tout), 1, Yout != nullptr, M, p, q, R, R, Ch2Gather{}, parts, s);
 }
 
 hipError_t launch_chain2_gather_bf16(const void* image, const PatchGeom& g, const void* P, const void* Q,
@@ -801,7 +820,7 @@ hipError_t launch_chain2_gather_bf16(const void* image, const PatchGeom& g, cons
     const int64_t p = (int64_t)g.kh * g.kw * cpb * 64;
     if (!gather_ok(g, M, p, t_pitch, R, 64) || !chain2_supports(R, (int)p, q)) return hipErrorInvalidValue;
     const Ch2Gather gg{g.H, g.W, g.Cin, cpb, g.kh, g.kw, g.sign};
-    return launch_chain_64<true>(image, P, Q, Yout, Tout, M, (int)p, q, R, t_pitch, gg, s);
+    return launch_chain_64<true>(one_problem(image, P, Q, Yout, Tout), 1, Yout != nullptr, M, (int)p, q, R, t_pitch, gg, s);
 }
 
 hipError_t launch_chain2_tall_gather_bf16(const void* image, const PatchGeom& g, const void* P, const void* Q,
@@ -810,7 +829,21 @@ hipError_t launch_chain2_tall_gather_bf16(const void* image, const PatchGeom& g,
     const int64_t p = (int64_t)g.kh * g.kw * cpb * 64;
     if (!gather_ok(g, M, p, t_pitch, R, 128) || !chain2_tall_supports(R, (int)p, q)) return hipErrorInvalidValue;
     const Ch2Gather gg{g.H, g.W, g.Cin, cpb, g.kh, g.kw, g.sign};
-    return launch_chain_128<true>(image, P, Q, Yout, Tout, M, (int)p, q, R, t_pitch, gg, 1, s);
+    return launch_chain_128<true>(one_problem(image, P, Q, Yout, Tout), 1, Yout != nullptr, M, (int)p, q, R, t_pitch, gg, 1, s);
+}
+
+hipError_t launch_chain2_grouped_bf16(const ChainProblem* problems, int G, int64_t M, int p, int q, int R,
+                                      int rows, int parts, hipStream_t s) {
+    if (G < 1 || G > kChainMaxGroups || !problems) return hipErrorInvalidValue;
+    Ch2Ptrs t{};
+    const bool second_stage = problems[0].Yout != nullptr;
+    for (int g = 0; g < G; ++g) {
+        if ((problems[g].Yout != nullptr) != second_stage) return hipErrorInvalidValue;   // one launch shape for all
+        t.X[g] = (const uint16_t*)problems[g].Xin; t.P[g] = (const uint16_t*)problems[g].P;
+        t.Q[g] = (const uint16_t*)problems[g].Q; t.Y[g] = (uint16_t*)problems[g].Yout; t.T[g] = (uint16_t*)problems[g].Tout;
+    }
+    if (rows == 128) return launch_chain_128<false>(t, G, second_stage, M, p, q, R, R, Ch2Gather{}, parts, s);
+    return launch_chain_64<false>(t, G, second_stage, M, p, q, R, R, Ch2Gather{}, s);
 }
 
 }  // namespace abt

@@ -54,7 +54,7 @@ struct Tn2Job { const uint16_t* U; const uint16_t* V; float* part; int P; int ti
 // tap C + c of row i of the virtual U is channel c of pixel (y + ky - kh/2, x + kx - kw/2) of the
 // same image (tap = ky kw + kx), zero outside it.  job.P = kh kw C.
 struct Tn2Gather { int H, W, C, kh, kw; };
-struct Tn2Args { Tn2Job job[2]; int njobs; int tiles; int splits; int64_t M; int64_t rows_per_split; Tn2Gather g; };
+struct Tn2Args { Tn2Job job[kTnMaxJobs]; int njobs; int tiles; int splits; int64_t M; int64_t rows_per_split; Tn2Gather g; };
 
 // LDS slab: column-major, 64 batch rows = 128 bytes per column, two columns per 256-byte line.  The
 // sixteen 16-byte units of a line are XOR-swizzled with bits of the column-pair index p so that
@@ -251,7 +251,9 @@ __global__ __launch_bounds__(Tn2<R>::NT) void tn2_bf16_kernel(Tn2Args args) {
     const int pair = xcd * ((int)gridDim.x >> 3) + slot;
     if (pair >= args.tiles * args.splits) return;
     const int tile = pair % args.tiles, split = pair / args.tiles;
-    const int jid = (args.njobs > 1 && tile >= args.job[1].tile_begin) ? 1 : 0;
+    int jid = 0;                                         // the job whose tile range holds this tile
+    for (int i = 1; i < args.njobs; ++i)
+        if (tile >= args.job[i].tile_begin) jid = i;
     const Tn2Job job = args.job[jid];
     const int p0 = (tile - job.tile_begin) * TP;
     const int64_t k_begin = (int64_t)split * args.rows_per_split;
@@ -346,13 +348,15 @@ __global__ __launch_bounds__(Tn2<R>::NT) void tn2_bf16_kernel(Tn2Args args) {
 }
 
 // out (+)= sum over splits of part[split], element-wise (part already has the layout of out).
-struct Red2Job { const float* part; float* out; int64_t total; };
-struct Red2Args { Red2Job job[2]; int njobs; int splits; int accumulate; int blocks0; };
+struct Red2Job { const float* part; float* out; int64_t total; int block_begin; };
+struct Red2Args { Red2Job job[kTnMaxJobs]; int njobs; int splits; int accumulate; };
 
 __global__ __launch_bounds__(256) void tn2_reduce_kernel(Red2Args a) {
-    const int jid = (a.njobs > 1 && (int)blockIdx.x >= a.blocks0) ? 1 : 0;
+    int jid = 0;
+    for (int i = 1; i < a.njobs; ++i)
+        if ((int)blockIdx.x >= a.job[i].block_begin) jid = i;
     const Red2Job j = a.job[jid];
-    const int64_t idx = ((int64_t)((int)blockIdx.x - (jid ? a.blocks0 : 0)) * 256 + threadIdx.x) * 4;
+    const int64_t idx = ((int64_t)((int)blockIdx.x - j.block_begin) * 256 + threadIdx.x) * 4;
     if (idx >= j.total) return;   // totals are multiples of 4 (R % 32 == 0)
     f32x4 sum = *reinterpret_cast<const f32x4*>(j.part + idx);
     for (int s = 1; s < a.splits; ++s) sum += *reinterpret_cast<const f32x4*>(j.part + (int64_t)s * j.total + idx);
@@ -405,7 +409,7 @@ namespace {
 // gather != NULL: the LAST job's U is gathered from an image, any job before it is plain
 hipError_t launch_tn_common(const TnJob* jobs, int njobs, int64_t M, int R, int accumulate,
                             float* partials, const Tn2Gather* gather, hipStream_t s) {
-    if (njobs < 1 || njobs > 2) return hipErrorInvalidValue;
+    if (njobs < 1 || njobs > kTnMaxJobs || (gather && njobs > 2)) return hipErrorInvalidValue;
     const int tiles = tn2_total_tiles(jobs, njobs);
     const int splits = tn2_choose_splits(M, tiles);
     Tn2Args args{};
@@ -432,9 +436,8 @@ hipError_t launch_tn_common(const TnJob* jobs, int njobs, int64_t M, int R, int 
         red.job[i].out = jobs[i].out;
         red.job[i].total = (int64_t)jobs[i].P * R;
         tile_begin += (jobs[i].P + TP - 1) / TP;
-        const int blocks = (int)ceil_div((int64_t)jobs[i].P * R / 4, 256);
-        if (i == 0) red.blocks0 = blocks;
-        red_blocks += blocks;
+        red.job[i].block_begin = red_blocks;
+        red_blocks += (int)ceil_div((int64_t)jobs[i].P * R / 4, 256);
         part += (size_t)jobs[i].P * R * splits;
     }
     hipError_t e;

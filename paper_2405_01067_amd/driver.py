@@ -5,8 +5,8 @@ This module holds control flow, the step schedule and pointer marshalling only; 
 operation of the method runs in the library's kernels:
 
     abDecomposition of every W with the cut-off rule          ab_factorize_batched
-    group training (the A groups train A, the B groups B,     lr_linear_fwd, lr_linear_bwd (the frozen
-      the other factor frozen), learning-rate rebound           factor's gradient skipped), ab_adamw_step
+    group training (the A groups train A, the B groups B,     lr_linear_fwd_grouped, lr_linear_bwd_grouped (the
+      the other factor frozen), learning-rate rebound           frozen factor's gradient skipped), ab_adamw_step
                                                                 over the trained factors of all groups
                                                                 and layers in one launch, ab_lr_rebound_scale
     A <- allReduce(A / worldSize), B likewise, W <- A B       ab_merge_batched over all layers (mean of the
@@ -18,9 +18,9 @@ and rebound phases (a callback that receives the dense weights, the step number 
 and the learning-rate factor of the rebound).  The layers form a chain without activations:
 the output of layer l is the input of layer l + 1.
 
-Groups are emulated as G copies of the factors in one GPU's memory; the groups of a step are
-issued one after the other on the caller's stream (each launch already fills the GPU at training
-sizes) and share one optimiser launch.
+Groups are emulated as G copies of the factors in one GPU's memory (at most eight per call of the
+grouped entry points); a step issues, per layer, one grouped forward and one grouped backward for
+all groups (lr_linear_fwd_grouped, lr_linear_bwd_grouped) and one optimiser launch for everything.
 """
 from dataclasses import dataclass
 from typing import Callable, List, Optional, Sequence
@@ -70,8 +70,8 @@ class ABDriver:
                  dtype=None, k_cap: Optional[int] = None, beta1: float = 0.9, beta2: float = 0.999,
                  eps: float = 1e-8, weight_decay: float = 0.01):
         torch = abt._torch()
-        if groups < 1:
-            raise abt.AbtError("need at least one group")
+        if not 1 <= groups <= abt.MAX_GROUPS:
+            raise abt.AbtError(f"between 1 and {abt.MAX_GROUPS} groups")
         self.torch = torch
         self.W = list(weights)
         for l, w in enumerate(self.W):
@@ -157,22 +157,22 @@ class ABDriver:
                     entry["param_bf16"] = (Ac if group_target(g, G) == "A" else Bc)[l][g]
                 table.append(entry)
         plan = abt.AdamwPlan(table)
+        targets = [group_target(g, G) for g in range(G)]
         for i in range(steps):
-            for g in range(G):
-                target = group_target(g, G)
-                X = self.batch(g, self.step)
-                acts, Ts = [X], []
-                for l in range(L):
-                    Y, T = abt.lr_linear_fwd(acts[-1], Ac[l][g], Bc[l][g], save_T=True)
-                    acts.append(Y)
-                    Ts.append(T)
-                dY = self.loss_grad(acts[-1], g, self.step)
-                for l in reversed(range(L)):
-                    dX, _, _ = abt.lr_linear_bwd(dY, acts[l], Ts[l], Ac[l][g], Bc[l][g],
-                                                 need_dX=(l > 0), need_dA=(target == "A"), need_dB=(target == "B"),
-                                                 dA=grads[g][l] if target == "A" else None,
-                                                 dB=grads[g][l] if target == "B" else None)
-                    dY = dX
+            # forward of every layer for all groups in one grouped call, then the backward likewise
+            acts = [[self.batch(g, self.step) for g in range(G)]]
+            Ts = []
+            for l in range(L):
+                outs = abt.lr_linear_fwd_grouped([dict(X=acts[l][g], A=Ac[l][g], B=Bc[l][g]) for g in range(G)])
+                acts.append([y for y, _ in outs])
+                Ts.append([t for _, t in outs])
+            dY = [self.loss_grad(acts[L][g], g, self.step) for g in range(G)]
+            for l in reversed(range(L)):
+                outs = abt.lr_linear_bwd_grouped(
+                    [dict(dY=dY[g], X=acts[l][g], T=Ts[l][g], A=Ac[l][g], B=Bc[l][g], dX=(l > 0),
+                          dA=grads[g][l] if targets[g] == "A" else None,
+                          dB=grads[g][l] if targets[g] == "B" else None) for g in range(G)])
+                dY = [o[0] for o in outs]
             # one optimiser launch for the trained factors of all groups and layers
             abt.ab_adamw_step(plan, step=i + 1, lr=self.lr, lr_scale=abt.lr_rebound_scale(i, lr_rebound_steps),
                               **self.hyper)

@@ -238,3 +238,79 @@ def test_reconstruct(m, n, k):
     W = abt.ab_reconstruct(dev(A), dev(B))
     torch.cuda.synchronize()
     assert rel(host(W), orc.reconstruct(A, B)) < 1e-4
+
+
+# ------------------------------------------------------------------ G groups per launch
+
+@pytest.mark.parametrize("dtype,shape", [(torch.bfloat16, (700, 256, 192, 64)), (torch.bfloat16, (1500, 320, 128, 192)),
+                                          (torch.float32, (150, 70, 50, 12))],
+                         ids=["bf16-r64", "bf16-r192", "fp32"])
+def test_grouped_step_matches_the_oracle_and_the_single_group_calls(dtype, shape):
+    """Four groups of one shape, each with its own batch and its own factors, two training A and two
+    training B (one of the B groups without dX, one A group without a saved T): one grouped forward
+    and one grouped backward against the oracle, element by element, and against the single-group
+    calls (same kernels; the factor gradients may differ in summation order only)."""
+    M, m, n, r = shape
+    bf = dtype == torch.bfloat16
+    tol = 1e-2 if bf else 1e-4
+    G = 4
+    cases = [gen.lr_case(M=M, m=m, n=n, r=r, seed=500 + g, bf16=bf, dy_std=1e-2 if bf else 1.0) for g in range(G)]
+    groups = [dict(X=dev(c["X"], dtype), A=dev(c["A"], dtype), B=dev(c["B"], dtype), dY=dev(c["dY"], dtype)) for c in cases]
+    fwd = abt.lr_linear_fwd_grouped(groups)
+    for g, (Y, T) in enumerate(fwd):
+        groups[g]["T"] = T
+    plan = [dict(dX=True, dA=True), dict(dX=True, dA=True, T=None), dict(dX=True, dB=True), dict(dB=True)]
+    for g in range(G):
+        groups[g].update(plan[g])
+    bwd = abt.lr_linear_bwd_grouped(groups)
+    again = abt.lr_linear_bwd_grouped(groups)
+    torch.cuda.synchronize()
+    for g, c in enumerate(cases):
+        Yo, To = orc.lr_linear_fwd(c["X"], c["A"], c["B"])
+        dXo, dAo, dBo, _ = orc.lr_linear_bwd(c["dY"], c["X"], c["A"], c["B"])
+        Y, T = fwd[g]
+        dX, dA, dB = bwd[g]
+        assert rel(host(Y), Yo) < tol and rel(host(T), To) < tol
+        assert (dX is None) == ("dX" not in plan[g]) and (dA is None) == ("dA" not in plan[g]) and (dB is None) == ("dB" not in plan[g])
+        Y1, T1 = abt.lr_linear_fwd(groups[g]["X"], groups[g]["A"], groups[g]["B"], save_T=True)
+        assert rel(host(Y), host(Y1)) < (2e-3 if bf else 1e-6)
+        s_dX, s_dA, s_dB = abt.lr_linear_bwd(groups[g]["dY"], groups[g]["X"], T1, groups[g]["A"], groups[g]["B"],
+                                             need_dX=dX is not None, need_dA=dA is not None, need_dB=dB is not None)
+        for got, ref, single, name in ((dX, dXo, s_dX, "dX"), (dA, dAo, s_dA, "dA"), (dB, dBo, s_dB, "dB")):
+            if got is None:
+                continue
+            assert rel(host(got), ref) < tol, (g, name, rel(host(got), ref))
+            assert rel(host(got), host(single)) < (2e-3 if bf else 1e-5), (g, name)
+        for a, b in zip(bwd[g], again[g]):
+            assert (a is None and b is None) or torch.equal(a, b)      # fixed split and summation order
+
+
+def test_grouped_backward_accumulates_and_fills_the_chip_shape():
+    """config-2 shape, four groups: accumulate adds into the gradients; the 128-row kernel is the
+    one chosen for 4 x 197 row blocks."""
+    c = gen.lr_case(M=12608, m=3072, n=768, r=192, seed=77)
+    bf = torch.bfloat16
+    base = dict(X=dev(c["X"], bf), A=dev(c["A"], bf), B=dev(c["B"], bf), dY=dev(c["dY"], bf))
+    groups = [dict(base) for _ in range(4)]
+    for g, (Y, T) in enumerate(abt.lr_linear_fwd_grouped(groups)):
+        groups[g]["T"] = T
+    for g in range(4):
+        groups[g].update(dict(dX=True, dA=True) if g < 2 else dict(dX=True, dB=True))
+    outs = abt.lr_linear_bwd_grouped(groups)
+    torch.cuda.synchronize()
+    dXo, dAo, dBo, _ = orc.lr_linear_bwd(c["dY"], c["X"], c["A"], c["B"])
+    for g, (dX, dA, dB) in enumerate(outs):
+        assert rel(host(dX), dXo) < 1e-2
+        assert rel(host(dA if g < 2 else dB), dAo if g < 2 else dBo) < 1e-2
+    # the groups hold the same inputs here, so they must agree bit for bit among themselves
+    assert torch.equal(outs[0][0], outs[3][0]) and torch.equal(outs[0][1], outs[1][1]) and torch.equal(outs[2][2], outs[3][2])
+    acc = [dict(g) for g in groups]
+    for g in range(4):
+        key = "dA" if g < 2 else "dB"
+        acc[g][key] = outs[g][1 if g < 2 else 2].clone()
+        acc[g]["dX"] = None
+    abt.lr_linear_bwd_grouped(acc, accumulate=True)
+    torch.cuda.synchronize()
+    for g in range(4):
+        key = "dA" if g < 2 else "dB"
+        assert rel(host(acc[g][key]), 2 * host(outs[g][1 if g < 2 else 2])) < 1e-6
