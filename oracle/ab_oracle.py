@@ -274,12 +274,15 @@ def ab_training_run(weights, groups, tau, lr, batch, loss_grad, full_rank_step, 
 # A [m, k] and B [k, kh kw C]: B is a kh x kw convolution to k channels, A a 1 x 1 convolution.
 # Layout here: activations N x H x W x C (channels last); the flattened axis is ordered tap-major,
 # column (ky kw + kx) C + c.  (The order of the flattened axis only permutes the columns of W
-# and of B; it does not change the factorisation.)  Stride 1, zero padding (kh-1)/2, (kw-1)/2
-# ("same"), kh and kw odd: the 3x3 and 1x1 convolutions of ResNet-50's bottleneck blocks.
+# and of B; it does not change the factorisation.)  Zero padding (kh-1)/2, (kw-1)/2, kh and kw odd,
+# stride s >= 1 in both directions: output pixel (y', x') is centred on input pixel (s y', s x') and
+# the output has ceil(H / s) x ceil(W / s) pixels: the 3x3 and 1x1 convolutions of ResNet-50's
+# bottleneck blocks, the down-sampling ones (s = 2) included.
 
-def conv_patches(act, kh, kw):
-    """Patch matrix of a channels-last activation: Xcol [N H W, kh kw C] with
-    Xcol[(b, y, x), (ky, kx, c)] = act[b, y + ky - ph, x + kx - pw, c], zero outside the image."""
+def conv_patches(act, kh, kw, stride=1):
+    """Patch matrix of a channels-last activation: Xcol [N H' W', kh kw C] with
+    Xcol[(b, y', x'), (ky, kx, c)] = act[b, s y' + ky - ph, s x' + kx - pw, c], zero outside the
+    image (H' = ceil(H / s), W' = ceil(W / s)): the patches of every s-th pixel in both directions."""
     act = _f64(act)
     N, H, W, C = act.shape
     assert kh % 2 == 1 and kw % 2 == 1
@@ -290,14 +293,17 @@ def conv_patches(act, kh, kw):
     for ky in range(kh):
         for kx in range(kw):
             cols[:, :, :, ky * kw + kx, :] = padded[:, ky:ky + H, kx:kx + W, :]
-    return cols.reshape(N * H * W, kh * kw * C)
+    cols = cols[:, ::stride, ::stride]
+    return np.ascontiguousarray(cols).reshape(-1, kh * kw * C)
 
 
-def conv_patches_adjoint(G, shape, kh, kw):
-    """Adjoint of conv_patches: sums every entry of G [N H W, kh kw C] back onto the activation
+def conv_patches_adjoint(G, shape, kh, kw, stride=1):
+    """Adjoint of conv_patches: sums every entry of G [N H' W', kh kw C] back onto the activation
     element it was read from.  Returns [N, H, W, C]."""
     N, H, W, C = shape
-    G = _f64(G).reshape(N, H, W, kh * kw, C)
+    Gs = _f64(G).reshape(N, -(-H // stride), -(-W // stride), kh * kw, C)
+    G = np.zeros((N, H, W, kh * kw, C), dtype=_F64)     # the pixels between the strided ones had no patch
+    G[:, ::stride, ::stride] = Gs
     ph, pw = kh // 2, kw // 2
     padded = np.zeros((N, H + 2 * ph, W + 2 * pw, C), dtype=_F64)
     for ky in range(kh):
@@ -306,16 +312,16 @@ def conv_patches_adjoint(G, shape, kh, kw):
     return padded[:, ph:ph + H, pw:pw + W, :]
 
 
-def lr_conv_fwd(act, A, B, kh, kw):
+def lr_conv_fwd(act, A, B, kh, kw, stride=1):
     """Forward of a convolution whose flattened weight is W = A B: the factored linear layer
-    applied to the patch matrix.  Returns (Y [N H W, m], T [N H W, k])."""
-    return lr_linear_fwd(conv_patches(act, kh, kw), A, B)
+    applied to the patch matrix.  Returns (Y [N H' W', m], T [N H' W', k])."""
+    return lr_linear_fwd(conv_patches(act, kh, kw, stride), A, B)
 
 
-def lr_conv_bwd(dY, act, A, B, kh, kw):
+def lr_conv_bwd(dY, act, A, B, kh, kw, stride=1):
     """Backward of the same layer: the factored layer's gradients on the patch matrix, and the
     activation gradient as the adjoint of the patch extraction applied to dXcol = dT B.
     Returns (dAct [N, H, W, C], dA, dB, dT)."""
     act = _f64(act)
-    dXcol, dA, dB, dT = lr_linear_bwd(dY, conv_patches(act, kh, kw), A, B)
-    return conv_patches_adjoint(dXcol, act.shape, kh, kw), dA, dB, dT
+    dXcol, dA, dB, dT = lr_linear_bwd(dY, conv_patches(act, kh, kw, stride), A, B)
+    return conv_patches_adjoint(dXcol, act.shape, kh, kw, stride), dA, dB, dT

@@ -479,6 +479,21 @@ def test_conv_fwd_against_library_correlation():
             for o in range(m):
                 ref = sum(sig.correlate2d(act[b, :, :, c], Wd[o, :, :, c], mode="same") for c in range(C))
                 np.testing.assert_allclose(Y.reshape(N, H, W, m)[b, :, :, o], ref, rtol=1e-11, atol=1e-11)
+    # stride 2: the library's stride-1 correlation at every second pixel (5 x 6 -> 3 x 3 outputs)
+    kh, kw = 3, 3
+    act = rng.standard_normal((N, H, W, C))
+    A = rng.standard_normal((m, k)); B = rng.standard_normal((k, kh * kw * C))
+    Y, T = orc.lr_conv_fwd(act, A, B, kh, kw, stride=2)
+    assert Y.shape == (N * 3 * 3, m) and T.shape == (N * 3 * 3, k)
+    Wd = (A @ B).reshape(m, kh, kw, C)
+    for b in range(N):
+        for o in range(m):
+            ref = sum(sig.correlate2d(act[b, :, :, c], Wd[o, :, :, c], mode="same") for c in range(C))
+            np.testing.assert_allclose(Y.reshape(N, 3, 3, m)[b, :, :, o], ref[::2, ::2], rtol=1e-11, atol=1e-11)
+    # a 1 x 1 window with stride 2 is the plain factored layer on every second pixel
+    Bp = rng.standard_normal((k, C))
+    np.testing.assert_array_equal(orc.lr_conv_fwd(act, A, Bp, 1, 1, stride=2)[0],
+                                  orc.lr_linear_fwd(act[:, ::2, ::2].reshape(-1, C), A, Bp)[0])
     # a 1 x 1 window is the plain factored linear layer on the pixels
     act = rng.standard_normal((N, H, W, C)); A = rng.standard_normal((m, k)); B = rng.standard_normal((k, C))
     np.testing.assert_array_equal(orc.lr_conv_fwd(act, A, B, 1, 1)[0],
@@ -494,15 +509,22 @@ def test_conv_patches_adjoint_identity():
         lhs = np.sum(orc.conv_patches(act, kh, kw) * G)
         rhs = np.sum(act * orc.conv_patches_adjoint(G, shape, kh, kw))
         assert lhs == pytest.approx(rhs, rel=1e-12)
+        # stride 2: 4 x 5 -> 2 x 3 patches
+        G2 = rng.standard_normal((2 * 2 * 3, kh * kw * 3))
+        lhs = np.sum(orc.conv_patches(act, kh, kw, 2) * G2)
+        rhs = np.sum(act * orc.conv_patches_adjoint(G2, shape, kh, kw, 2))
+        assert lhs == pytest.approx(rhs, rel=1e-12)
 
 
-def test_conv_bwd_matches_central_finite_differences():
+@pytest.mark.parametrize("stride", [1, 2])
+def test_conv_bwd_matches_central_finite_differences(stride):
     rng = np.random.default_rng(10)
     N, H, W, C, m, k, kh, kw = 2, 4, 3, 2, 3, 2, 3, 3
+    rows = N * (-(-H // stride)) * (-(-W // stride))
     act = rng.standard_normal((N, H, W, C)); A = rng.standard_normal((m, k))
-    B = rng.standard_normal((k, kh * kw * C)); R = rng.standard_normal((N * H * W, m))
-    loss = lambda a_, A_, B_: float(np.sum(orc.lr_conv_fwd(a_, A_, B_, kh, kw)[0] * R))
-    dAct, dA, dB, _ = orc.lr_conv_bwd(R, act, A, B, kh, kw)
+    B = rng.standard_normal((k, kh * kw * C)); R = rng.standard_normal((rows, m))
+    loss = lambda a_, A_, B_: float(np.sum(orc.lr_conv_fwd(a_, A_, B_, kh, kw, stride)[0] * R))
+    dAct, dA, dB, _ = orc.lr_conv_bwd(R, act, A, B, kh, kw, stride)
     eps = 1e-6
     for arr, grad, which in ((act, dAct, 0), (A, dA, 1), (B, dB, 2)):
         for _ in range(12):
