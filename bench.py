@@ -387,10 +387,12 @@ def main():
         # config 4's two 3x3 cases without the patch matrix: same flops as the im2col form, the
         # activation read at its true size (lr_conv_fwd + lr_conv_bwd, all three gradients)
         conv = []
-        for name, N, H, W, C, m, r in gen.RESNET50_CONVS_NATIVE:
-            c = gen.conv_case(N, H, W, C, m, r, 3, 3, seed=11)
-            Mc, nc = N * H * W, 9 * C
-            sets = sets_for(2.0 * (2 * Mc * C + 2 * Mc * m + Mc * r))
+        native = [(nm, N, H, W, C, m, r, 3, 3, 1) for nm, N, H, W, C, m, r in gen.RESNET50_CONVS_NATIVE] + \
+                 [row + (2,) for row in gen.RESNET50_CONVS_STRIDED]
+        for name, N, H, W, C, m, r, kh, kw, stride in native:
+            c = gen.conv_case(N, H, W, C, m, r, kh, kw, seed=11, stride=stride)
+            Mc, nc = N * (-(-H // stride)) * (-(-W // stride)), kh * kw * C
+            sets = sets_for(2.0 * (2 * N * H * W * C + 2 * Mc * m + Mc * r))
             act0, dY0 = up(c["act"], bf16), up(c["dY"], bf16)
             Ac, Bc = up(c["A"], bf16), up(c["B"], bf16)
             bufs = [dict(act=act0 if i == 0 else act0.clone(), dY=dY0 if i == 0 else dY0.clone(),
@@ -398,19 +400,21 @@ def main():
                          dAct=torch.empty_like(act0)) for i in range(sets)]
             dAc = torch.empty((m, r), dtype=torch.float32, device=dev)
             dBc = torch.empty((r, nc), dtype=torch.float32, device=dev)
-            geom = abt.ConvGeom(N, H, W, C, 3, 3)
+            geom = abt.ConvGeom(N, H, W, C, kh, kw, stride)
             wsc = torch.empty(lib.lr_conv_bwd_workspace_bytes(ctypes.byref(geom), m, r, abt.ABT_BF16), dtype=torch.uint8, device=dev)
 
             def conv_step(i):
                 b = bufs[i % len(bufs)]
-                abt.lr_conv_fwd(b["act"], Ac, Bc, 3, 3, save_T=True, Y=b["Y"], T=b["T"])
-                abt.lr_conv_bwd(b["dY"], b["act"], b["T"], Ac, Bc, 3, 3, dAct=b["dAct"], dA=dAc, dB=dBc, workspace=wsc)
+                abt.lr_conv_fwd(b["act"], Ac, Bc, kh, kw, save_T=True, Y=b["Y"], T=b["T"], stride=stride)
+                abt.lr_conv_bwd(b["dY"], b["act"], b["T"], Ac, Bc, kh, kw, dAct=b["dAct"], dA=dAc, dB=dBc, workspace=wsc,
+                                stride=stride)
 
             sc = event_ms(conv_step)[1]
             flops = 6.0 * Mc * r * (m + nc)
             # algorithmic bytes: activation, its gradient, Y, dY, T (written, read), dT (written, read twice)
-            byt = 2.0 * (2 * Mc * C + 2 * Mc * m + 5 * Mc * r + 2 * (m * r + r * nc)) + 4.0 * (m * r + r * nc)
-            conv.append({"case": name, "N": N, "H": H, "W": W, "C": C, "m": m, "r": r, "buffer_sets": sets,
+            byt = 2.0 * (2 * N * H * W * C + 2 * Mc * m + 5 * Mc * r + 2 * (m * r + r * nc)) + 4.0 * (m * r + r * nc)
+            conv.append({"case": name, "N": N, "H": H, "W": W, "C": C, "m": m, "r": r, "kh": kh, "kw": kw,
+                         "stride": stride, "buffer_sets": sets,
                          "ms": round(sc, 4), "tflops": round(flops / sc / 1e9, 1),
                          "pct_mfma_peak": round(100 * flops / sc / 1e9 / PEAK_BF16_TFLOPS, 2),
                          "hbm_frac": round(byt / sc / 1e6 / PEAK_HBM_GBS, 4)})

@@ -322,8 +322,11 @@ int ab_reconstruct(const float* A, const float* B, float* W,
  * convolution to r channels, A as a 1 x 1 convolution.  The patch matrix is never materialised:
  * the kernels gather it from the activation.
  * Layout: activation act [N, H, W, C] channels last; the flattened axis of B is tap-major,
- * column (ky kw + kx) C + c; outputs Y [N H W, m], T [N H W, r] (row = pixel, in act's order).
- * Stride 1, zero padding kh/2, kw/2 ("same"), kh and kw odd.  bf16 only (fp32 accumulation).
+ * column (ky kw + kx) C + c.  Zero padding kh/2, kw/2, kh and kw odd, stride 1 or 2 in both
+ * directions: output pixel (y', x') is centred on input pixel (stride y', stride x'), the output
+ * grid is H' x W' = ceil(H / stride) x ceil(W / stride) (ResNet-50's down-sampling 3 x 3 and 1 x 1
+ * convolutions are the stride-2 case).  Y [N H' W', m], T [N H' W', r], dY likewise (row = output
+ * pixel, row-major); dAct has act's shape.  bf16 only (fp32 accumulation).
  *   lr_conv_fwd:  T = patches(act) . B^T,  Y = T . A^T          (T_save may be NULL)
  *   lr_conv_bwd:  dT = dY . A,  dA = dY^T . T,  dB = dT^T . patches(act),
  *                 dAct = adjoint of the patch extraction applied to dT . B
@@ -335,6 +338,8 @@ int ab_reconstruct(const float* A, const float* B, float* W,
 typedef struct {
     int64_t N, H, W, C;
     int32_t kh, kw;
+    int32_t stride;               /* 1 or 2 */
+    int32_t reserved;             /* 0 */
 } abt_conv_geom;
 
 int lr_conv_fwd(const void* act, const void* A, const void* B, void* Y, void* T_save,

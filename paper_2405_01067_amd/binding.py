@@ -44,7 +44,10 @@ class FactorizeDesc(ctypes.Structure):
 
 class ConvGeom(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int64), ("H", ctypes.c_int64), ("W", ctypes.c_int64), ("C", ctypes.c_int64),
-                ("kh", ctypes.c_int32), ("kw", ctypes.c_int32)]
+                ("kh", ctypes.c_int32), ("kw", ctypes.c_int32), ("stride", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+    def __init__(self, N=0, H=0, W=0, C=0, kh=1, kw=1, stride=1):
+        super().__init__(N, H, W, C, kh, kw, stride, 0)
 
 
 class AdamwTensor(ctypes.Structure):
@@ -414,7 +417,7 @@ def lr_linear_bwd_static(dY, X, T, A, B, dX=None, dA=None, dB=None, accumulate: 
     return dX, dA, dB
 
 
-def _conv_geom(act, B, kh, kw):
+def _conv_geom(act, B, kh, kw, stride=1):
     torch = _torch()
     _dev_tensor(act, "act")
     if act.dim() != 4 or act.dtype != torch.bfloat16:
@@ -422,16 +425,19 @@ def _conv_geom(act, B, kh, kw):
     N, H, W, C = act.shape
     if B.dim() != 2 or B.shape[1] != kh * kw * C:
         raise AbtError("B must be [r, kh*kw*C] with tap-major columns")
-    return ConvGeom(N, H, W, C, kh, kw), N * H * W
+    if stride not in (1, 2):
+        raise AbtError("stride must be 1 or 2")
+    return ConvGeom(N, H, W, C, kh, kw, stride), N * (-(-H // stride)) * (-(-W // stride))
 
 
-def lr_conv_fwd(act, A, B, kh: int, kw: int, save_T: bool = True, Y=None, T=None):
-    """Factored kh x kw convolution (stride 1, zero padding): Y [N*H*W, m], T [N*H*W, r] from the
-    channels-last activation act [N, H, W, C], A [m, r], B [r, kh*kw*C] (all bf16, on the GPU)."""
+def lr_conv_fwd(act, A, B, kh: int, kw: int, save_T: bool = True, Y=None, T=None, stride: int = 1):
+    """Factored kh x kw convolution (zero padding kh/2, kw/2; stride 1 or 2): Y [N*H'*W', m],
+    T [N*H'*W', r] with H' = ceil(H / stride), from the channels-last activation act [N, H, W, C],
+    A [m, r], B [r, kh*kw*C] (all bf16, on the GPU)."""
     torch = _torch()
     lib = load()
     A, B = _dev_tensor(A, "A"), _dev_tensor(B, "B")
-    geom, M = _conv_geom(act, B, kh, kw)
+    geom, M = _conv_geom(act, B, kh, kw, stride)
     m, r = A.shape
     if B.shape[0] != r:
         raise AbtError("shape mismatch: A [m,r], B [r, kh*kw*C]")
@@ -447,13 +453,14 @@ def lr_conv_fwd(act, A, B, kh: int, kw: int, save_T: bool = True, Y=None, T=None
 
 
 def lr_conv_bwd(dY, act, T, A, B, kh: int, kw: int, need_dAct: bool = True, need_dA: bool = True,
-                need_dB: bool = True, dAct=None, dA=None, dB=None, accumulate: bool = False, workspace=None):
+                need_dB: bool = True, dAct=None, dA=None, dB=None, accumulate: bool = False, workspace=None,
+                stride: int = 1):
     """Gradients of the factored convolution: dAct [N,H,W,C] bf16, dA [m,r] fp32, dB [r, kh*kw*C] fp32;
-    skipped gradients are None.  T may be None (recomputed)."""
+    skipped gradients are None.  T may be None (recomputed).  dY and T have N*H'*W' rows."""
     torch = _torch()
     lib = load()
     dY, A, B = _dev_tensor(dY, "dY"), _dev_tensor(A, "A"), _dev_tensor(B, "B")
-    geom, M = _conv_geom(act, B, kh, kw)
+    geom, M = _conv_geom(act, B, kh, kw, stride)
     m, r = A.shape
     if tuple(dY.shape) != (M, m) or B.shape[0] != r or (T is not None and tuple(_dev_tensor(T, "T").shape) != (M, r)):
         raise AbtError("shape mismatch: dY [N*H*W, m], A [m,r], B [r, kh*kw*C], T [N*H*W, r]")

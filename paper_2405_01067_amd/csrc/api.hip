@@ -165,17 +165,34 @@ const char* abt_status_string(int status) {
 
 namespace {
 
+// output grid of a convolution with zero padding kh/2, kw/2 and stride s: ceil(H / s) x ceil(W / s)
+inline int64_t conv_out(int64_t extent, int stride) { return (extent + stride - 1) / stride; }
+inline int64_t conv_rows(const abt_conv_geom& g) { return g.N * conv_out(g.H, g.stride) * conv_out(g.W, g.stride); }
+// the three gathers of a factored convolution
+PatchGeom conv_patches_geom(const abt_conv_geom& g) {        // rows = output pixels, image = act
+    return PatchGeom{(int)g.H, (int)g.W, (int)g.C, g.kh, g.kw, +1,
+                     (int)conv_out(g.H, g.stride), (int)conv_out(g.W, g.stride), g.stride, 0};
+}
+PatchGeom conv_adjoint_geom(const abt_conv_geom& g, int r) {  // rows = input pixels, image = dT on the output grid
+    return PatchGeom{(int)conv_out(g.H, g.stride), (int)conv_out(g.W, g.stride), r, g.kh, g.kw, -1,
+                     (int)g.H, (int)g.W, 1, g.stride == 2 ? 1 : 0};
+}
+
 int check_conv(const abt_conv_geom* g, int64_t m, int64_t r, int dt) {
     if (!g) return ABT_EINVAL;
     if (dt != ABT_BF16) return ABT_EDTYPE;
+    if (g->stride != 1 && g->stride != 2) return ABT_ESHAPE;
     if (g->N < 1 || g->H < 1 || g->W < 1 || g->C < 1 || m < 1 || r < 1 || g->kh < 1 || g->kw < 1) return ABT_ESHAPE;
     if (!(g->kh & 1) || !(g->kw & 1) || g->kh > 15 || g->kw > 15) return ABT_ESHAPE;
     if (g->C % 64 || m % 64 || r % 32 || r > 384 || r == 224 || r == 288 || r == 352) return ABT_ESHAPE;
     if (g->H > (1 << 20) || g->W > (1 << 20) || g->C > (1 << 20) || m > (1 << 20)) return ABT_ESHAPE;
     if ((int64_t)g->kh * g->kw * g->C > (1 << 20)) return ABT_ESHAPE;
     if (g->N > 0x7fffffff / (g->H * g->W)) return ABT_ESHAPE;     // pixel count fits an int
-    // the window of the image that one 64-row block's patches touch is addressed with 32-bit offsets
-    if ((64 + 2 * ((g->kh / 2) * g->W + g->kw / 2)) * g->C * 2 >= kBufMaxBytes) return ABT_ESHAPE;
+    // the window of the image that one 128-row block's patches touch is addressed with 32-bit offsets
+    // (the launchers check their own windows again, with the exact geometry)
+    if (((int64_t)g->stride * g->stride * (128 + 2 * g->W + 2) + 2 * g->stride * g->W +
+         2 * ((g->kh / 2) * g->W + g->kw / 2)) * g->C * 2 >= kBufMaxBytes)
+        return ABT_ESHAPE;
     return ABT_OK;
 }
 
@@ -190,7 +207,7 @@ struct ConvBwdLayout { size_t At, dT, T, Pst, partials, total; int r_pad; };
 
 ConvBwdLayout conv_bwd_layout(const abt_conv_geom& g, int64_t m, int64_t r) {
     ConvBwdLayout w{};
-    const int64_t M = g.N * g.H * g.W, taps = (int64_t)g.kh * g.kw;
+    const int64_t M = conv_rows(g), taps = (int64_t)g.kh * g.kw;     // rows of Y, T, dY, dT
     w.r_pad = (int)((r + 63) / 64 * 64);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -222,8 +239,8 @@ int lr_conv_fwd(const void* act, const void* A, const void* B, void* Y, void* T_
     if (!aligned(act, 16) || !aligned(A, 16) || !aligned(B, 16) || !aligned(Y, 16) || !aligned(T_save, 16))
         return ABT_EALIGN;
     const abt_conv_geom& g = *geom;
-    const int64_t M = g.N * g.H * g.W;
-    const PatchGeom pg{(int)g.H, (int)g.W, (int)g.C, g.kh, g.kw, +1};
+    const int64_t M = conv_rows(g);
+    const PatchGeom pg = conv_patches_geom(g);
     return chain_gather(act, pg, B, A, Y, T_save, (int)r, M, (int)m, (int)r, (hipStream_t)stream) == hipSuccess
                ? ABT_OK : ABT_EHIP;
 }
@@ -245,10 +262,10 @@ int lr_conv_bwd(const void* dY, const void* act, const void* T, const void* A, c
     if (!dAct && !dA && !dB) return ABT_OK;
     hipStream_t s = (hipStream_t)stream;
     char* ws = (char*)workspace;
-    const int64_t M = g.N * g.H * g.W;
+    const int64_t M = conv_rows(g), M_in = g.N * g.H * g.W;     // output pixels (rows of dY, T, dT), input pixels
     const int taps = g.kh * g.kw;
     const int acc = accumulate ? 1 : 0;
-    const PatchGeom fwd_geom{(int)g.H, (int)g.W, (int)g.C, g.kh, g.kw, +1};
+    const PatchGeom fwd_geom = conv_patches_geom(g);
     void* dT = ws + w.dT;
     const void* Tp = T;
     if (!Tp && dA) {   // recompute T = patches(act) B^T (first stage of the chain only)
@@ -263,16 +280,17 @@ int lr_conv_bwd(const void* dY, const void* act, const void* T, const void* A, c
         if (chain(dY, ws + w.At, nullptr, nullptr, dT, M, (int)m, 64, (int)r, s) != hipSuccess) return ABT_EHIP;
     }
     if (dAct) {
-        // dAct[q, c] = sum over taps and j of dT[q - shift(tap), j] B[j, tap, c]: the same gathered
-        // product as the forward, on the image dT [N, H, W, r] with mirrored shifts, against the
-        // re-laid-out factor Pst [C, taps r_pad]; one launch per block of output channels
+        // dAct[q, c] = sum over taps and j of dT[(q - shift(tap)) / stride, j] B[j, tap, c] (only where
+        // the division is exact): the same gathered product as the forward, on the image
+        // dT [N, H', W', r] with mirrored shifts, against the re-laid-out factor Pst [C, taps r_pad];
+        // rows are the input pixels; one launch per block of output channels
         if (launch_conv_bstack_bf16(B, ws + w.Pst, (int)r, (int)g.C, taps, w.r_pad, s) != hipSuccess) return ABT_EHIP;
-        const PatchGeom adj{(int)g.H, (int)g.W, (int)r, g.kh, g.kw, -1};
+        const PatchGeom adj = conv_adjoint_geom(g, (int)r);
         const int chunk = conv_dact_chunk(g.C);
         const int64_t pst_pitch = (int64_t)taps * w.r_pad;
         for (int64_t c0 = 0; c0 < g.C; c0 += chunk) {
             const char* Pc = ws + w.Pst + (size_t)c0 * pst_pitch * 2;
-            if (chain_gather(dT, adj, Pc, nullptr, nullptr, (char*)dAct + c0 * 2, (int)g.C, M, 64, chunk, s) !=
+            if (chain_gather(dT, adj, Pc, nullptr, nullptr, (char*)dAct + c0 * 2, (int)g.C, M_in, 64, chunk, s) !=
                 hipSuccess)
                 return ABT_EHIP;
         }

@@ -88,13 +88,20 @@ constexpr int kChainMaxGroups = 8;
 struct ChainProblem { const void* Xin; const void* P; const void* Q; void* Yout; void* Tout; };
 hipError_t launch_chain2_grouped_bf16(const ChainProblem* problems, int G, int64_t M, int p, int q, int R,
                                       int rows, int parts, hipStream_t s);
-// The same chain with the first operand gathered from a channels-last image [M / (H W), H, W, Cin]
-// instead of read from a matrix: row i of the virtual operand is the kh x kw patch around pixel i
+// The same chain with the first operand gathered from a channels-last image [images, H, W, Cin]
+// instead of read from a matrix: row i of the virtual operand is the kh x kw patch around a pixel
 // (zero outside the image), columns ordered (tap, channel) with every tap padded to a multiple of
 // 64 channels: p = kh kw ceil(Cin / 64) 64 columns, which is the row length of P [R, p].
-// sign = +1 reads pixel (y + ky - kh/2, x + kx - kw/2) for tap (ky, kx); sign = -1 the mirrored
-// pixel (the adjoint gather).  Tout rows are t_pitch elements apart (>= R).
-struct PatchGeom { int H, W, Cin, kh, kw, sign; };
+// Rows are the pixels of a grid RH x RW per image (M = images RH RW); row (y, x) is centred on image
+// pixel (mul y, mul x) and tap (ky, kx) reads the position sign (ky - kh/2, kx - kw/2) away from it,
+// which with shift = 1 exists only where both coordinates are even, as pixel (ty / 2, tx / 2):
+//   patches, stride 1:        RH x RW = H x W, mul = 1, shift = 0, sign = +1
+//   patches, stride 2:        RH x RW = output grid, mul = 2, shift = 0, sign = +1
+//   adjoint gather, stride 1: the same with sign = -1
+//   adjoint gather, stride 2: image = gradient on the output grid, RH x RW = input grid, mul = 1,
+//                             shift = 1, sign = -1.
+// Tout rows are t_pitch elements apart (>= R).
+struct PatchGeom { int H, W, Cin, kh, kw, sign, RH, RW, mul, shift; };
 hipError_t launch_chain2_gather_bf16(const void* image, const PatchGeom& g, const void* P, const void* Q,
                                      void* Yout, void* Tout, int t_pitch, int64_t M, int q, int R, hipStream_t s);
 hipError_t launch_chain2_tall_gather_bf16(const void* image, const PatchGeom& g, const void* P, const void* Q,

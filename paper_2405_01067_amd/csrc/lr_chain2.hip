@@ -138,12 +138,28 @@ struct Ch2Cfg {
 };
 
 // Gather form of the Xin operand (GATHER = true): Xin is not a matrix but a channels-last image
-// [pixels / (H W), H, W, Cin], and row i of the virtual matrix is the patch around pixel i: virtual
+// [images, H, W, Cin], and row i of the virtual matrix is the patch around a pixel of it: virtual
 // column (tap, block, c) with tap = ky kw + kx, `cpb` 64-column blocks per tap, reads channel
-// 64 block + c of pixel (y + sign (ky - kh/2), x + sign (kx - kw/2)) of the same image, zero outside
-// the image and for channels >= Cin.  A slab of 64 contraction columns is then one tap and one
-// channel block: 128 contiguous bytes per row, as in the plain case.  p = kh kw cpb 64.
-struct Ch2Gather { int H, W, Cin, cpb, kh, kw, sign; };
+// 64 block + c of the pixel `sign (ky - kh/2, kx - kw/2)` away from the row's centre, zero outside the
+// image and for channels >= Cin.  A slab of 64 contraction columns is then one tap and one channel
+// block: 128 contiguous bytes per row, as in the plain case.  p = kh kw cpb 64.
+// Rows are the pixels of a grid RH x RW per image, row-major; the centre of row (y, x) is the image
+// pixel (mul y, mul x), and with shift > 0 the shifted position (ty, tx) only exists in the image
+// where both are multiples of 2^shift, as pixel (ty >> shift, tx >> shift):
+//   stride 1:                     RH x RW = H x W, mul = 1, shift = 0
+//   strided patches (forward):    RH x RW = the output grid, mul = stride, shift = 0
+//   their adjoint (image = the gradient on the output grid, rows = input pixels): mul = 1, shift = log2 stride.
+struct Ch2Gather { int H, W, Cin, cpb, kh, kw, sign, RH, RW, mul, shift; };
+
+// Source pixel (linear, over all images) at the centre of the first (end = 0) or last (end = 1)
+// pixel of the grid row that row i lies in.  The centre is monotone in (image, y) and in x, so the
+// centres of rows i0 .. i1 lie between ch2_centre(i0, 0) and ch2_centre(i1, 1).
+__device__ __forceinline__ int ch2_centre(const Ch2Gather& gg, int i, int end) {
+    const int per = gg.RH * gg.RW;
+    const int img = i / per, rem = i - img * per;
+    const int y = rem / gg.RW, x = end ? gg.RW - 1 : 0;
+    return (img * gg.H + ((gg.mul * y) >> gg.shift)) * gg.W + ((gg.mul * x) >> gg.shift);
+}
 
 // Operands of up to kChainMaxGroups problems of one shape (the emulated groups of a training step:
 // same M, p, q, R, each with its own activations and its own copy of the factors); blockIdx.y picks one.
@@ -218,10 +234,18 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(Ch2
         // rows past M read as zeros and stores to them are dropped.
         const int lt = tid - NMT;
         const int64_t rows_valid = M - row0 < ROWS ? M - row0 : ROWS;
-        // gather: the descriptor covers the pixels this work-group's patches can touch
+        // gather: the descriptor covers the pixels this work-group's patches can touch (from the start of
+        // the grid row of its first row to the end of the grid row of its last, and the reach of the window)
         const int reach = GATHER ? (gg.kh / 2) * gg.W + gg.kw / 2 : 0;
-        const int64_t gpix0 = row0 > reach ? row0 - reach : 0;
-        const int64_t gpix1 = row0 + ROWS + reach < M ? row0 + ROWS + reach : M;
+        const bool plain = !GATHER || (gg.mul == 1 && gg.shift == 0);
+        int64_t gpix0 = 0, gpix1 = 0;
+        if constexpr (GATHER) {
+            const int last = (int)(row0 + ROWS < M ? row0 + ROWS : M) - 1;
+            const int64_t pixels = (M / ((int64_t)gg.RH * gg.RW)) * gg.H * gg.W;
+            const int c0 = ch2_centre(gg, (int)row0, 0), c1 = ch2_centre(gg, last, 1);
+            gpix0 = c0 > reach ? c0 - reach : 0;
+            gpix1 = (int64_t)c1 + reach + 1 < pixels ? (int64_t)c1 + reach + 1 : pixels;
+        }
         const rsrc_t xres = GATHER ? make_rsrc(Xin + gpix0 * gg.Cin, (gpix1 - gpix0) * gg.Cin * 2)
                                    : make_rsrc(Xin + row0 * p, rows_valid * p * 2);
         const rsrc_t pres = make_rsrc(Pm, (int64_t)R * p * 2);
@@ -247,9 +271,13 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(Ch2
                 off[e] = row * (BK1 * 2) + swz<CPR1>(ch, row) * 16;
                 if constexpr (GATHER) {
                     const int64_t pix = row0 + row;
-                    gx[e] = (int)(pix % gg.W);
-                    gy[e] = pix < M ? (int)((pix / gg.W) % gg.H) : -(1 << 20);   // rows past M: never valid
-                    xsrc[e] = ((int)(pix - gpix0) * gg.Cin + ch * 8) * 2;
+                    const int x = (int)(pix % gg.RW), y = (int)((pix / gg.RW) % gg.RH);
+                    const int64_t img = pix / ((int64_t)gg.RW * gg.RH);
+                    gx[e] = gg.mul * x;
+                    gy[e] = pix < M ? gg.mul * y : -(1 << 20);   // rows past M: never valid
+                    // plain: offset of the row's own pixel; else: offset of its image's first pixel
+                    xsrc[e] = plain ? ((int)(pix - gpix0) * gg.Cin + ch * 8) * 2
+                                    : ((int)(img * gg.H * gg.W - gpix0) * gg.Cin + ch * 8) * 2;
                 } else {
                     gx[e] = gy[e] = 0;
                     xsrc[e] = (row * p + ch * 8) * 2;
@@ -262,9 +290,17 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(Ch2
                     const int ky = tap / gg.kw, kx = tap - ky * gg.kw;
                     const int dy = gg.sign * (ky - gg.kh / 2), dx = gg.sign * (kx - gg.kw / 2);
                     const int ch8 = (lt % CPR1) * 8;
-                    const bool ok = (unsigned)(gy[e] + dy) < (unsigned)gg.H && (unsigned)(gx[e] + dx) < (unsigned)gg.W &&
-                                    cb * 64 + ch8 < gg.Cin;
-                    voff = ok ? xsrc[e] + ((dy * gg.W + dx) * gg.Cin + cb * 64) * 2 : kBufNowhere;
+                    if (plain) {
+                        const bool ok = (unsigned)(gy[e] + dy) < (unsigned)gg.H && (unsigned)(gx[e] + dx) < (unsigned)gg.W &&
+                                        cb * 64 + ch8 < gg.Cin;
+                        voff = ok ? xsrc[e] + ((dy * gg.W + dx) * gg.Cin + cb * 64) * 2 : kBufNowhere;
+                    } else {
+                        const int ty = gy[e] + dy, tx = gx[e] + dx, low = (1 << gg.shift) - 1;
+                        const int sy = ty >> gg.shift, sx = tx >> gg.shift;
+                        const bool ok = ty >= 0 && tx >= 0 && ((ty | tx) & low) == 0 && sy < gg.H && sx < gg.W &&
+                                        cb * 64 + ch8 < gg.Cin;
+                        voff = ok ? xsrc[e] + ((sy * gg.W + sx) * gg.Cin + cb * 64) * 2 : kBufNowhere;
+                    }
                     soff = 0;
                 } else {
                     voff = xsrc[e];
@@ -778,10 +814,21 @@ Ch2Ptrs one_problem(const void* Xin, const void* P, const void* Q, void* Yout, v
 
 // checks shared by the two gathered launchers; rows = work-group height
 bool gather_ok(const PatchGeom& g, int64_t M, int64_t p, int t_pitch, int R, int rows) {
-    return g.H >= 1 && g.W >= 1 && g.Cin >= 8 && g.Cin % 8 == 0 && g.kh >= 1 && g.kw >= 1 && (g.kh & 1) && (g.kw & 1) &&
-           (g.sign == 1 || g.sign == -1) && M % ((int64_t)g.H * g.W) == 0 && p <= (1 << 20) && t_pitch >= R &&
-           // 32-bit offsets inside a work-group's window of the image
-           ((int64_t)rows + 2 * ((g.kh / 2) * (int64_t)g.W + g.kw / 2)) * g.Cin * 2 < kBufMaxBytes;
+    if (!(g.H >= 1 && g.W >= 1 && g.Cin >= 8 && g.Cin % 8 == 0 && g.kh >= 1 && g.kw >= 1 && (g.kh & 1) && (g.kw & 1) &&
+          (g.sign == 1 || g.sign == -1) && g.RH >= 1 && g.RW >= 1 && (g.mul == 1 || g.mul == 2) &&
+          (g.shift == 0 || g.shift == 1) && M % ((int64_t)g.RH * g.RW) == 0 && M <= 0x7fffffff && p <= (1 << 20) &&
+          t_pitch >= R))
+        return false;
+    // 32-bit offsets inside a work-group's window of the image: `rows` consecutive rows and the grid
+    // rows they start and end in have their centres within mul^2 (rows + 2 RW) + 2 mul W pixels of
+    // one another; the reach of the window comes on top
+    const int64_t span = (int64_t)g.mul * g.mul * (rows + 2 * g.RW + 2) + 2 * (int64_t)g.mul * g.W +
+                         2 * ((g.kh / 2) * (int64_t)g.W + g.kw / 2);
+    return span * g.Cin * 2 < kBufMaxBytes && (M / ((int64_t)g.RH * g.RW)) * g.H * g.W <= 0x7fffffff;
+}
+
+Ch2Gather device_geom(const PatchGeom& g) {
+    return Ch2Gather{g.H, g.W, g.Cin, (g.Cin + 63) / 64, g.kh, g.kw, g.sign, g.RH, g.RW, g.mul, g.shift};
 }
 
 }  // namespace
@@ -819,7 +866,7 @@ hipError_t launch_chain2_gather_bf16(const void* image, const PatchGeom& g, cons
     const int cpb = (g.Cin + 63) / 64;
     const int64_t p = (int64_t)g.kh * g.kw * cpb * 64;
     if (!gather_ok(g, M, p, t_pitch, R, 64) || !chain2_supports(R, (int)p, q)) return hipErrorInvalidValue;
-    const Ch2Gather gg{g.H, g.W, g.Cin, cpb, g.kh, g.kw, g.sign};
+    const Ch2Gather gg = device_geom(g);
     return launch_chain_64<true>(one_problem(image, P, Q, Yout, Tout), 1, Yout != nullptr, M, (int)p, q, R, t_pitch, gg, s);
 }
 
@@ -828,7 +875,7 @@ hipError_t launch_chain2_tall_gather_bf16(const void* image, const PatchGeom& g,
     const int cpb = (g.Cin + 63) / 64;
     const int64_t p = (int64_t)g.kh * g.kw * cpb * 64;
     if (!gather_ok(g, M, p, t_pitch, R, 128) || !chain2_tall_supports(R, (int)p, q)) return hipErrorInvalidValue;
-    const Ch2Gather gg{g.H, g.W, g.Cin, cpb, g.kh, g.kw, g.sign};
+    const Ch2Gather gg = device_geom(g);
     return launch_chain_128<true>(one_problem(image, P, Q, Yout, Tout), 1, Yout != nullptr, M, (int)p, q, R, t_pitch, gg, 1, s);
 }
 

@@ -53,7 +53,9 @@ struct Tn2Job { const uint16_t* U; const uint16_t* V; float* part; int P; int ti
 // Gather form of U (jobs with gather != 0): U is a channels-last image [M / (H W), H, W, C] and column
 // tap C + c of row i of the virtual U is channel c of pixel (y + ky - kh/2, x + kx - kw/2) of the
 // same image (tap = ky kw + kx), zero outside it.  job.P = kh kw C.
-struct Tn2Gather { int H, W, C, kh, kw; };
+// Rows are the pixels of a grid RH x RW per image; row (y, x) is centred on image pixel (mul y, mul x)
+// (mul = 1 with RH x RW = H x W: every pixel; mul = 2: the patches of a stride-2 convolution).
+struct Tn2Gather { int H, W, C, kh, kw, RH, RW, mul; };
 struct Tn2Args { Tn2Job job[kTnMaxJobs]; int njobs; int tiles; int splits; int64_t M; int64_t rows_per_split; Tn2Gather g; };
 
 // LDS slab: column-major, 64 batch rows = 128 bytes per column, two columns per 256-byte line.  The
@@ -120,8 +122,18 @@ __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int co
     // can touch (the host keeps that window below 2 GiB).
     int bx[BPT], by[BPT], boff[BPT];
     const int step_x = GATHER ? BKM % tg.W : 0, step_y = GATHER ? (BKM / tg.W) % tg.H : 0;
-    const int64_t sp0 = k_begin > reach ? k_begin - reach : 0;
+    // window of the image the split's patches can touch: [sp0, sp1) in pixels over all images
+    int64_t sp0 = k_begin > reach ? k_begin - reach : 0;
     int64_t sp1 = k_end + reach;
+    if (GATHER && tg.mul != 1 && k_end > k_begin) {
+        auto centre = [&](int64_t i) {     // centre pixel of row i (monotone in i)
+            const int64_t per = (int64_t)tg.RH * tg.RW, img = i / per, rem = i - img * per;
+            return (img * tg.H + tg.mul * (rem / tg.RW)) * tg.W + tg.mul * (rem % tg.RW);
+        };
+        const int64_t c0 = centre(k_begin), c1 = centre(k_end - 1);
+        sp0 = c0 > reach ? c0 - reach : 0;
+        sp1 = c1 + reach + 1;
+    }
     if (sp1 > pixels) sp1 = pixels;
     const rsrc_t gres = make_rsrc(src + sp0 * tg.C, GATHER ? (sp1 - sp0) * tg.C * 2 : 0);
 #pragma unroll
@@ -131,7 +143,39 @@ __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int co
         by[b] = GATHER ? (int)((first / tg.W) % tg.H) : 0;
         boff[b] = (((int)(first - sp0) + gdy * tg.W + gdx) * tg.C + gc) * 2;
     }
+    // Strided rows (mul > 1): the state of a block is the grid position and image of its first row;
+    // offsets are formed per row from the coordinates (a few multiplies per slab), the window of the
+    // descriptor starts at pixel sp0.
+    int sx[BPT], sy[BPT], simg[BPT];
+    const bool strided = GATHER && tg.mul != 1;
+#pragma unroll
+    for (int b = 0; b < BPT; ++b) {
+        const int64_t first = k_begin + 8 * rg0 + 32 * b;
+        sx[b] = strided ? (int)(first % tg.RW) : 0;
+        sy[b] = strided ? (int)((first / tg.RW) % tg.RH) : 0;
+        simg[b] = strided ? (int)(first / ((int64_t)tg.RW * tg.RH)) : 0;
+    }
+    auto load_block_strided = [&](u32x4 (&dst)[8], int s, int b) {
+        int x = sx[b], y = sy[b], img = simg[b];
+        const int left = rows_in_split - (s * BKM + 8 * rg0 + 32 * b);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int ty = tg.mul * y + gdy, tx = tg.mul * x + gdx;
+            const bool ok = colok && e < left && (unsigned)ty < (unsigned)tg.H && (unsigned)tx < (unsigned)tg.W;
+            const int pix = (img * tg.H + ty) * tg.W + tx - (int)sp0;
+            dst[e] = buf_load16(gres, ok ? (pix * tg.C + gc) * 2 : kBufNowhere, 0);
+            if (++x == tg.RW) { x = 0; if (++y == tg.RH) { y = 0; ++img; } }
+        }
+        // advance the block's first row by one slab of 64 rows (64 = qy RW + qx)
+        const int qy = BKM / tg.RW, qx = BKM - qy * tg.RW;
+        int nx = sx[b] + qx, ny = sy[b] + qy;
+        if (nx >= tg.RW) { nx -= tg.RW; ++ny; }
+        simg[b] += ny / tg.RH;
+        sy[b] = ny % tg.RH;
+        sx[b] = nx;
+    };
     auto load_block_gather = [&](u32x4 (&dst)[8], int s, int b) {
+        if (strided) { load_block_strided(dst, s, b); return; }
         const int x = bx[b], y = by[b], off = boff[b];
         // advance to the next slab (this lambda is called once per slab and block, in slab order)
         boff[b] += BKM * tg.C * 2;
@@ -271,7 +315,7 @@ __global__ __launch_bounds__(Tn2<R>::NT) void tn2_bf16_kernel(Tn2Args args) {
         if constexpr (GATHER) {
             if (job.gather) {
                 tn_loader<TP, C::BPT, D, true>(job.U, job.P, job.P - p0, 0, tid - 64 * NMW, k_begin, k_end, np, C::slab, lds,
-                                               args.g, p0, args.M);
+                                               args.g, p0, (args.M / ((int64_t)args.g.RH * args.g.RW)) * args.g.H * args.g.W);
                 return;
             }
         }
@@ -462,21 +506,26 @@ hipError_t launch_tn_bf16(const TnJob* jobs, int njobs, int64_t M, int R, int ac
 
 hipError_t launch_tn_gather_bf16(const TnJob* jobs, int njobs, const PatchGeom& g, int64_t M, int R, int accumulate,
                                  float* partials, hipStream_t s) {
-    // 32-bit offsets inside the window of the image that one slab's patches touch
+    // patches only (no adjoint form here); 32-bit offsets inside the window of the image that one
+    // slab's patches touch
     if (njobs < 1 || njobs > 2 ||
         g.H < 1 || g.W < 1 || g.Cin < 8 || g.Cin % 8 || g.kh < 1 || g.kw < 1 || !(g.kh & 1) || !(g.kw & 1) ||
-        M % ((int64_t)g.H * g.W) != 0 || jobs[njobs - 1].P != g.kh * g.kw * g.Cin ||
+        g.sign != 1 || g.shift != 0 || (g.mul != 1 && g.mul != 2) || g.RH < 1 || g.RW < 1 ||
+        (g.mul == 1 && (g.RH != g.H || g.RW != g.W)) ||
+        M % ((int64_t)g.RH * g.RW) != 0 || (M / ((int64_t)g.RH * g.RW)) * g.H * g.W > 0x7fffffff ||
+        jobs[njobs - 1].P != g.kh * g.kw * g.Cin ||
         ((int64_t)64 + 2 * ((g.kh / 2) * (int64_t)g.W + g.kw / 2)) * g.Cin * 2 >= kBufMaxBytes)
         return hipErrorInvalidValue;
-    // one descriptor per row split: its window of the image (the split's rows, the reach of the
-    // window on both sides, the padded slabs of the loaders' ring) must stay below 2 GiB
+    // one descriptor per row split: its window of the image (the centres of the split's rows, the
+    // reach of the window on both sides, the padded slabs of the loaders' ring) must stay below 2 GiB
     {
         const int splits = tn2_choose_splits(M, tn2_total_tiles(jobs, njobs));
         const int64_t rps = ceil_div(ceil_div(M, splits), 64) * 64;
         const int64_t reach = (g.kh / 2) * (int64_t)g.W + g.kw / 2;
-        if ((rps + 2 * reach + 64 * 8) * g.Cin * 2 >= kBufMaxBytes) return hipErrorInvalidValue;
+        const int64_t span = (int64_t)g.mul * g.mul * (rps + 64 * 8 + g.RW + 2) + 2 * (int64_t)g.mul * g.W;
+        if ((span + 2 * reach) * g.Cin * 2 >= kBufMaxBytes) return hipErrorInvalidValue;
     }
-    const Tn2Gather tg{g.H, g.W, g.Cin, g.kh, g.kw};
+    const Tn2Gather tg{g.H, g.W, g.Cin, g.kh, g.kw, g.RH, g.RW, g.mul};
     return launch_tn_common(jobs, njobs, M, R, accumulate, partials, &tg, s);
 }
 

@@ -182,10 +182,10 @@ def config4_cases():
 
 
 def conv_case(N: int, H: int, W: int, C: int, m: int, r: int, kh: int, kw: int, seed: int,
-              relu_act: bool = True, dy_std: float = 1e-2):
+              relu_act: bool = True, dy_std: float = 1e-2, stride: int = 1):
     """One factored convolution's training-step inputs, channels last, all bf16-representable:
     act N x H x W x C ~ max(0, N(0,1)) (post-ReLU feature map; relu_act=False keeps the Gaussian),
-    dY (N H W) x m ~ N(0, dy_std^2), A m x r ~ N(0, 1/r), B r x (kh kw C) ~ N(0, 1/(kh kw C)),
+    dY (N H' W') x m ~ N(0, dy_std^2) (H' = ceil(H / stride)), A m x r ~ N(0, 1/r), B r x (kh kw C) ~ N(0, 1/(kh kw C)),
     B's columns ordered tap-major: (ky kw + kx) C + c."""
     rng = np.random.default_rng(seed)
     n = kh * kw * C
@@ -194,16 +194,22 @@ def conv_case(N: int, H: int, W: int, C: int, m: int, r: int, kh: int, kw: int, 
     act = gaussian(rng, (N, H, W, C))
     if relu_act:
         np.maximum(act, 0.0, out=act)
-    dy = gaussian(rng, (N * H * W, m), std=dy_std)
+    rows = N * (-(-H // stride)) * (-(-W // stride))      # output pixels: ceil(H / stride) x ceil(W / stride) per image
+    dy = gaussian(rng, (rows, m), std=dy_std)
     a, b, act, dy = (round_to_bf16(t) for t in (a, b, act, dy))
     return {"act": act, "dY": dy, "A": a, "B": b, "N": N, "H": H, "W": W, "C": C, "m": m, "r": r,
-            "kh": kh, "kw": kw}
+            "kh": kh, "kw": kw, "stride": stride}
 
 
 # ResNet-50 3x3 convolutions of config 4 in their native form: (name, N, H, W, C, m, r)
 RESNET50_CONVS_NATIVE = (
     ("conv3x3_256_14", 256, 14, 14, 256, 256, 64),
     ("conv3x3_512_7", 256, 7, 7, 512, 512, 128),
+)
+# down-sampling convolutions of ResNet-50's stage 3 (28 x 28 -> 14 x 14): (name, N, H, W, C, m, r, kh, kw), stride 2
+RESNET50_CONVS_STRIDED = (
+    ("conv3x3_s2_128_28", 256, 28, 28, 128, 128, 64, 3, 3),
+    ("conv1x1_s2_256_512_28", 256, 28, 28, 256, 512, 128, 1, 1),
 )
 
 

@@ -195,7 +195,9 @@ def test_conv_validation_without_device(lib):
                 abt.ConvGeom(0, 14, 14, 256, 3, 3),
                 abt.ConvGeom(2, 14, 14, 256, 17, 3),
                 abt.ConvGeom(2, 14, 14, 1 << 20, 3, 3),         # kh kw C too wide
-                abt.ConvGeom(1 << 31, 14, 14, 64, 3, 3)):       # too many pixels
+                abt.ConvGeom(1 << 31, 14, 14, 64, 3, 3),        # too many pixels
+                abt.ConvGeom(2, 14, 14, 256, 3, 3, 3),          # stride other than 1 or 2
+                abt.ConvGeom(2, 14, 14, 256, 3, 3, 0)):
         assert fwd(bad) == -2
         assert lib.lr_conv_bwd_workspace_bytes(ctypes.byref(bad), 256, 64, BF) == 0
     assert fwd(good, m=100) == -2 and fwd(good, r=48) == -2 and fwd(good, r=224) == -2 and fwd(good, r=416) == -2

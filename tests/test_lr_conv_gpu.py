@@ -35,16 +35,17 @@ def host(t):
 
 def run(c, **bwd_kw):
     act, dY, A, B = (dev(c[k]) for k in ("act", "dY", "A", "B"))
-    Y, T = abt.lr_conv_fwd(act, A, B, c["kh"], c["kw"], save_T=True)
-    dAct, dA, dB = abt.lr_conv_bwd(dY, act, T, A, B, c["kh"], c["kw"], **bwd_kw)
+    Y, T = abt.lr_conv_fwd(act, A, B, c["kh"], c["kw"], save_T=True, stride=c.get("stride", 1))
+    dAct, dA, dB = abt.lr_conv_bwd(dY, act, T, A, B, c["kh"], c["kw"], stride=c.get("stride", 1), **bwd_kw)
     torch.cuda.synchronize()
     return act, dY, A, B, Y, T, dAct, dA, dB
 
 
 def check(c):
     act, dY, A, B, Y, T, dAct, dA, dB = run(c)
-    Yo, To = orc.lr_conv_fwd(c["act"], c["A"], c["B"], c["kh"], c["kw"])
-    dActo, dAo, dBo, _ = orc.lr_conv_bwd(c["dY"], c["act"], c["A"], c["B"], c["kh"], c["kw"])
+    st = c.get("stride", 1)
+    Yo, To = orc.lr_conv_fwd(c["act"], c["A"], c["B"], c["kh"], c["kw"], st)
+    dActo, dAo, dBo, _ = orc.lr_conv_bwd(c["dY"], c["act"], c["A"], c["B"], c["kh"], c["kw"], st)
     errs = {"T": rel(host(T), To), "Y": rel(host(Y), Yo), "dAct": rel(host(dAct), dActo),
             "dA": rel(host(dA), dAo), "dB": rel(host(dB), dBo)}
     assert all(e < TOL for e in errs.values()), errs
@@ -80,6 +81,40 @@ def test_conv_step_with_tall_work_groups(N, H, W, C, m, r, kh, kw):
         check(c)
     finally:
         abt.set_chain_rows(prev)
+
+
+STRIDED = [
+    # N, H, W, C, m, r, kh, kw: stride 2, output grid ceil(H / 2) x ceil(W / 2)
+    (3, 8, 8, 64, 128, 32, 3, 3),      # even sides: 4 x 4 outputs per image, 48 rows
+    (5, 7, 5, 64, 64, 64, 3, 3),       # odd sides: 4 x 3 outputs, the last window hangs over the edge
+    (4, 9, 6, 128, 64, 96, 1, 1),      # 1 x 1, stride 2: the shortcut projection of a down-sampling block
+    (2, 14, 14, 128, 128, 32, 3, 3),   # 98 rows: two row blocks, ragged
+    (9, 6, 10, 64, 64, 128, 5, 3),     # wide window, unequal sides, 135 rows
+    (40, 8, 8, 64, 64, 32, 3, 3),      # 640 rows from 2560 pixels: several splits and row blocks
+]
+
+
+@pytest.mark.parametrize("N,H,W,C,m,r,kh,kw", STRIDED)
+def test_strided_conv_step_against_oracle(N, H, W, C, m, r, kh, kw):
+    c = gen.conv_case(N, H, W, C, m, r, kh, kw, seed=900 + N + H + r, stride=2)
+    check(c)
+
+
+@pytest.mark.parametrize("N,H,W,C,m,r,kh,kw", STRIDED[:4])
+def test_strided_conv_step_with_tall_work_groups(N, H, W, C, m, r, kh, kw):
+    prev = abt.set_chain_rows(128)
+    try:
+        check(gen.conv_case(N, H, W, C, m, r, kh, kw, seed=950 + N + H + r, stride=2))
+    finally:
+        abt.set_chain_rows(prev)
+
+
+def test_resnet50_downsampling_convolutions():
+    """The two strided convolutions of a ResNet-50 down-sampling block (stage 3: 28 x 28 -> 14 x 14), at a
+    batch the oracle's explicit patch matrix still fits: 3 x 3 stride 2 on 128 channels, and the
+    1 x 1 stride 2 shortcut 256 -> 512."""
+    check(gen.conv_case(16, 28, 28, 128, 128, 32, 3, 3, seed=31, stride=2))
+    check(gen.conv_case(16, 28, 28, 256, 512, 128, 1, 1, seed=32, stride=2))
 
 
 def test_conv_equals_linear_layer_on_explicit_patches():
