@@ -117,14 +117,17 @@ struct Ch2Cfg {
     static constexpr int D1 = RG == 1 ? clampi(32 / (NCHX + NCHP), 2, 6) : clampi(30 / (NCHX + NCHP), 2, 4);
     // stage 2: a slab is 128 rows of Q times BK2 = R / KSL columns
     // RG = 2: at most 96 contraction columns per slab beyond R = 128 (LDS: four staging tiles)
-    static constexpr int KSL = RG == 1 ? (R <= 224 ? 1 : 2) : (R <= 128 ? 1 : R / 96);
+    static constexpr int KSL = RG == 1 ? (R <= 224 ? 1 : 2) : (R <= 128 ? 1 : (R <= 192 ? R / 96 : 4));
+    // RG = 2 beyond R = 192: a wave cannot hold 64 rows of T (R / 2 registers of 168).  Each wave then
+    // owns 32 rows of T and two column blocks of the output tile instead of 64 rows and one block.
+    static constexpr bool RSPLIT = RG == 2 && R > 192;
     static constexpr int BK2 = R / KSL, CPR2 = BK2 / 8;
     static constexpr int slab2 = 128 * BK2 * 2;
     static constexpr int NCHQ = 128 * CPR2 / NLT;             // chunks per loader thread = BK2 / 16
     static constexpr int D2 = RG == 1 ? clampi(36 / NCHQ, 2, 6) : clampi(20 / NCHQ, 2, 4);   // stage-2 slabs in flight
     static constexpr int U2 = D2 * KSL / gcdi(D2, KSL);       // stage-2 trip count is padded to a multiple of this
     // operand buffers of an MFMA wave in stage 2 (registers: T takes R / 2 of them, twelve waves leave 168)
-    static constexpr int NB2 = RG == 1 ? (R > 320 ? 2 : 6) : (R > 128 ? 3 : 6);
+    static constexpr int NB2 = RG == 1 ? (R > 320 ? 2 : 6) : (RSPLIT ? 3 : (R > 128 ? 3 : 6));
     static constexpr int ypitch = 128 * 2 + 16;
     static constexpr int ytile = 64 * ypitch;
     static constexpr int red = (C::KS / 2) * C::CS * C::RS * RA * CB * 4096;   // first (largest) round of the tree
@@ -642,14 +645,19 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(Ch2
     if (Yout == nullptr) return;
 
     // Stage 2: wave w4 of a row group owns the group's 64 rows of T (in registers, as MFMA B operands)
-    // and column block w4 (32 columns) of every 128-column output tile.
+    // and column block w4 (32 columns) of every 128-column output tile; in the row-split form, rows
+    // 32 (w4 & 1) .. + 31 of the group and column blocks 2 (w4 >> 1), 2 (w4 >> 1) + 1.
     constexpr int KB = R / 16;
-    u32x4 tf[2][KB];   // T[32a + lj][16kb + 8 lh .. +7]
+    constexpr int TA = L::RSPLIT ? 1 : 2;               // row blocks of T per wave
+    constexpr int QB = L::RSPLIT ? 2 : 1;               // column blocks of the tile per wave
+    const int trow0 = L::RSPLIT ? 32 * (w4 & 1) : 0;
+    const int qrow0 = L::RSPLIT ? 64 * (w4 >> 1) : 32 * w4;
+    u32x4 tf[TA][KB];   // T[trow0 + 32a + lj][16kb + 8 lh .. +7]
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < TA; ++a)
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
-            tf[a][kb] = *reinterpret_cast<const u32x4*>(ttile_g + (32 * a + lj) * L::tpitch + (16 * kb + 8 * lh) * 2);
+            tf[a][kb] = *reinterpret_cast<const u32x4*>(ttile_g + (trow0 + 32 * a + lj) * L::tpitch + (16 * kb + 8 * lh) * 2);
     wg_barrier();                                       // T tile consumed; stage 2 takes over the LDS
     wg_barrier();                                       // Q slab 0 is in slot 0
     // ------------------------------------------------------------------ stage 2
@@ -662,37 +670,48 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(Ch2
     // The swizzle XORs the low XB bits of the chunk index 2 kk + lh with row bits, and a row starts
     // at a multiple of 16 << XB bytes (BK2 is a multiple of 8 << XB elements), so the address
     // of step kk is that of step 0 with (kk mod PER) << 5 XORed in, plus a constant for kk / PER:
-    // one lane address serves all steps.
+    // one lane address serves all steps (and all column blocks: 32 rows on leave the row bits alone).
     constexpr int XB = CPR2 % 16 == 0 ? 4 : (CPR2 % 8 == 0 ? 3 : 2);
     constexpr int PER = (1 << XB) / 2;
     static_assert((BK2 * 2) % (16 << XB) == 0, "row pitch and swizzle width");
-    const int qaddr0 = (32 * w4 + lj) * (BK2 * 2) + swz<CPR2>(lh, 32 * w4 + lj) * 16;
-    auto read2 = [&](u32x4& dst, int s, int kk) {
-        dst = *reinterpret_cast<const u32x4*>(lds + (s & 1) * L::slab2 + (qaddr0 ^ ((kk % PER) << 5)) + (kk / PER) * (16 << XB));
+    const int qaddr0 = (qrow0 + lj) * (BK2 * 2) + swz<CPR2>(lh, qrow0 + lj) * 16;
+    struct Ops2 { u32x4 qf[QB]; };
+    auto read2 = [&](Ops2& dst, int s, int kk) {
+#pragma unroll
+        for (int b = 0; b < QB; ++b)
+            dst.qf[b] = *reinterpret_cast<const u32x4*>(lds + (s & 1) * L::slab2 + (qaddr0 ^ ((kk % PER) << 5)) +
+                                                       (kk / PER) * (16 << XB) + b * 32 * (BK2 * 2));
     };
-    f32x16 acc2[2];
-    u32x4 ring[NB];
-    auto mma2 = [&](const u32x4& qf, int kb) {
-        acc2[0] = mfma16(qf, tf[0][kb], acc2[0]);
-        acc2[1] = mfma16(qf, tf[1][kb], acc2[1]);
+    f32x16 acc2[TA][QB];
+    Ops2 ring[NB];
+    auto mma2 = [&](const Ops2& o, int kb) {
+#pragma unroll
+        for (int a = 0; a < TA; ++a)
+#pragma unroll
+            for (int b = 0; b < QB; ++b) acc2[a][b] = mfma16(o.qf[b], tf[a][kb], acc2[a][b]);
     };
     auto stage_out = [&](int t) {
-        // lane holds Y[32a + lj][32 wave + 8g + 4 lh + (0..3)] of this 64 x 128 tile
+        // lane holds Y[trow0 + 32a + lj][qrow0 + 32b + 8g + 4 lh + (0..3)] of its group's 64 x 128 tile
         unsigned char* yt = ytile + (grp * 2 + (t & 1)) * L::ytile;
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < TA; ++a)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                u32x2 o = {pack2_bf16(acc2[a][4 * g + 0], acc2[a][4 * g + 1]),
-                           pack2_bf16(acc2[a][4 * g + 2], acc2[a][4 * g + 3])};
-                *reinterpret_cast<u32x2*>(yt + (32 * a + lj) * L::ypitch + (32 * w4 + 8 * g + 4 * lh) * 2) = o;
-            }
+            for (int b = 0; b < QB; ++b)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    u32x2 o = {pack2_bf16(acc2[a][b][4 * g + 0], acc2[a][b][4 * g + 1]),
+                               pack2_bf16(acc2[a][b][4 * g + 2], acc2[a][b][4 * g + 3])};
+                    *reinterpret_cast<u32x2*>(yt + (trow0 + 32 * a + lj) * L::ypitch +
+                                              (qrow0 + 32 * b + 8 * g + 4 * lh) * 2) = o;
+                }
     };
     auto clear2 = [&]() {
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < TA; ++a)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc2[a][v] = 0.0f;
+            for (int b = 0; b < QB; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc2[a][b][v] = 0.0f;
     };
     clear2();
     for (int s0 = 0; s0 < n2p; s0 += KSL) {
@@ -799,7 +818,7 @@ hipError_t launch_chain_128(const Ch2Ptrs& ptrs, int G, bool second_stage,
                             int64_t M, int p, int q, int R, int t_pitch, const Ch2Gather& gg, int parts, hipStream_t s) {
     switch (R) {
 #define ABT_CASE(RR) case RR: return launch_chain_r<RR, 2, GATHER>(ptrs, G, second_stage, M, p, q, t_pitch, gg, parts, s);
-        ABT_CASE(32) ABT_CASE(64) ABT_CASE(96) ABT_CASE(128) ABT_CASE(192)
+        ABT_CASE(32) ABT_CASE(64) ABT_CASE(96) ABT_CASE(128) ABT_CASE(192) ABT_CASE(384)
 #undef ABT_CASE
         default: return hipErrorInvalidValue;
     }
@@ -846,8 +865,8 @@ bool chain2_supports(int R, int p, int q) {
 bool chain2_tall_supports(int R, int p, int q) {
     if (p % 64 != 0 || p > (1 << 20) || q > (1 << 20)) return false;
     switch (R) {
-        case 32: case 64: case 96: case 128: case 192: return true;
-        default: return false;
+        case 32: case 64: case 96: case 128: case 192: case 384: return true;
+        default: return chain3_supports(R, p, q);
     }
 }
 
@@ -858,6 +877,10 @@ hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, voi
 
 hipError_t launch_chain2_tall_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                               int64_t M, int p, int q, int R, int parts, hipStream_t s) {
+    if (chain3_supports(R, p, q)) {                     // wide ranks: the kernel of eight equal waves
+        const ChainProblem one{Xin, P, Q, Yout, Tout};
+        return launch_chain3_bf16(&one, 1, M, p, q, R, parts, s);
+    }
     return launch_chain_128<false>(one_problem(Xin, P, Q, Yout, Tout), 1, Yout != nullptr, M, p, q, R, R, Ch2Gather{}, parts, s);
 }
 
@@ -874,7 +897,7 @@ hipError_t launch_chain2_tall_gather_bf16(const void* image, const PatchGeom& g,
                                      void* Yout, void* Tout, int t_pitch, int64_t M, int q, int R, hipStream_t s) {
     const int cpb = (g.Cin + 63) / 64;
     const int64_t p = (int64_t)g.kh * g.kw * cpb * 64;
-    if (!gather_ok(g, M, p, t_pitch, R, 128) || !chain2_tall_supports(R, (int)p, q)) return hipErrorInvalidValue;
+    if (!gather_ok(g, M, p, t_pitch, R, 128) || !chain2_tall_supports(R, (int)p, q) || R == 256) return hipErrorInvalidValue;
     const Ch2Gather gg = device_geom(g);
     return launch_chain_128<true>(one_problem(image, P, Q, Yout, Tout), 1, Yout != nullptr, M, (int)p, q, R, t_pitch, gg, 1, s);
 }
@@ -882,6 +905,7 @@ hipError_t launch_chain2_tall_gather_bf16(const void* image, const PatchGeom& g,
 hipError_t launch_chain2_grouped_bf16(const ChainProblem* problems, int G, int64_t M, int p, int q, int R,
                                       int rows, int parts, hipStream_t s) {
     if (G < 1 || G > kChainMaxGroups || !problems) return hipErrorInvalidValue;
+    if (rows == 128 && chain3_supports(R, p, q)) return launch_chain3_bf16(problems, G, M, p, q, R, parts, s);
     Ch2Ptrs t{};
     const bool second_stage = problems[0].Yout != nullptr;
     for (int g = 0; g < G; ++g) {

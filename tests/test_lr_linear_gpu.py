@@ -304,7 +304,7 @@ def tall_chain():
     abt.set_chain_rows(prev)
 
 
-@pytest.mark.parametrize("r", [32, 64, 96, 128, 192])
+@pytest.mark.parametrize("r", [32, 64, 96, 128, 192, 256, 384])
 @pytest.mark.parametrize("M", [1, 64, 129, 1000])
 def test_bf16_tall_work_groups(tall_chain, M, r):
     # forced on small batches so that the oracle can check every element: one row, one row group,
@@ -314,7 +314,7 @@ def test_bf16_tall_work_groups(tall_chain, M, r):
 
 
 @pytest.mark.parametrize("parts", [2, 3, 8])
-@pytest.mark.parametrize("M,r", [(129, 192), (1000, 96), (300, 32)])
+@pytest.mark.parametrize("M,r", [(129, 192), (1000, 96), (300, 32), (200, 384), (257, 256)])
 def test_bf16_tall_work_groups_with_column_parts(tall_chain, M, r, parts):
     # several work-groups per row block, each doing a share of the output tiles (m = 448: four
     # tiles, the last ragged; 8 parts are capped to 4)
