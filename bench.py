@@ -33,10 +33,10 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 CACHE_BYTES = 256 << 20     # last-level cache: a rotated working set must exceed it
 # HBM bytes of one launch of the dominant kernel (forward chain of fc1 at r = 384, M = 50432) from two
-# rocprofv3 --pmc runs of `bench.py --only-launch fc1_r384 --pmc-copy` (profiles/chain2_fwd_pmc_counters.txt):
-# FETCH_SIZE 138307.9 KiB x 2.00 (the factor that makes a plain 256 MiB copy read 256 MiB) + WRITE_SIZE
-# 340416 KiB x 1.00.  A stored measurement: re-collect it when the kernel changes.
-DOMINANT_TRAFFIC_BYTES = int((138307.9 * 2.0 + 340416.0) * 1024)
+# rocprofv3 --pmc runs of `bench.py --only-launch fc1_r384 --pmc-copy` (profiles/chain_fwd_pmc_counters.txt,
+# second table): FETCH_SIZE 98020.3 KiB x 2.00 (the factor that makes a plain 256 MiB copy read 256 MiB)
+# + WRITE_SIZE 340416 KiB x 1.00.  A stored measurement: re-collect it when the kernel changes.
+DOMINANT_TRAFFIC_BYTES = int((98020.3 * 2.0 + 340416.0) * 1024)
 
 
 def main():
@@ -275,15 +275,15 @@ def main():
         dom_flops = 2.0 * dom.M * dom.r * (dom.m + dom.n)
         achieved = dom_flops / (dom_avg * 1e-3) / 1e12
         roofline = {
-            "kernel": "chain2_bf16_kernel<384, 1, false> (lr_linear_fwd of fc1 at r = 384, M = 50432: "
+            "kernel": "chain3_bf16_kernel<384> (lr_linear_fwd of fc1 at r = 384, M = 50432: "
                       "T = X B^T and Y = T A^T fused, one launch per call)",
             "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": DOMINANT_TRAFFIC_BYTES,
-        "traffic_source": "stored measurement, not live: profiles/chain2_fwd_pmc_counters.txt",
+        "traffic_source": "stored measurement, not live: profiles/chain_fwd_pmc_counters.txt",
             "algorithmic_flops_per_launch": dom_flops, "algorithmic_bytes_per_launch": dom.bytes_fwd,
             "avg_launch_ms": round(dom_avg, 5),
             "hbm_frac": round(dom.bytes_fwd / (dom_avg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-            "profile": "profiles/chain2_r384_cfg3_fc1_kernel_trace.txt",
+            "profile": "profiles/chain3_r384_cfg3_fc1_kernel_trace.txt",
         }
 
         out = {

@@ -27,8 +27,8 @@
 //   them and holds the last step of a slab back across the barrier (a lone MFMA wave per SIMD has
 //   nobody to hide its LDS latency behind: with reads issued step by step the loop time was about
 //   three times the MFMA time).
-// (The direct-to-LDS loads of gfx950 were measured at about half the rate of register-staged
-// loads per wave and are not used.)
+// (The direct-to-LDS loads of gfx950 give one wave no more than register-staged loads do and are
+// not used here; the kernel of eight equal waves in lr_chain3.hip is built on them.)
 //
 // LDS slab layout: row-major, 16-byte chunks XOR-swizzled inside each row so that the 16 rows a
 // quarter-wave reads for one MFMA operand fall on different banks.
@@ -48,6 +48,9 @@
 // often needs fewer rounds.  Twelve waves leave 168 registers per lane, so the register rings are
 // shallower and a stage-2 slab holds at most 96 contraction columns (two slabs per output tile for
 // R = 192), which also keeps four staging tiles plus two slab slots inside the 160 KB of LDS.
+// At R = 384 a wave cannot hold 64 rows of T (192 registers): stage 2 is then split by rows, a wave
+// owning 32 rows of T and two 32-column blocks of the output tile (every Q operand read from LDS
+// feeds one MFMA instead of two).
 #include <atomic>
 #include <type_traits>
 

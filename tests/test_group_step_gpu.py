@@ -246,6 +246,21 @@ def test_reconstruct(m, n, k):
                                           (torch.float32, (150, 70, 50, 12))],
                          ids=["bf16-r64", "bf16-r192", "fp32"])
 def test_grouped_step_matches_the_oracle_and_the_single_group_calls(dtype, shape):
+    grouped_step_check(dtype, shape)
+
+
+@pytest.mark.parametrize("r", [256, 384])
+def test_grouped_step_wide_rank_128_row_work_groups(r):
+    # the kernel of eight equal waves (plain 128-row launches at r = 256, 384), four groups per launch,
+    # a ragged last row block and a ragged last output tile
+    prev = abt.set_chain_rows(128)
+    try:
+        grouped_step_check(torch.bfloat16, (700, 320, 192, r))
+    finally:
+        abt.set_chain_rows(prev)
+
+
+def grouped_step_check(dtype, shape):
     """Four groups of one shape, each with its own batch and its own factors, two training A and two
     training B (one of the B groups without dX, one A group without a saved T): one grouped forward
     and one grouped backward against the oracle, element by element, and against the single-group

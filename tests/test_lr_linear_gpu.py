@@ -338,6 +338,14 @@ def test_bf16_last_round_shared_by_output_tiles(M):
         abt.set_chain_rows(prev)
 
 
+@pytest.mark.parametrize("r", [256, 384])
+def test_bf16_wide_rank_last_round_shared_by_output_tiles(tall_chain, r):
+    # 259 row blocks of 128 rows: the three of the last round are split four ways by output tiles
+    # (m = 512: four tiles) in the kernel of eight equal waves; the last block is ragged
+    c = gen.lr_case(M=128 * 258 + 17, m=512, n=64, r=r, seed=7400 + r)
+    check_full(c, torch.bfloat16, TOL_BF16)
+
+
 def test_bf16_tall_work_groups_chosen_for_large_batches():
     # above one round of 64-row work-groups the library picks the 128-row kernel by itself; the
     # result must agree with the 64-row kernel's up to summation order, and with the oracle on samples
