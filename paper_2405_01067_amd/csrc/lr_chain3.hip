@@ -5,26 +5,30 @@
 // registers next to two other waves on its SIMD, and four loader waves cannot put a factor slab
 // into LDS as fast as the MFMA waves use it up.
 //
-// Here all eight waves of a work-group (two per SIMD, 256 registers each) do the same work:
-//   * every wave brings in its eighth of each slab with buffer loads that write straight to LDS
-//     (16 bytes per lane, no registers): a wave's load instruction fills 1 KB of the slab, and the
-//     XOR swizzle of the slab layout is applied on the source side (lane l fetches the chunk
-//     that belongs at LDS position l).  Rows past the end of an operand are outside the buffer
-//     descriptor and arrive as zeros.  Loads run one slab ahead; a wave waits for its own loads
-//     before the barrier that ends a slab, which makes the next slab visible to all.
+// Here all eight waves of a work-group (two per SIMD, 256 registers each) do the same matrix work:
+//   * slabs come in by buffer loads that write straight to LDS (16 bytes per lane, no registers: lane
+//     l's data lands at the instruction's LDS base + 16 l, lanes outside the buffer descriptor write
+//     zeros): an instruction fills 1 KB of a slab, and the XOR swizzle of the slab layout is applied
+//     on the source side (lane l fetches the chunk that belongs at LDS position l).  A wave waits for
+//     its own loads before the barrier that ends a slab, which makes the next slab visible to all.
 //   * stage 1: slabs of 64 contraction columns (128 rows of Xin, R rows of P); wave (h, c) owns
-//     rows 64h.. and columns (R/4)c.. of T in accumulators.
+//     rows 64h.. and columns (R/4)c.. of T in accumulators.  Waves 0 and 1 load the Xin parts, three
+//     slabs ahead (HBM latency) into four slots; waves 2..7 the P parts, one slab ahead into two.
 //   * T: rounded to bf16 once, written as a 128 x R tile to LDS (and from there to Tout); every
 //     wave then loads 32 rows of it as MFMA operands, which stay in registers for all of stage 2.
-//   * stage 2: slabs of 128 rows of Q x 128 contraction columns; wave (b, c) owns rows 32b.. and
-//     columns 64c.. of each 128 x 128 output tile: every Q operand read from LDS feeds one MFMA,
-//     every T operand is already in registers.  A finished tile is staged in LDS (two buffers)
-//     and leaves one slab later as full 256-byte row segments, four pieces per thread.
+//   * stage 2: slabs of 128 rows of Q x 128 contraction columns, one slab ahead, every wave loading an
+//     eighth; wave (b, c) owns rows 32b.. and columns 64c.. of each 128 x 128 output tile: every Q
+//     operand read from LDS feeds one MFMA, every T operand is already in registers.  A finished
+//     tile is rounded at once, staged in LDS piece by piece during the next slab (two buffers)
+//     and leaves during the slab after that as full 256-byte row segments, four pieces per thread.
 //   In both stages a wave keeps several operand reads in flight and holds the last step of a slab
 //   back across the barrier, as the MFMA waves of the other chain kernel do.
 //
 // Measured on the stage-2 loop alone (factor resident in L2): 1.45 thousand cycles per slab against
-// 1.02 thousand of MFMA time; the same loop with register-staged loads and LDS stores: 1.75.
+// 1.02 thousand of MFMA time (1.14 without the loads); the same loop with register-staged loads and
+// LDS stores: 1.75.  In the whole kernel a stage-2 tile (three slabs) takes 6.0 thousand cycles and
+// a stage-1 slab 2.6 thousand (1.5 of MFMA time): the older wave of each SIMD reaches the barrier
+// 800 - 1100 cycles before the younger one.
 #include <atomic>
 
 #include "common.h"
