@@ -60,6 +60,18 @@ __device__ __forceinline__ void buf_store16(u32x4 v, rsrc_t r, int lane_off, int
     __builtin_amdgcn_raw_buffer_store_b128(v, r, lane_off, wave_off, 0);
 }
 
+// The same accesses with the non-temporal hint, for data that a kernel touches once (activations in,
+// results out): such lines should not push the factors, which every work-group re-reads, out of L2.
+#ifndef ABT_STREAM_HINT
+#define ABT_STREAM_HINT 2
+#endif
+__device__ __forceinline__ u32x4 buf_load16_stream(rsrc_t r, int lane_off, int wave_off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, wave_off, ABT_STREAM_HINT);
+}
+__device__ __forceinline__ void buf_store16_stream(u32x4 v, rsrc_t r, int lane_off, int wave_off) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, lane_off, wave_off, ABT_STREAM_HINT);
+}
+
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

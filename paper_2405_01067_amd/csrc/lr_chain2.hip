@@ -331,7 +331,7 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(Ch2
                 for (int e = 0; e < L::NCHX; ++e) {
                     int vo, xo;
                     xaddr(e, vs, vo, xo);
-                    dst[e] = buf_load16(xres, vo, xo);
+                    dst[e] = buf_load16_stream(xres, vo, xo);
                 }
 #pragma unroll
                 for (int e = 0; e < L::NCHP; ++e) dst[L::NCHX + e] = buf_load16(pres, psrc, so + e * pstep);
@@ -355,7 +355,7 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(Ch2
                     int vo, xo;
                     xaddr(e, vs, vo, xo);
                     *reinterpret_cast<u32x4*>(lds + slot * L::slab1 + off[e]) = rg[e];
-                    rg[e] = buf_load16(xres, vo, xo);
+                    rg[e] = buf_load16_stream(xres, vo, xo);
                     __builtin_amdgcn_sched_barrier(0);
                 }
 #pragma unroll
@@ -413,7 +413,7 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(Ch2
             constexpr int CPT = R / 8;   // 16-byte chunks per T row
             for (int i = lt; i < ROWS * CPT; i += NLT) {
                 const int row = i / CPT, ch = i % CPT;
-                buf_store16(*reinterpret_cast<const u32x4*>(ttile + (row >> 6) * L::ttile + (row & 63) * L::tpitch + ch * 16),
+                buf_store16_stream(*reinterpret_cast<const u32x4*>(ttile + (row >> 6) * L::ttile + (row & 63) * L::tpitch + ch * 16),
                             tres, (row * t_pitch + ch * 8) * 2, 0);
             }
         }
@@ -450,7 +450,7 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(Ch2
         auto flush_store = [&](int seq, int e) {
             const int t = tile_of(seq);
             const bool whole = q - t * 128 >= 128;
-            if (whole || yleft[e]) buf_store16(ypiece[e], yres, ydst[e], t * 256);
+            if (whole || yleft[e]) buf_store16_stream(ypiece[e], yres, ydst[e], t * 256);
         };
         auto step2 = [&](u32x4 (&rg)[L::NCHQ], int s, bool flush, int seq) {
             const int slot = (s + 1) & 1;

@@ -53,6 +53,10 @@ __device__ __forceinline__ void wait_loads3() {
 __device__ __forceinline__ void dma16(rsrc_t r, unsigned char* dst, int lane_off, int wave_off) {
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void*)dst, 16, lane_off, wave_off, 0, 0);
 }
+// the same with the non-temporal hint (activations: read once)
+__device__ __forceinline__ void dma16_stream(rsrc_t r, unsigned char* dst, int lane_off, int wave_off) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void*)dst, 16, lane_off, wave_off, 0, ABT_STREAM_HINT);
+}
 
 constexpr int largest_divisor3(int n, int most) { return most <= 1 ? 1 : (n % most == 0 ? most : largest_divisor3(n, most - 1)); }
 
@@ -153,7 +157,7 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
         unsigned char* dst = lds + (s & (L::NXB - 1)) * L::xpart + i0 * 1024;
         const int so = slab1_of(s) * (BK1 * 2);
 #pragma unroll
-        for (int j = 0; j < L::NI1X; ++j) dma16(xres, dst + j * (L::NXW * 1024), v1 + j * (8 * L::NXW) * p * 2, so);
+        for (int j = 0; j < L::NI1X; ++j) dma16_stream(xres, dst + j * (L::NXW * 1024), v1 + j * (8 * L::NXW) * p * 2, so);
     };
     auto issue1p = [&](int s) {
         unsigned char* dst = lds + L::NXB * L::xpart + (s & 1) * L::ppart + i0 * 1024;
@@ -274,7 +278,7 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
         constexpr int CPT = R / 8;                      // 16-byte chunks per T row
         for (int i = tid; i < ROWS * CPT; i += L::NT) {
             const int row = i / CPT, ch = i % CPT;
-            buf_store16(*reinterpret_cast<const u32x4*>(ttile + row * L::tpitch + ch * 16), tres, (row * R + ch * 8) * 2, 0);
+            buf_store16_stream(*reinterpret_cast<const u32x4*>(ttile + row * L::tpitch + ch * 16), tres, (row * R + ch * 8) * 2, 0);
         }
     }
     if (Yout == nullptr) return;
@@ -343,7 +347,7 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
         for (int e = 0; e < 4; ++e) {
             const int i = e * L::NT + tid;
             // always four store instructions per wave (the slab's wait counts them); pieces past a ragged tile go nowhere
-            buf_store16(piece[e], yres, whole || (i & 15) < 8 ? ((i >> 4) * q + (i & 15) * 8) * 2 : kBufNowhere, t * 256);
+            buf_store16_stream(piece[e], yres, whole || (i & 15) < 8 ? ((i >> 4) * q + (i & 15) * 8) * 2 : kBufNowhere, t * 256);
         }
     };
     clear2();

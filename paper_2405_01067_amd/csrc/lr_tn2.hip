@@ -73,7 +73,8 @@ __device__ __forceinline__ int slab_addr(int col, int unit) {
 // Loader role: moves NCOLS columns (multiple of 8) of a row-major bf16 matrix, 64 batch rows at a
 // time, into LDS columns [col0, col0 + NCOLS) transposed: a thread loads an 8 x 8 block as eight
 // 16-byte row pieces, transposes it in registers, and stores eight 16-byte column pieces.
-template <int NCOLS, int BPT, int D, bool GATHER = false>
+// STREAM: the source is read once by the whole launch (the U strips): loads carry the non-temporal hint.
+template <int NCOLS, int BPT, int D, bool GATHER = false, bool STREAM = false>
 __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int cols_valid, int col0, int lt,
                                           int64_t k_begin, int64_t k_end, int np, int slab_bytes,
                                           unsigned char* lds, const Tn2Gather tg = Tn2Gather{}, int vcol0 = 0,
@@ -103,7 +104,8 @@ __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int co
     };
     auto load_block = [&](u32x4 (&dst)[8], rsrc_t res, int b) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) dst[e] = buf_load16(res, goff[e] + b * gstep, 0);
+        for (int e = 0; e < 8; ++e)
+            dst[e] = STREAM ? buf_load16_stream(res, goff[e] + b * gstep, 0) : buf_load16(res, goff[e] + b * gstep, 0);
     };
     // gather: this thread's eight virtual columns lie in one tap (C is a multiple of 8)
     const bool colok = active && cc * 8 < cols_valid;
@@ -319,7 +321,7 @@ __global__ __launch_bounds__(Tn2<R>::NT) void tn2_bf16_kernel(Tn2Args args) {
                 return;
             }
         }
-        tn_loader<TP, C::BPT, D>(job.U + p0, job.P, job.P - p0, 0, tid - 64 * NMW, k_begin, k_end, np, C::slab, lds);
+        tn_loader<TP, C::BPT, D, false, true>(job.U + p0, job.P, job.P - p0, 0, tid - 64 * NMW, k_begin, k_end, np, C::slab, lds);
         return;
     }
 
