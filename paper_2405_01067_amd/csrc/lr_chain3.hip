@@ -75,7 +75,7 @@ struct Ch3Cfg {
     static constexpr int slab2 = 128 * BK2 * 2;
     static constexpr int NI2 = slab2 / 1024 / NW;             // 4
     static constexpr int NS = BK2 / 16;                       // k16 steps per stage-2 slab
-    static constexpr int NB = largest_divisor3(NS, 4);        // operand buffers of a wave in stage 2
+    static constexpr int NB = largest_divisor3(NS, 2);        // operand buffers of a wave in stage 2 (deeper rings measured slower)
     static constexpr int ypitch = 128 * 2 + 16;
     static constexpr int ytile = ROWS * ypitch;
     static constexpr int tpitch = R * 2 + 16;
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
             for (int v = 0; v < 16; ++v) acc1[a][b][v] = 0.0f;
     struct Ops1 { u32x4 xf[2]; u32x4 pf[CB]; };
     constexpr int SPW = BK1 / 16;                       // 4 steps per slab
-    constexpr int NB1 = SPW;                            // operand buffers: a slab's reads are all issued at its start
+    constexpr int NB1 = 2;                              // operand buffers (divides SPW: the held step sits in the last one)
     Ops1 ob[NB1];
     auto read1 = [&](Ops1& o, int s, int kk) {
         const unsigned char* xb = lds + (s & (L::NXB - 1)) * L::xpart;
@@ -452,7 +452,11 @@ hipError_t launch_chain3_r(const Ch3Ptrs& ptrs, int G, bool second_stage, int64_
 
 bool chain3_supports(int R, int p, int q) {
     if (p % 64 != 0 || p < 64 || q < 64 || q % 64 != 0 || p > (1 << 20) || q > (1 << 20)) return false;
+#ifdef ABT_NO_CHAIN3_384
+    return R == 256;
+#else
     return R == 256 || R == 384;
+#endif
 }
 
 hipError_t launch_chain3_bf16(const ChainProblem* problems, int G, int64_t M, int p, int q, int R, int parts, hipStream_t s) {
