@@ -307,6 +307,12 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
         acc2[0] = mfma3(o.qf[0], tf[kb], acc2[0]);
         acc2[1] = mfma3(o.qf[1], tf[kb], acc2[1]);
     };
+    // first step of a tile: the accumulators start from a zero operand instead of being cleared
+    auto mma2_first = [&](const Ops2& o, int kb) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        acc2[0] = mfma3(o.qf[0], tf[kb], zero);
+        acc2[1] = mfma3(o.qf[1], tf[kb], zero);
+    };
     // A finished tile is rounded to bf16 right away (16 registers) and written to its staging buffer
     // piece by piece between the steps of the slab that follows, instead of all at once while the
     // matrix cores of this wave's SIMD wait: lane holds Y[trow0 + lj][qrow0 + 32b + 8g + 4 lh + (0..3)].
@@ -323,12 +329,6 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
         const int b = i >> 2, g = i & 3;
         unsigned char* yt = ytile + (t & 1) * L::ytile;
         *reinterpret_cast<u32x2*>(yt + (trow0 + lj) * L::ypitch + (qrow0 + 32 * b + 8 * g + 4 * lh) * 2) = packed[b][g];
-    };
-    auto clear2 = [&]() {
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc2[b][v] = 0.0f;
     };
     // a staged tile leaves as 2048 pieces of 16 bytes, four per thread: piece i = row i / 16, chunk i % 16
     u32x4 piece[4];
@@ -350,7 +350,6 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
             buf_store16_stream(piece[e], yres, whole || (i & 15) < 8 ? ((i >> 4) * q + (i & 15) * 8) * 2 : kBufNowhere, t * 256);
         }
     };
-    clear2();
     int flushed = 0;
     for (int s0 = 0; s0 < ns2; s0 += KSL) {
         const int t = s0 / KSL;
@@ -369,17 +368,15 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
             if (s > 0) {
                 // last step of the slab before this one
                 mma2(ring[NB - 1], ((kp + KSL - 1) % KSL) * NS + NS - 1);
-                if (kp == 0) {
-                    pack_out();
-                    clear2();
-                }
+                if (kp == 0) pack_out();
             }
             __builtin_amdgcn_sched_barrier(0);
             read2(ring[NB - 1], s, NB - 1);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int kk = 0; kk + 1 < NS; ++kk) {
-                mma2(ring[kk % NB], kp * NS + kk);
+                if (kp == 0 && kk == 0) mma2_first(ring[0], 0);
+                else mma2(ring[kk % NB], kp * NS + kk);
                 __builtin_amdgcn_sched_barrier(0);
                 if (kk + NB < NS) read2(ring[kk % NB], s, kk + NB);
                 if (stage_now) {
