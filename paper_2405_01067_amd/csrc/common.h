@@ -93,7 +93,7 @@ hipError_t launch_chain2_bf16(const void* Xin, const void* P, const void* Q, voi
 bool chain2_tall_supports(int R, int p, int q);
 hipError_t launch_chain2_tall_bf16(const void* Xin, const void* P, const void* Q, void* Yout, void* Tout,
                               int64_t M, int p, int q, int R, int parts, hipStream_t s);
-// (For R = 256 and 384 the plain 128-row launches go to the kernel of eight equal waves below; the
+// (For R = 192, 256 and 384 the plain 128-row launches go to the kernel of eight equal waves below; the
 // gathered form has 128-row work-groups for R in {32, 64, 96, 128, 192, 384}.)
 // Up to kChainMaxGroups problems of one shape in one launch (the emulated groups of a training step).
 // rows = 64 or 128 (work-group height; the caller has checked chain2_supports / chain2_tall_supports);
@@ -102,7 +102,7 @@ constexpr int kChainMaxGroups = 8;
 struct ChainProblem { const void* Xin; const void* P; const void* Q; void* Yout; void* Tout; };
 hipError_t launch_chain2_grouped_bf16(const ChainProblem* problems, int G, int64_t M, int p, int q, int R,
                                       int rows, int parts, hipStream_t s);
-// The same chain for R = 256, 384 with 128-row work-groups of eight equal waves, slabs loaded
+// The same chain for R = 192, 256, 384 with 128-row work-groups of eight equal waves, slabs loaded
 // straight into LDS; p, q multiples of 64, at most 2^20; `parts` as above; groups as above.
 bool chain3_supports(int R, int p, int q);
 hipError_t launch_chain3_bf16(const ChainProblem* problems, int G, int64_t M, int p, int q, int R, int parts, hipStream_t s);

@@ -1,4 +1,4 @@
-// Chain kernel for wide ranks and large batches (R = 256, 384; 128-row work-groups):
+// Chain kernel for wide ranks and large batches (R = 192, 256, 384; 128-row work-groups):
 //   Tout[M,R] = Xin[M,p] . P[R,p]^T  then  Yout[M,q] = Tout . Q[q,R]^T      (bf16 in, fp32 accumulate)
 // the same contract as the 64-row / 128-row chain kernel with its two roles of waves, for the
 // shapes where that one is held back by its loaders: at R = 384 a wave cannot keep 64 rows of T in
@@ -12,12 +12,12 @@
 //     on the source side (lane l fetches the chunk that belongs at LDS position l).  A wave waits for
 //     its own loads before the barrier that ends a slab, which makes the next slab visible to all.
 //   * stage 1: slabs of 64 contraction columns (128 rows of Xin, R rows of P); wave (h, c) owns
-//     rows 64h.. and columns (R/4)c.. of T in accumulators.  Waves 0 and 1 load the Xin parts, three
+//     rows 64h.. and columns (R/4)c.. of T in accumulators (R = 192: rows 32h.., columns 96c..).  Waves 0 and 1 load the Xin parts, three
 //     slabs ahead (HBM latency) into four slots; waves 2..7 the P parts, one slab ahead into two.
 //   * T: rounded to bf16 once, written as a 128 x R tile to LDS (and from there to Tout); every
 //     wave then loads 32 rows of it as MFMA operands, which stay in registers for all of stage 2.
-//   * stage 2: slabs of 128 rows of Q x 128 contraction columns, one slab ahead, every wave loading an
-//     eighth; wave (b, c) owns rows 32b.. and columns 64c.. of each 128 x 128 output tile: every Q
+//   * stage 2: slabs of 128 rows of Q x 128 contraction columns (64 at R = 192), one slab ahead, every
+//     wave loading an eighth; wave (b, c) owns rows 32b.. and columns 64c.. of each 128 x 128 output tile: every Q
 //     operand read from LDS feeds one MFMA, every T operand is already in registers.  A finished
 //     tile is rounded at once, staged in LDS piece by piece during the next slab (two buffers)
 //     and leaves during the slab after that as full 256-byte row segments, four pieces per thread.
@@ -64,16 +64,23 @@ template <int R>
 struct Ch3Cfg {
     static constexpr int ROWS = 128, NW = 8, NT = 64 * NW;
     static constexpr int BK1 = 64;                            // stage-1 slab: 64 contraction columns, 8 chunks per row
-    static constexpr int CB = R / 128;                        // 32-column blocks of T per wave in stage 1
+    // stage-1 split of the 128 x R tile of T over the eight waves: two row halves x four column
+    // quarters when a quarter is whole 32-column blocks (R a multiple of 128), else four row blocks
+    // of 32 x two column halves
+    static constexpr int RA = R % 128 == 0 ? 2 : 1;           // 32-row blocks of T per wave
+    static constexpr int CG = RA == 2 ? 4 : 2;                // column groups
+    static constexpr int CB = R / 32 / CG;                    // 32-column blocks of T per wave
     static constexpr int xpart = ROWS * BK1 * 2;              // Xin part of a stage-1 slab: 16 KB, NXB slots
     static constexpr int ppart = R * BK1 * 2;                 // P part: two slots
     static constexpr int NXB = 4, LX = NXB - 1;               // Xin comes from HBM: its loads run LX slabs ahead
     static constexpr int NXW = 2;                             // waves that load Xin; the other six load P
     static constexpr int NI1X = xpart / 1024 / NXW;           // load instructions per slab of an Xin wave (8)
     static constexpr int NI1P = (R / 8 + NW - NXW - 1) / (NW - NXW);   // of a P wave (at most)
-    static constexpr int BK2 = 128, KSL = R / BK2;            // stage-2 slab: 128 rows of Q x 128 columns, 16 chunks per row
+    // stage-2 slab: 128 rows of Q x BK2 contraction columns (128, or 64 where R is not a multiple of 128)
+    static constexpr int BK2 = R % 128 == 0 ? 128 : 64, KSL = R / BK2, CPR2 = BK2 / 8;
     static constexpr int slab2 = 128 * BK2 * 2;
-    static constexpr int NI2 = slab2 / 1024 / NW;             // 4
+    static constexpr int NI2 = slab2 / 1024 / NW;             // load instructions per wave per slab (4 or 2)
+    static constexpr int RPI2 = 64 / CPR2;                    // rows of a slab per load instruction (4 or 8)
     static constexpr int NS = BK2 / 16;                       // k16 steps per stage-2 slab
     static constexpr int NB = largest_divisor3(NS, 2);        // operand buffers of a wave in stage 2 (deeper rings measured slower)
     static constexpr int ypitch = 128 * 2 + 16;
@@ -83,9 +90,10 @@ struct Ch3Cfg {
     // the T tile sits above the first stage-2 slab slot, so that slab 0 of Q can arrive while T is in use
     static constexpr int a = NXB * xpart + 2 * ppart, b = slab2 + ttile, c = 2 * slab2 + 2 * ytile;
     static constexpr int lds_bytes = a > b ? (a > c ? a : c) : (b > c ? b : c);
-    static_assert(R % 128 == 0 && NI1X == 8 && (NXB & (NXB - 1)) == 0 && LX <= 3 && NI2 == 4, "slab shape");
+    static_assert(R % 64 == 0 && R % BK2 == 0 && KSL >= 2 && NI1X == 8 && (NXB & (NXB - 1)) == 0 && LX <= 3, "slab shape");
+    static_assert(CB * CG * 32 == R && (CPR2 == 16 || CPR2 == 8) && NI2 * NW * RPI2 == 128, "wave split");
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
-    static_assert(NS == 8, "a staged tile leaves in eight pieces, one per step");
+    static_assert(NS >= 2 && NS <= 9, "a staged tile leaves in eight pieces spread over the NS - 1 steps of a slab");
 };
 
 struct Ch3Ptrs {
@@ -173,12 +181,14 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
         else if (n == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     };
-    // Stage 2: an instruction covers 4 rows of 16 chunks; rows 4 (wave + 8u) + lane / 16; logical chunk
-    // c ^ (r & 15).  The descriptor covers the rows of the tile that exist: the rest arrive as zeros
-    // and feed output columns that are never stored.
-    const int r4 = lane >> 4;
-    const int chunk2 = (lane & 15) ^ ((4 * wave + r4) & 15);
-    const int v2 = ((4 * wave + r4) * R + chunk2 * 8) * 2;
+    // Stage 2: an instruction covers RPI2 rows of CPR2 chunks: rows RPI2 (wave + 8u) + lane / CPR2; logical
+    // chunk c ^ (r & 15) for 16-chunk rows, c ^ ((r >> 1) & 7) for 8-chunk rows (the same for all
+    // instructions of a wave).  The descriptor covers the rows of the tile that exist: the rest
+    // arrive as zeros and feed output columns that are never stored.
+    const int r4 = lane / L::CPR2;
+    const int row2 = L::RPI2 * wave + r4;
+    const int chunk2 = (lane % L::CPR2) ^ (L::CPR2 == 16 ? (row2 & 15) : ((row2 >> 1) & 7));
+    const int v2 = (row2 * R + chunk2 * 8) * 2;
     auto issue2 = [&](int s) {
         const int t = tile_of(s / KSL);
         const int rows = q - t * 128 < 128 ? q - t * 128 : 128;
@@ -186,19 +196,21 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
         unsigned char* dst = lds + (s & 1) * L::slab2 + wave * 1024;
         const int so = (s % KSL) * (BK2 * 2);
 #pragma unroll
-        for (int u = 0; u < L::NI2; ++u) dma16(qres, dst + u * 8192, v2 + u * 32 * R * 2, so);
+        for (int u = 0; u < L::NI2; ++u) dma16(qres, dst + u * 8192, v2 + u * (8 * L::RPI2) * R * 2, so);
     };
 
     // ------------------------------------------------------------------ stage 1
-    const int rh = wave >> 2, cq = wave & 3;            // rows 64 rh .., columns (R / 4) cq ..
-    f32x16 acc1[2][CB];
+    constexpr int RA = L::RA;
+    const int rg = RA == 2 ? wave >> 2 : wave >> 1;     // rows 32 RA rg ..
+    const int cq = RA == 2 ? wave & 3 : wave & 1;       // columns 32 CB cq ..
+    f32x16 acc1[RA][CB];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < RA; ++a)
 #pragma unroll
         for (int b = 0; b < CB; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc1[a][b][v] = 0.0f;
-    struct Ops1 { u32x4 xf[2]; u32x4 pf[CB]; };
+    struct Ops1 { u32x4 xf[RA]; u32x4 pf[CB]; };
     constexpr int SPW = BK1 / 16;                       // 4 steps per slab
     constexpr int NB1 = 2;                              // operand buffers (divides SPW: the held step sits in the last one)
     Ops1 ob[NB1];
@@ -207,8 +219,8 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
         const unsigned char* pb = lds + L::NXB * L::xpart + (s & 1) * L::ppart;
         const int qc = 2 * kk + lh;                     // logical chunk of this lane's 8 values
 #pragma unroll
-        for (int a = 0; a < 2; ++a) {
-            const int row = 64 * rh + 32 * a + lj;
+        for (int a = 0; a < RA; ++a) {
+            const int row = 32 * (RA * rg + a) + lj;
             o.xf[a] = *reinterpret_cast<const u32x4*>(xb + row * (BK1 * 2) + ((qc ^ ((row >> 1) & 7)) * 16));
         }
 #pragma unroll
@@ -219,7 +231,7 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
     };
     auto mma1 = [&](const Ops1& o) {
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < RA; ++a)
 #pragma unroll
             for (int b = 0; b < CB; ++b) acc1[a][b] = mfma3(o.pf[b], o.xf[a], acc1[a][b]);
     };
@@ -259,16 +271,16 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
     }
     mma1(ob[NB1 - 1]);
     // ------------------------------------------------------------------ T tile (bf16) to LDS
-    // lane holds T[64 rh + 32a + lj][32 (cq CB + b) + 8g + 4 lh + (0..3)] in acc1[a][b][4g .. 4g+3]
+    // lane holds T[32 (RA rg + a) + lj][32 (cq CB + b) + 8g + 4 lh + (0..3)] in acc1[a][b][4g .. 4g+3]
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < RA; ++a)
 #pragma unroll
         for (int b = 0; b < CB; ++b)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 u32x2 o = {pack2_bf16(acc1[a][b][4 * g + 0], acc1[a][b][4 * g + 1]),
                            pack2_bf16(acc1[a][b][4 * g + 2], acc1[a][b][4 * g + 3])};
-                *reinterpret_cast<u32x2*>(ttile + (64 * rh + 32 * a + lj) * L::tpitch +
+                *reinterpret_cast<u32x2*>(ttile + (32 * (RA * rg + a) + lj) * L::tpitch +
                                           (32 * (cq * CB + b) + 8 * g + 4 * lh) * 2) = o;
             }
     if (Yout != nullptr) issue2(0);                     // slot 0 lies below the T tile
@@ -293,8 +305,9 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
     const rsrc_t yres = make_rsrc(Yout + row0 * q, rows_valid * q * 2);
     wait_loads3();
     wg_barrier3();                                      // T tile consumed; Q slab 0 is in slot 0
-    // address of step kk = address of step 0 with kk << 5 XORed in (16 chunks per row, chunk 2 kk + lh)
-    const int qaddr0 = (qrow0 + lj) * (BK2 * 2) + ((lh ^ ((qrow0 + lj) & 15)) * 16);
+    // address of step kk = address of step 0 with kk << 5 XORed in (chunk 2 kk + lh of 16 or 8 per row)
+    const int qsw = L::CPR2 == 16 ? ((qrow0 + lj) & 15) : (((qrow0 + lj) >> 1) & 7);
+    const int qaddr0 = (qrow0 + lj) * (BK2 * 2) + ((lh ^ qsw) * 16);
     struct Ops2 { u32x4 qf[2]; };
     auto read2 = [&](Ops2& dst, int s, int kk) {
 #pragma unroll
@@ -380,10 +393,10 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
                 __builtin_amdgcn_sched_barrier(0);
                 if (kk + NB < NS) read2(ring[kk % NB], s, kk + NB);
                 if (stage_now) {
-                    stage_piece(t - 1, kk);
-                    if (kk + 2 == NS) stage_piece(t - 1, kk + 1);
+#pragma unroll
+                    for (int i = kk * 8 / (NS - 1); i < (kk + 1) * 8 / (NS - 1); ++i) stage_piece(t - 1, i);
                 }
-                if (kk == 1 && flush_now) {
+                if (kk == (NS > 2 ? 1 : 0) && flush_now) {
                     flush_store(flushed);
                     ++flushed;
                 }
@@ -450,9 +463,9 @@ hipError_t launch_chain3_r(const Ch3Ptrs& ptrs, int G, bool second_stage, int64_
 bool chain3_supports(int R, int p, int q) {
     if (p % 64 != 0 || p < 64 || q < 64 || q % 64 != 0 || p > (1 << 20) || q > (1 << 20)) return false;
 #ifdef ABT_NO_CHAIN3_384
-    return R == 256;
+    return R == 192 || R == 256;
 #else
-    return R == 256 || R == 384;
+    return R == 192 || R == 256 || R == 384;
 #endif
 }
 
@@ -468,6 +481,7 @@ hipError_t launch_chain3_bf16(const ChainProblem* problems, int G, int64_t M, in
     }
     if (second_stage && first_stage_only) return hipErrorInvalidValue;
     switch (R) {
+        case 192: return launch_chain3_r<192>(t, G, second_stage, M, p, q, parts, s);
         case 256: return launch_chain3_r<256>(t, G, second_stage, M, p, q, parts, s);
         case 384: return launch_chain3_r<384>(t, G, second_stage, M, p, q, parts, s);
         default: return hipErrorInvalidValue;
