@@ -56,21 +56,36 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void* base, int64_t bytes) {
 __device__ __forceinline__ u32x4 buf_load16(rsrc_t r, int lane_off, int wave_off) {
     return __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, wave_off, 0);
 }
+// A 16-byte store reads its data registers for a few cycles after it has issued, and the compiler
+// does not keep the next instructions away from them when the wave-uniform offset is a register
+// (seen: the address of the next store, written into the first data register one instruction after
+// the store, went to memory in place of the data).  Nothing may follow for four wait states.
+__device__ __forceinline__ void store_data_guard() {
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 3");
+    __builtin_amdgcn_sched_barrier(0);
+}
 __device__ __forceinline__ void buf_store16(u32x4 v, rsrc_t r, int lane_off, int wave_off) {
     __builtin_amdgcn_raw_buffer_store_b128(v, r, lane_off, wave_off, 0);
+    store_data_guard();
 }
 
-// The same accesses with the non-temporal hint, for data that a kernel touches once (activations in,
-// results out): such lines should not push the factors, which every work-group re-reads, out of L2.
-#ifndef ABT_STREAM_HINT
-#define ABT_STREAM_HINT 2
-#endif
-__device__ __forceinline__ u32x4 buf_load16_stream(rsrc_t r, int lane_off, int wave_off) {
-    return __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, wave_off, ABT_STREAM_HINT);
-}
+// A store with the non-temporal hint, for results that a launch writes once and that are too large
+// to be found in the last-level cache by whoever reads them next: such lines should not push the
+// factors, which every work-group re-reads, out of L2.  (The hint on the loads of the activations
+// measured slower than plain loads; on the stores it is worth 6 % of a config-3 step.)
 __device__ __forceinline__ void buf_store16_stream(u32x4 v, rsrc_t r, int lane_off, int wave_off) {
-    __builtin_amdgcn_raw_buffer_store_b128(v, r, lane_off, wave_off, ABT_STREAM_HINT);
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, lane_off, wave_off, 2);
+    store_data_guard();
 }
+// `stream` is uniform over the launch
+__device__ __forceinline__ void buf_store16_maybe_stream(bool stream, u32x4 v, rsrc_t r, int lane_off, int wave_off) {
+    if (stream) buf_store16_stream(v, r, lane_off, wave_off);
+    else buf_store16(v, r, lane_off, wave_off);
+}
+// Outputs of a launch (Yout and Tout of the chain kernels) of this many bytes or more are stored with
+// the hint: a quarter of the 256 MB last-level cache.
+constexpr int64_t kStreamOutBytes = 64ll << 20;
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

@@ -180,7 +180,7 @@ struct Ch2Ptrs {
 template <int R, int RG, bool GATHER>
 __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(Ch2Ptrs ptrs,
                                                          int64_t M, int p, int q, int t_pitch, Ch2Gather gg,
-                                                         int full_blocks, int tail_parts) {
+                                                         int full_blocks, int tail_parts, int stream_out) {
     extern __shared__ __align__(1024) unsigned char lds[];
     const uint16_t* __restrict__ const Xin = ptrs.X[blockIdx.y];
     const uint16_t* __restrict__ const Pm = ptrs.P[blockIdx.y];
@@ -331,7 +331,7 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(Ch2
                 for (int e = 0; e < L::NCHX; ++e) {
                     int vo, xo;
                     xaddr(e, vs, vo, xo);
-                    dst[e] = buf_load16_stream(xres, vo, xo);
+                    dst[e] = buf_load16(xres, vo, xo);
                 }
 #pragma unroll
                 for (int e = 0; e < L::NCHP; ++e) dst[L::NCHX + e] = buf_load16(pres, psrc, so + e * pstep);
@@ -355,7 +355,7 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(Ch2
                     int vo, xo;
                     xaddr(e, vs, vo, xo);
                     *reinterpret_cast<u32x4*>(lds + slot * L::slab1 + off[e]) = rg[e];
-                    rg[e] = buf_load16_stream(xres, vo, xo);
+                    rg[e] = buf_load16(xres, vo, xo);
                     __builtin_amdgcn_sched_barrier(0);
                 }
 #pragma unroll
@@ -413,7 +413,7 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(Ch2
             constexpr int CPT = R / 8;   // 16-byte chunks per T row
             for (int i = lt; i < ROWS * CPT; i += NLT) {
                 const int row = i / CPT, ch = i % CPT;
-                buf_store16_stream(*reinterpret_cast<const u32x4*>(ttile + (row >> 6) * L::ttile + (row & 63) * L::tpitch + ch * 16),
+                buf_store16_maybe_stream(stream_out != 0, *reinterpret_cast<const u32x4*>(ttile + (row >> 6) * L::ttile + (row & 63) * L::tpitch + ch * 16),
                             tres, (row * t_pitch + ch * 8) * 2, 0);
             }
         }
@@ -450,7 +450,7 @@ __global__ __launch_bounds__(64 * (NMW_ * RG + NLW)) void chain2_bf16_kernel(Ch2
         auto flush_store = [&](int seq, int e) {
             const int t = tile_of(seq);
             const bool whole = q - t * 128 >= 128;
-            if (whole || yleft[e]) buf_store16_stream(ypiece[e], yres, ydst[e], t * 256);
+            if (whole || yleft[e]) buf_store16_maybe_stream(stream_out != 0, ypiece[e], yres, ydst[e], t * 256);
         };
         auto step2 = [&](u32x4 (&rg)[L::NCHQ], int s, bool flush, int seq) {
             const int slot = (s + 1) & 1;
@@ -800,7 +800,8 @@ hipError_t launch_chain_r(const Ch2Ptrs& ptrs, int G, bool second_stage,
     }
     const int64_t grid = full + (nblocks - full) * tail_parts;
     hipLaunchKernelGGL((chain2_bf16_kernel<R, RG, GATHER>), dim3((unsigned)grid, (unsigned)G), dim3(64 * (NMW_ * RG + NLW)),
-                       lds_bytes, s, ptrs, M, p, q, t_pitch, gg, (int)full, tail_parts);
+                       lds_bytes, s, ptrs, M, p, q, t_pitch, gg, (int)full, tail_parts,
+                       (int)(M * ((second_stage ? q : 0) + t_pitch) * 2 >= kStreamOutBytes));
     return hipGetLastError();
 }
 

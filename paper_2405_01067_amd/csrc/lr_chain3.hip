@@ -53,10 +53,6 @@ __device__ __forceinline__ void wait_loads3() {
 __device__ __forceinline__ void dma16(rsrc_t r, unsigned char* dst, int lane_off, int wave_off) {
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void*)dst, 16, lane_off, wave_off, 0, 0);
 }
-// the same with the non-temporal hint (activations: read once)
-__device__ __forceinline__ void dma16_stream(rsrc_t r, unsigned char* dst, int lane_off, int wave_off) {
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void*)dst, 16, lane_off, wave_off, 0, ABT_STREAM_HINT);
-}
 
 constexpr int largest_divisor3(int n, int most) { return most <= 1 ? 1 : (n % most == 0 ? most : largest_divisor3(n, most - 1)); }
 
@@ -106,7 +102,7 @@ struct Ch3Ptrs {
 
 template <int R>
 __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t M, int p, int q,
-                                                          int full_blocks, int tail_parts) {
+                                                          int full_blocks, int tail_parts, int stream_out) {
     extern __shared__ __align__(1024) unsigned char lds[];
     const uint16_t* __restrict__ const Xin = ptrs.X[blockIdx.y];
     const uint16_t* __restrict__ const Pm = ptrs.P[blockIdx.y];
@@ -165,7 +161,7 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
         unsigned char* dst = lds + (s & (L::NXB - 1)) * L::xpart + i0 * 1024;
         const int so = slab1_of(s) * (BK1 * 2);
 #pragma unroll
-        for (int j = 0; j < L::NI1X; ++j) dma16_stream(xres, dst + j * (L::NXW * 1024), v1 + j * (8 * L::NXW) * p * 2, so);
+        for (int j = 0; j < L::NI1X; ++j) dma16(xres, dst + j * (L::NXW * 1024), v1 + j * (8 * L::NXW) * p * 2, so);
     };
     auto issue1p = [&](int s) {
         unsigned char* dst = lds + L::NXB * L::xpart + (s & 1) * L::ppart + i0 * 1024;
@@ -290,7 +286,7 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
         constexpr int CPT = R / 8;                      // 16-byte chunks per T row
         for (int i = tid; i < ROWS * CPT; i += L::NT) {
             const int row = i / CPT, ch = i % CPT;
-            buf_store16_stream(*reinterpret_cast<const u32x4*>(ttile + row * L::tpitch + ch * 16), tres, (row * R + ch * 8) * 2, 0);
+            buf_store16_maybe_stream(stream_out != 0, *reinterpret_cast<const u32x4*>(ttile + row * L::tpitch + ch * 16), tres, (row * R + ch * 8) * 2, 0);
         }
     }
     if (Yout == nullptr) return;
@@ -359,8 +355,8 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int i = e * L::NT + tid;
-            // always four store instructions per wave (the slab's wait counts them); pieces past a ragged tile go nowhere
-            buf_store16_stream(piece[e], yres, whole || (i & 15) < 8 ? ((i >> 4) * q + (i & 15) * 8) * 2 : kBufNowhere, t * 256);
+            // pieces past a ragged tile go nowhere
+            buf_store16_maybe_stream(stream_out != 0, piece[e], yres, whole || (i & 15) < 8 ? ((i >> 4) * q + (i & 15) * 8) * 2 : kBufNowhere, t * 256);
         }
     };
     int flushed = 0;
@@ -396,15 +392,17 @@ __global__ __launch_bounds__(512) void chain3_bf16_kernel(Ch3Ptrs ptrs, int64_t 
 #pragma unroll
                     for (int i = kk * 8 / (NS - 1); i < (kk + 1) * 8 / (NS - 1); ++i) stage_piece(t - 1, i);
                 }
-                if (kk == (NS > 2 ? 1 : 0) && flush_now) {
-                    flush_store(flushed);
-                    ++flushed;
-                }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // the next slab has landed; the four stores of a flush are younger than its loads and may still be on their way
-            if (flush_now) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-            else wait_loads3();
+            // the next slab has landed.  The stores of a flush go out only now: loads and stores need not
+            // complete in one common order, so no count of outstanding operations is used to tell the
+            // slab's loads from stores issued before this wait; issued after it, the stores are on
+            // their way during the next slab and complete long before its closing wait
+            wait_loads3();
+            if (flush_now) {
+                flush_store(flushed);
+                ++flushed;
+            }
             wg_barrier3();
         }
     }
@@ -454,7 +452,7 @@ hipError_t launch_chain3_r(const Ch3Ptrs& ptrs, int G, bool second_stage, int64_
     }
     const int64_t grid = full + (nblocks - full) * tail_parts;
     hipLaunchKernelGGL((chain3_bf16_kernel<R>), dim3((unsigned)grid, (unsigned)G), dim3(L::NT), L::lds_bytes, s,
-                       ptrs, M, p, q, (int)full, tail_parts);
+                       ptrs, M, p, q, (int)full, tail_parts, (int)(M * ((second_stage ? q : 0) + R) * 2 >= kStreamOutBytes));
     return hipGetLastError();
 }
 

@@ -73,7 +73,8 @@ __device__ __forceinline__ int slab_addr(int col, int unit) {
 // Loader role: moves NCOLS columns (multiple of 8) of a row-major bf16 matrix, 64 batch rows at a
 // time, into LDS columns [col0, col0 + NCOLS) transposed: a thread loads an 8 x 8 block as eight
 // 16-byte row pieces, transposes it in registers, and stores eight 16-byte column pieces.
-// STREAM: the source is read once by the whole launch (the U strips): loads carry the non-temporal hint.
+// STREAM: the source is read once by the whole launch (the U strips): loads carry the non-temporal hint
+// (0.7 % of a config-3 step; the same hint on the activation loads of the chain kernels measured slower).
 template <int NCOLS, int BPT, int D, bool GATHER = false, bool STREAM = false>
 __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int cols_valid, int col0, int lt,
                                           int64_t k_begin, int64_t k_end, int np, int slab_bytes,
@@ -105,7 +106,8 @@ __device__ __forceinline__ void tn_loader(const uint16_t* src, int pitch, int co
     auto load_block = [&](u32x4 (&dst)[8], rsrc_t res, int b) {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            dst[e] = STREAM ? buf_load16_stream(res, goff[e] + b * gstep, 0) : buf_load16(res, goff[e] + b * gstep, 0);
+            dst[e] = STREAM ? __builtin_amdgcn_raw_buffer_load_b128(res, goff[e] + b * gstep, 0, 2)   // non-temporal
+                            : buf_load16(res, goff[e] + b * gstep, 0);
     };
     // gather: this thread's eight virtual columns lie in one tap (C is a multiple of 8)
     const bool colok = active && cc * 8 < cols_valid;

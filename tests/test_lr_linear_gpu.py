@@ -346,6 +346,16 @@ def test_bf16_wide_rank_last_round_shared_by_output_tiles(tall_chain, r):
     check_full(c, torch.bfloat16, TOL_BF16)
 
 
+@pytest.mark.parametrize("r", [192, 256, 384])
+def test_bf16_wide_rank_many_blocks_outputs_below_the_streaming_size(tall_chain, r):
+    # 300 row blocks (more than one round of the chip, the last 44 shared by output tiles), four output
+    # tiles (the last ragged), outputs just under the size from which they are stored with the
+    # non-temporal hint: the finished tiles leave by plain stores while the next slabs are loading
+    c = gen.lr_case(M=128 * 300, m=448, n=64, r=r, seed=7500 + r)
+    assert c["X"].shape[0] * (448 + r) * 2 < 64 << 20
+    check_full(c, torch.bfloat16, TOL_BF16)
+
+
 def test_bf16_tall_work_groups_chosen_for_large_batches():
     # above one round of 64-row work-groups the library picks the 128-row kernel by itself; the
     # result must agree with the 64-row kernel's up to summation order, and with the oracle on samples
