@@ -34,9 +34,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 CACHE_BYTES = 256 << 20     # last-level cache: a rotated working set must exceed it
 # HBM bytes of one launch of the dominant kernel (forward chain of fc1 at r = 384, M = 50432) from two
 # rocprofv3 --pmc runs of `bench.py --only-launch fc1_r384 --pmc-copy` (profiles/chain_fwd_pmc_counters.txt,
-# second table): FETCH_SIZE 49652.9 KiB x 2.00 (the factor that makes a plain 256 MiB copy read 256 MiB)
-# + WRITE_SIZE 340458.8 KiB x 1.00.  A stored measurement: re-collect it when the kernel changes.
-DOMINANT_TRAFFIC_BYTES = int((49652.9 * 2.0 + 340458.8) * 1024)
+# second table): FETCH_SIZE 58308.8 KiB x 2.00 (the factor that makes a plain 256 MiB copy read 256 MiB)
+# + WRITE_SIZE 340459.5 KiB x 1.00.  A stored measurement: re-collect it when the kernel changes.
+DOMINANT_TRAFFIC_BYTES = int((58308.8 * 2.0 + 340459.5) * 1024)
 
 
 def main():
