@@ -59,10 +59,11 @@ __device__ __forceinline__ u32x4 buf_load16(rsrc_t r, int lane_off, int wave_off
 // A 16-byte store reads its data registers for a few cycles after it has issued, and the compiler
 // does not keep the next instructions away from them when the wave-uniform offset is a register
 // (seen: the address of the next store, written into the first data register one instruction after
-// the store, went to memory in place of the data).  Nothing may follow for four wait states.
+// the store, went to memory in place of the data).  Nothing may follow for eight wait states: 64 lanes
+// of 16 bytes leave the register file at 64 bytes per cycle.
 __device__ __forceinline__ void store_data_guard() {
     __builtin_amdgcn_sched_barrier(0);
-    asm volatile("s_nop 3");
+    asm volatile("s_nop 7");
     __builtin_amdgcn_sched_barrier(0);
 }
 __device__ __forceinline__ void buf_store16(u32x4 v, rsrc_t r, int lane_off, int wave_off) {
